@@ -1,0 +1,28 @@
+"""CPU oracle for the resilient ring all-reduce hot path.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg.  The product package never imports it and it
+never imports the product package.
+"""
+from .r2_oracle import (  # noqa: F401
+    BF16,
+    F32,
+    OP_COPY,
+    OP_SUM,
+    PHASE_AG,
+    PHASE_AR,
+    PHASE_RS,
+    NoHealthyChannel,
+    OracleError,
+    bf16_to_f32,
+    build,
+    expected,
+    f32_to_bf16,
+    num_steps,
+    num_transmissions,
+    partition,
+    reduce_copy,
+    ring_sim,
+    set_threads,
+    threads,
+)
