@@ -1,0 +1,192 @@
+/*
+ * r2ccl.h -- C ABI of the MI355X-native hot path of a resilient ring all-reduce.
+ *
+ * One rank's share of a chunked ring all-reduce as described in the R2CCL paper:
+ *   (a) partition each chunk over the server's NIC channels in proportion to their
+ *       bandwidth, leaving failed channels empty, and partition again whenever the
+ *       channel state changes mid-collective (Sec. 2.1 multi-channel partition;
+ *       Sec. 5.1 R2CCL-Balance and "Overhead Analysis"; Sec. 4.3 chunk-granular
+ *       resume; Sec. 4.2 recovery by re-probing);
+ *   (b) the fused reduce-copy that adds the chunk arriving from the ring predecessor
+ *       into the local buffer and writes the result into the per-channel send staging
+ *       buffers (Sec. 2.1 "persistent GPU kernels over precomputed channels";
+ *       Sec. 4.3 Technique II, NIC-registered send buffers);
+ *   (c) the ring schedule, reduce-scatter followed by all-gather (Sec. 5.2), run over
+ *       R simulated ranks whose buffers all live in one GPU's memory.
+ *
+ * Conventions
+ *   - Every function returns an R2_* code (0 = success); nothing throws or aborts.
+ *   - "device" pointers are HIP device memory of the current device, "host" pointers
+ *     are ordinary process memory.  The caller owns every buffer.  Unless a function
+ *     says otherwise the library allocates nothing.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on it and return; r2_partition alone waits for its result.
+ *   - Data buffers (rank buffers, stage buffers) must be 16-byte aligned.
+ *   - Argument checks that need no device access happen before any HIP call, so a
+ *     bad call returns R2_ERR_INVALID even on a machine without a GPU.
+ */
+#ifndef R2CCL_H
+#define R2CCL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    R2_OK = 0,
+    R2_ERR_INVALID = -1,            /* null pointer, zero or too many channels/ranks, bad alignment,
+                                       size not a whole number of elements/chunks, bad enum, bad table */
+    R2_ERR_NO_HEALTHY_CHANNEL = -2, /* every channel failed or has zero bandwidth (Appendix C: at
+                                       least one healthy NIC must remain)                           */
+    R2_ERR_OVERFLOW = -3,           /* a size computation does not fit 64 bits                       */
+    R2_ERR_CAPACITY = -4,           /* a slice exceeds its stage buffer, or the workspace is too small */
+    R2_ERR_DEVICE = -5              /* the HIP runtime reported an error                             */
+};
+
+#define R2_MAX_CHANNELS 64 /* one wavefront lane and one mask bit per channel */
+#define R2_MAX_RANKS 64
+
+typedef enum { R2_F32 = 0, R2_BF16 = 1 } r2_dtype;
+enum { R2_OP_SUM = 0, R2_OP_COPY = 1 };
+enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2 }; /* both = all-reduce */
+
+/* Static, human-readable text for a return code. */
+const char *r2_strerror(int code);
+
+/* ---------------------------------------------------------------------------------------------
+ * (a) Channel partition -- Sec. 5.1, paragraph R2CCL-Balance.
+ *
+ * A chunk of `bytes` bytes is cut into n_channels consecutive slices, slice c = bytes
+ * [offsets[c], offsets[c+1]).  With e[c] = 0 for a failed channel (bit c of fail_mask set) and
+ * weights[c] otherwise, P[c] the sum of e before c, W the sum of all e and U = floor(bytes/align):
+ *     offsets[c] = align * floor(U * P[c] / W)   while P[c] < W,
+ *     offsets[c] = bytes                         once P[c] == W,        offsets[C] = bytes.
+ * Hence failed or zero-bandwidth channels get nothing, healthy ones get their proportional share to
+ * within one alignment unit, and the sub-unit tail goes to the last healthy channel.  The arithmetic
+ * is exact for any uint32 weights and any 64-bit byte count.  align may be any value >= 1 here; the
+ * data-moving calls below additionally need tables cut at multiples of 16 bytes.
+ * --------------------------------------------------------------------------------------------- */
+
+/* n_problems independent partitions on the device, one wavefront each, asynchronous.
+ *   weights   device [n_problems][n_channels]   bandwidth in integer units (e.g. MB/s)
+ *   fail_mask device [n_problems]
+ *   bytes     device [n_problems]
+ *   offsets   device [n_problems][n_channels+1]  out
+ *   status    device [n_problems]                out, R2_OK or R2_ERR_NO_HEALTHY_CHANNEL (then the
+ *                                                problem's offsets are all zero); may be NULL
+ * n_problems == 0 is a no-op. */
+int r2_partition_device(const uint32_t *weights, const uint64_t *fail_mask, const uint64_t *bytes,
+                        uint32_t n_channels, uint32_t align, uint32_t n_problems,
+                        uint64_t *offsets, int32_t *status, void *stream);
+
+/* One partition with HOST pointers: weights[n_channels] in, offsets[n_channels+1] out.  Runs the
+ * same device code, on the default stream, and waits for it.  Convenience call: it allocates and
+ * frees a few hundred bytes of device memory. */
+int r2_partition(const uint32_t *weights, uint64_t fail_mask, uint32_t n_channels, uint64_t bytes,
+                 uint32_t align, uint64_t *offsets);
+
+/* ---------------------------------------------------------------------------------------------
+ * (b) Fused reduce-copy on one chunk -- Sec. 2.1 (collective kernels over channels), Sec. 4.3
+ *     Technique II (send/receive staging buffers).
+ *
+ * `incoming` is the chunk the ring predecessor staged: the concatenation over c of the first
+ * in_offsets[c+1]-in_offsets[c] bytes of in_stage[c] (each slice is packed at offset 0 of its
+ * channel's buffer).  Then
+ *     in_stage == NULL              : v = local                 (copy-send; op is ignored)
+ *     op == R2_OP_SUM               : v = incoming + local      (fp32 add; bf16 is widened to fp32,
+ *                                                                added, rounded to nearest even)
+ *     op == R2_OP_COPY              : v = incoming
+ *     in_stage != NULL              : local <- v
+ *     out_stage != NULL             : v is cut by out_offsets and slice c written to out_stage[c]+0
+ * in_stage and out_stage may not both be NULL.
+ *   local       device, `bytes` bytes (a whole number of elements), 16-byte aligned for full speed;
+ *               an address that is only element-aligned is handled one element at a time
+ *   in_stage    HOST array of n_channels device pointers (copied at call time), each 16-byte aligned
+ *               and `stage_capacity` bytes long; likewise out_stage
+ *   in_offsets  DEVICE table of n_channels+1 entries, as written by r2_partition_device; likewise
+ *               out_offsets.  The tables are read by the kernel, so they may still be in flight on
+ *               `stream` when this is called
+ *   status      device int32, optional.  The kernel checks both tables (start at 0, end at `bytes`,
+ *               non-decreasing, interior cuts multiples of 16, every slice <= stage_capacity); on a
+ *               bad table it moves no data and stores R2_ERR_INVALID or R2_ERR_CAPACITY there.
+ *               It never writes R2_OK: clear it beforehand.
+ * local, the in_stage buffers and the out_stage buffers must not overlap. */
+int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int op,
+                   const void *const *in_stage, const uint64_t *in_offsets,
+                   void *const *out_stage, const uint64_t *out_offsets,
+                   uint32_t n_channels, uint64_t stage_capacity, int32_t *status, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * (c) Ring all-reduce over R simulated ranks -- Sec. 5.2 (reduce-scatter then all-gather),
+ *     Sec. 5.1 (same channel state for the whole server), Sec. 4.3 (chunk-granular progress).
+ *
+ * Each rank buffer holds n_elems elements = n_slabs slabs of n_ranks ring chunks.  Per slab the
+ * ring takes J fused steps (2R-1 for all-reduce, R for a single phase); at step j rank r works on
+ * ring chunk (r - j) mod R [all-gather alone: (r + 1 - j) mod R]:
+ *     j = 0                     copy-send:        stage <- local
+ *     reduce-scatter steps      local <- incoming + local, staged onward
+ *     all-gather steps          local <- incoming,         staged onward
+ *     j = J-1                   local updated, nothing staged
+ * and `incoming` is what rank r-1 staged at step j-1.  A stage write at step j of slab l is
+ * transmission t = l*(J-1) + j.  The channel state in force at t is the last epoch with
+ * t_start <= t; it decides the partition of that transmission, for all ranks alike, and the reader
+ * uses the writer's table.  A failure "at step k" is an epoch with t_start = k; a recovery is a
+ * later epoch with the bit cleared.  The result in the rank buffers does not depend on the epochs.
+ *
+ * One fused step of all ranks and all slabs is one kernel launch (slabs are independent).
+ * --------------------------------------------------------------------------------------------- */
+
+typedef struct {
+    uint64_t t_start;        /* first transmission index of this state; epochs[0].t_start == 0,
+                                strictly increasing                                             */
+    uint64_t fail_mask;      /* bit c set = channel c is down                                   */
+    const uint32_t *weights; /* HOST array of n_channels bandwidth weights                      */
+} r2_epoch;
+
+typedef struct {
+    uint32_t n_ranks;    /* R, 2..R2_MAX_RANKS                                                   */
+    uint32_t n_slabs;    /* S >= 1, R*S <= 65535                                                 */
+    uint32_t n_channels; /* C, 1..R2_MAX_CHANNELS                                                */
+    uint32_t align;      /* partition alignment in bytes, a multiple of 16                       */
+    uint64_t n_elems;    /* elements per rank, a multiple of R*S (0 is allowed: nothing to do)   */
+    int32_t dtype;       /* r2_dtype                                                             */
+    int32_t phases;      /* R2_PHASE_RS, R2_PHASE_AG or both                                     */
+} r2_sim_desc;
+
+/* Pure host arithmetic on a descriptor (0 if the descriptor is invalid). */
+uint32_t r2_sim_num_steps(const r2_sim_desc *desc);         /* J                                  */
+uint64_t r2_sim_num_transmissions(const r2_sim_desc *desc); /* S * (J-1) = rows of the tables     */
+uint64_t r2_sim_workspace_bytes(const r2_sim_desc *desc);
+uint64_t r2_sim_stage_offset(const r2_sim_desc *desc);      /* byte offset of the stage area      */
+uint64_t r2_sim_stage_capacity(const r2_sim_desc *desc);    /* bytes per channel buffer           */
+
+/* Workspace (device, 256-byte aligned, >= r2_sim_workspace_bytes) layout:
+ *   [0, ...)                 offsets tables  uint64 [S*(J-1)][C+1], row t = transmission t
+ *   [r2_sim_stage_offset)    stage buffers   [2 parities][R][S][C][r2_sim_stage_capacity bytes];
+ *                            the transmission of step j uses parity j & 1
+ * Stage memory is never initialised or cleared by the library. */
+
+/* Partition every transmission of the run: fills the tables (and, if not NULL, the device array
+ * offsets_log [S*(J-1)][C+1]) from the epoch list.  Epoch data travels as kernel arguments, so no
+ * host-to-device copy is made.  Returns R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if a state
+ * that is in force for some transmission has no healthy channel. */
+int r2_sim_prepare(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs,
+                   void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log, void *stream);
+
+/* Fused step j (0 <= j < J) of every rank and every slab: one launch.  rank_bufs is a HOST array of
+ * R device pointers.  Needs the tables of r2_sim_prepare and, for j > 0, the stage of step j-1. */
+int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step,
+                void *workspace, uint64_t workspace_bytes, void *stream);
+
+/* r2_sim_prepare followed by steps 0..J-1, in place on the rank buffers. */
+int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
+                          const r2_epoch *epochs, uint32_t n_epochs,
+                          void *workspace, uint64_t workspace_bytes,
+                          uint64_t *offsets_log, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* R2CCL_H */

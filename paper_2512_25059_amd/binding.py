@@ -1,0 +1,242 @@
+"""ctypes binding of ``libr2ccl.so`` (see ``include/r2ccl.h`` for the contract).
+
+Argument marshalling only.  torch is used for device memory and streams; a
+torch tensor stands for "device pointer + size".  Each wrapper has the name of
+the C entry point it calls and raises :class:`R2Error` on a non-zero code.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch  # imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libr2ccl.so")
+
+F32, BF16 = 0, 1
+OP_SUM, OP_COPY = 0, 1
+PHASE_RS, PHASE_AG = 1, 2
+PHASE_AR = PHASE_RS | PHASE_AG
+
+R2_OK = 0
+R2_ERR_INVALID = -1
+R2_ERR_NO_HEALTHY_CHANNEL = -2
+R2_ERR_OVERFLOW = -3
+R2_ERR_CAPACITY = -4
+R2_ERR_DEVICE = -5
+
+
+class R2Error(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {r2_strerror(code)} ({code})")
+        self.code = code
+
+
+class _Epoch(C.Structure):
+    _fields_ = [("t_start", C.c_uint64), ("fail_mask", C.c_uint64), ("weights", C.POINTER(C.c_uint32))]
+
+
+class _SimDesc(C.Structure):
+    _fields_ = [("n_ranks", C.c_uint32), ("n_slabs", C.c_uint32), ("n_channels", C.c_uint32),
+                ("align", C.c_uint32), ("n_elems", C.c_uint64), ("dtype", C.c_int32),
+                ("phases", C.c_int32)]
+
+
+@dataclass(frozen=True)
+class SimDesc:
+    n_ranks: int
+    n_slabs: int
+    n_channels: int
+    align: int
+    n_elems: int
+    dtype: int
+    phases: int
+
+    def c(self) -> _SimDesc:
+        return _SimDesc(self.n_ranks, self.n_slabs, self.n_channels, self.align, self.n_elems,
+                        self.dtype, self.phases)
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built library.  It is never built here: run ``__graft_entry__.build()`` (or
+    ``python -m paper_2512_25059_amd.build``) first."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2512_25059_amd.build`; "
+                           "there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
+    lib.r2_strerror.restype = C.c_char_p
+    lib.r2_strerror.argtypes = [i32]
+    lib.r2_partition.restype = i32
+    lib.r2_partition.argtypes = [vp, u64, u32, u64, u32, vp]
+    lib.r2_partition_device.restype = i32
+    lib.r2_partition_device.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp]
+    lib.r2_reduce_copy.restype = i32
+    lib.r2_reduce_copy.argtypes = [vp, u64, i32, i32, vp, vp, vp, vp, u32, u64, vp, vp]
+    pd = C.POINTER(_SimDesc)
+    lib.r2_sim_num_steps.restype = u32
+    lib.r2_sim_num_steps.argtypes = [pd]
+    for name in ("r2_sim_num_transmissions", "r2_sim_workspace_bytes", "r2_sim_stage_offset",
+                 "r2_sim_stage_capacity"):
+        getattr(lib, name).restype = u64
+        getattr(lib, name).argtypes = [pd]
+    lib.r2_sim_prepare.restype = i32
+    lib.r2_sim_prepare.argtypes = [pd, vp, u32, vp, u64, vp, vp]
+    lib.r2_sim_step.restype = i32
+    lib.r2_sim_step.argtypes = [pd, vp, u32, vp, u64, vp]
+    lib.r2_ring_allreduce_sim.restype = i32
+    lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != R2_OK:
+        raise R2Error(rc, what)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    return t.data_ptr() if isinstance(t, torch.Tensor) else int(t)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr_array(ts: Optional[Sequence]) -> Tuple[Optional[C.Array], Optional[int]]:
+    if ts is None:
+        return None, None
+    arr = (C.c_void_p * len(ts))(*[_ptr(t) for t in ts])
+    return arr, C.cast(arr, C.c_void_p).value
+
+
+def _epoch_array(epochs: Sequence[Tuple[int, int, Sequence[int]]]):
+    keep = []
+    arr = (_Epoch * max(len(epochs), 1))()
+    for i, (t0, mask, w) in enumerate(epochs):
+        wa = (C.c_uint32 * len(w))(*[int(x) for x in w])
+        keep.append(wa)
+        arr[i].t_start = int(t0)
+        arr[i].fail_mask = int(mask)
+        arr[i].weights = C.cast(wa, C.POINTER(C.c_uint32))
+    return arr, keep
+
+
+def r2_strerror(code: int) -> str:
+    return load_library().r2_strerror(int(code)).decode()
+
+
+def r2_partition(weights: Sequence[int], fail_mask: int, nbytes: int, align: int) -> List[int]:
+    """Host-pointer convenience call: returns the C+1 offsets."""
+    n = len(weights)
+    w = (C.c_uint32 * max(n, 1))(*[int(x) for x in weights])
+    off = (C.c_uint64 * (n + 1))()
+    rc = load_library().r2_partition(C.cast(w, C.c_void_p), int(fail_mask), n, int(nbytes), int(align),
+                                     C.cast(off, C.c_void_p))
+    _check(rc, "r2_partition")
+    return list(off)
+
+
+def r2_partition_device(weights: torch.Tensor, fail_mask: torch.Tensor, nbytes: torch.Tensor,
+                        align: int, offsets: torch.Tensor, status: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    """weights [T, C] (4-byte ints), fail_mask [T], nbytes [T], offsets [T, C+1] (8-byte ints),
+    status [T] int32 or None; all on the device."""
+    T, n_channels = weights.shape
+    assert weights.element_size() == 4 and weights.is_contiguous()
+    assert fail_mask.element_size() == 8 and nbytes.element_size() == 8 and offsets.element_size() == 8
+    assert fail_mask.numel() == T and nbytes.numel() == T and offsets.numel() == T * (n_channels + 1)
+    assert status is None or (status.element_size() == 4 and status.numel() == T)
+    rc = load_library().r2_partition_device(_ptr(weights), _ptr(fail_mask), _ptr(nbytes), n_channels,
+                                            int(align), T, _ptr(offsets), _ptr(status), _stream(stream))
+    _check(rc, "r2_partition_device")
+
+
+def r2_reduce_copy(local: torch.Tensor, dtype: int, op: int,
+                   in_stage: Optional[Sequence[torch.Tensor]], in_offsets: Optional[torch.Tensor],
+                   out_stage: Optional[Sequence[torch.Tensor]], out_offsets: Optional[torch.Tensor],
+                   n_channels: int, stage_capacity: int, status: Optional[torch.Tensor] = None,
+                   stream=None, nbytes: Optional[int] = None) -> None:
+    if nbytes is None:
+        nbytes = local.numel() * local.element_size()
+    in_arr, in_p = _ptr_array(in_stage)
+    out_arr, out_p = _ptr_array(out_stage)
+    rc = load_library().r2_reduce_copy(_ptr(local), int(nbytes), int(dtype), int(op), in_p,
+                                       _ptr(in_offsets), out_p, _ptr(out_offsets), int(n_channels),
+                                       int(stage_capacity), _ptr(status), _stream(stream))
+    del in_arr, out_arr
+    _check(rc, "r2_reduce_copy")
+
+
+def r2_sim_num_steps(desc: SimDesc) -> int:
+    return int(load_library().r2_sim_num_steps(C.byref(desc.c())))
+
+
+def r2_sim_num_transmissions(desc: SimDesc) -> int:
+    return int(load_library().r2_sim_num_transmissions(C.byref(desc.c())))
+
+
+def r2_sim_workspace_bytes(desc: SimDesc) -> int:
+    return int(load_library().r2_sim_workspace_bytes(C.byref(desc.c())))
+
+
+def r2_sim_stage_offset(desc: SimDesc) -> int:
+    return int(load_library().r2_sim_stage_offset(C.byref(desc.c())))
+
+
+def r2_sim_stage_capacity(desc: SimDesc) -> int:
+    return int(load_library().r2_sim_stage_capacity(C.byref(desc.c())))
+
+
+def _ws(workspace, workspace_bytes):
+    if isinstance(workspace, torch.Tensor):
+        return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    return (int(workspace) if workspace is not None else None), int(workspace_bytes or 0)
+
+
+def r2_sim_prepare(desc: SimDesc, epochs, workspace, offsets_log: Optional[torch.Tensor] = None,
+                   stream=None, workspace_bytes: Optional[int] = None) -> None:
+    ep, keep = _epoch_array(epochs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_sim_prepare(C.byref(desc.c()), C.cast(ep, C.c_void_p), len(epochs), wp, wb,
+                                       _ptr(offsets_log), _stream(stream))
+    del keep
+    _check(rc, "r2_sim_prepare")
+
+
+def r2_sim_step(desc: SimDesc, rank_bufs: Sequence, step: int, workspace, stream=None,
+                workspace_bytes: Optional[int] = None) -> None:
+    arr, p = _ptr_array(rank_bufs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_sim_step(C.byref(desc.c()), p, int(step), wp, wb, _stream(stream))
+    del arr
+    _check(rc, "r2_sim_step")
+
+
+def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
+                          offsets_log: Optional[torch.Tensor] = None, stream=None,
+                          workspace_bytes: Optional[int] = None) -> None:
+    arr, p = _ptr_array(rank_bufs)
+    ep, keep = _epoch_array(epochs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_ring_allreduce_sim(C.byref(desc.c()), p, C.cast(ep, C.c_void_p), len(epochs),
+                                              wp, wb, _ptr(offsets_log), _stream(stream))
+    del arr, keep
+    _check(rc, "r2_ring_allreduce_sim")

@@ -1,0 +1,182 @@
+// Channel partition on the device: one wavefront per chunk to partition, one lane per channel.
+//
+// Follows the R2CCL paper, Sec. 5.1 (R2CCL-Balance): the data a server must move is spread over
+// its healthy NICs in proportion to their bandwidth, a failed NIC carries nothing, and the volume
+// itself is unchanged ("Overhead Analysis").  The rounding rule is stated in r2ccl.h.
+#include "r2_internal.h"
+
+namespace r2 {
+namespace {
+
+// floor(r * p / w) for a 128-bit product, by restoring division; needs r*p < w * 2^64.
+__device__ inline uint64_t div128(uint64_t hi, uint64_t lo, uint64_t w)
+{
+    uint64_t rem = hi, quo = 0;
+    for (int i = 63; i >= 0; --i) {
+        const uint64_t carry = rem >> 63;
+        rem = (rem << 1) | ((lo >> i) & 1u);
+        if (carry || rem >= w) {
+            rem -= w;
+            quo |= 1ull << i;
+        }
+    }
+    return quo;
+}
+
+// floor(U * P / W) without overflow, for P <= W, W > 0.  U = q*W + r gives q*P + floor(r*P/W);
+// q*P <= U fits, and r*P < W^2 is divided in 128 bits when it does not fit 64.
+__device__ inline uint64_t mul_div_floor(uint64_t U, uint64_t P, uint64_t W)
+{
+    const uint64_t q = U / W, r = U - q * W;
+    const uint64_t lo = r * P, hi = __umul64hi(r, P);
+    const uint64_t frac = hi == 0 ? lo / W : div128(hi, lo, W);
+    return q * P + frac;
+}
+
+// The whole wavefront partitions one chunk.  Lane c carries channel c's weight (lanes >= C carry
+// nothing).  The cumulative bandwidth in front of each channel is a wavefront-wide inclusive scan.
+__device__ inline void partition_wave(uint32_t weight, bool failed, uint32_t C, uint64_t bytes,
+                                      uint32_t align, uint64_t *row, uint64_t *row2, int32_t *status)
+{
+    const unsigned lane = threadIdx.x & (kWave - 1);
+    const uint64_t e = (lane < C && !failed) ? weight : 0;
+    uint64_t incl = e;
+#pragma unroll
+    for (unsigned d = 1; d < kWave; d <<= 1) {
+        const uint64_t up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+    }
+    const uint64_t W = __shfl(incl, kWave - 1, kWave);
+    const uint64_t P = incl - e;  // bandwidth of the channels before this one
+
+    uint64_t o;
+    if (W == 0) {
+        o = 0;
+    } else if (P == W) {
+        o = bytes;
+    } else {
+        o = (uint64_t)align * mul_div_floor(bytes / align, P, W);
+    }
+    if (lane < C) {
+        row[lane] = o;
+        if (row2) row2[lane] = o;
+    }
+    if (lane == 0) {
+        const uint64_t end = W == 0 ? 0 : bytes;
+        row[C] = end;
+        if (row2) row2[C] = end;
+        if (status) *status = W == 0 ? R2_ERR_NO_HEALTHY_CHANNEL : R2_OK;
+    }
+}
+
+constexpr unsigned kBlock = 256;  // four problems per workgroup
+constexpr unsigned kWavesPerBlock = kBlock / kWave;
+
+__global__ __launch_bounds__(kBlock) void partition_arrays_kernel(
+    const uint32_t *__restrict__ weights, const uint64_t *__restrict__ fail_mask,
+    const uint64_t *__restrict__ bytes, uint32_t C, uint32_t align, uint32_t n_problems,
+    uint64_t *__restrict__ offsets, int32_t *__restrict__ status)
+{
+    const uint64_t p = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (p >= n_problems) return;  // whole wavefront leaves together
+    const unsigned lane = threadIdx.x & (kWave - 1);
+    const uint32_t w = lane < C ? weights[p * C + lane] : 0;
+    const bool failed = (fail_mask[p] >> lane) & 1u;
+    partition_wave(w, failed, C, bytes[p], align, offsets + p * (C + 1), nullptr,
+                   status ? status + p : nullptr);
+}
+
+// Channel states travel by value in the kernel argument block: no host-to-device copy, no
+// allocation.  A batch holds as many epochs as fit.
+constexpr uint32_t kBatchEpochs = 32;
+constexpr uint32_t kBatchWeights = 640;
+
+struct EpochBatch {
+    uint64_t t_start[kBatchEpochs];
+    uint64_t fail_mask[kBatchEpochs];
+    uint32_t weights[kBatchWeights];  // [n][C]
+    uint32_t n;
+};
+
+__global__ __launch_bounds__(kBlock) void partition_epochs_kernel(
+    const EpochBatch batch, uint32_t C, uint32_t align, uint64_t bytes, uint64_t t_begin,
+    uint64_t t_end, uint64_t *__restrict__ tables, uint64_t *__restrict__ log)
+{
+    const uint64_t t = t_begin + (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (t >= t_end) return;  // whole wavefront leaves together
+    uint32_t i = 0;          // state in force at t: the last epoch that started at or before t
+    for (uint32_t k = 1; k < batch.n; ++k)
+        if (batch.t_start[k] <= t) i = k;
+    const unsigned lane = threadIdx.x & (kWave - 1);
+    const uint32_t w = lane < C ? batch.weights[i * C + lane] : 0;
+    const bool failed = (batch.fail_mask[i] >> lane) & 1u;
+    partition_wave(w, failed, C, bytes, align, tables + t * (C + 1),
+                   log ? log + t * (C + 1) : nullptr, nullptr);
+}
+
+}  // namespace
+
+int launch_partition_epochs(const r2_epoch *epochs, uint32_t n_epochs, uint32_t C, uint32_t align,
+                            uint64_t chunk_bytes, uint64_t n_tx, uint64_t *tables, uint64_t *log,
+                            hipStream_t stream)
+{
+    const uint32_t per_batch = kBatchWeights / C < kBatchEpochs ? kBatchWeights / C : kBatchEpochs;
+    for (uint32_t i0 = 0; i0 < n_epochs; i0 += per_batch) {
+        const uint32_t i1 = i0 + per_batch < n_epochs ? i0 + per_batch : n_epochs;
+        const uint64_t t_begin = epochs[i0].t_start;
+        if (t_begin >= n_tx) break;
+        uint64_t t_end = i1 < n_epochs ? epochs[i1].t_start : n_tx;
+        if (t_end > n_tx) t_end = n_tx;
+        EpochBatch b;
+        b.n = i1 - i0;
+        for (uint32_t k = 0; k < b.n; ++k) {
+            b.t_start[k] = epochs[i0 + k].t_start;
+            b.fail_mask[k] = epochs[i0 + k].fail_mask;
+            for (uint32_t c = 0; c < C; ++c) b.weights[k * C + c] = epochs[i0 + k].weights[c];
+        }
+        const uint64_t n = t_end - t_begin;
+        const uint64_t blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (blocks > 0x7fffffffull) return R2_ERR_OVERFLOW;
+        hipLaunchKernelGGL(partition_epochs_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, stream,
+                           b, C, align, chunk_bytes, t_begin, t_end, tables, log);
+        const int rc = hip_rc(hipGetLastError());
+        if (rc) return rc;
+    }
+    return R2_OK;
+}
+
+}  // namespace r2
+
+extern "C" int r2_partition_device(const uint32_t *weights, const uint64_t *fail_mask,
+                                   const uint64_t *bytes, uint32_t n_channels, uint32_t align,
+                                   uint32_t n_problems, uint64_t *offsets, int32_t *status,
+                                   void *stream)
+{
+    if (n_channels == 0 || n_channels > R2_MAX_CHANNELS || align == 0) return R2_ERR_INVALID;
+    if (n_problems == 0) return R2_OK;
+    if (!weights || !fail_mask || !bytes || !offsets) return R2_ERR_INVALID;
+    const unsigned blocks = (n_problems + r2::kWavesPerBlock - 1) / r2::kWavesPerBlock;
+    hipLaunchKernelGGL(r2::partition_arrays_kernel, dim3(blocks), dim3(r2::kBlock), 0,
+                       (hipStream_t)stream, weights, fail_mask, bytes, n_channels, align, n_problems,
+                       offsets, status);
+    return r2::hip_rc(hipGetLastError());
+}
+
+extern "C" int r2_partition(const uint32_t *weights, uint64_t fail_mask, uint32_t n_channels,
+                            uint64_t bytes, uint32_t align, uint64_t *offsets)
+{
+    if (!weights || !offsets || n_channels == 0 || n_channels > R2_MAX_CHANNELS || align == 0)
+        return R2_ERR_INVALID;
+    if (!r2::any_healthy(weights, fail_mask, n_channels)) {
+        for (uint32_t c = 0; c <= n_channels; ++c) offsets[c] = 0;
+        return R2_ERR_NO_HEALTHY_CHANNEL;
+    }
+    const size_t row = (size_t)(n_channels + 1) * sizeof(uint64_t);
+    uint64_t *d_row = nullptr;
+    if (hipMalloc((void **)&d_row, row) != hipSuccess) return R2_ERR_DEVICE;
+    const r2_epoch ep = {0, fail_mask, weights};
+    int rc = r2::launch_partition_epochs(&ep, 1, n_channels, align, bytes, 1, d_row, nullptr, nullptr);
+    if (rc == R2_OK) rc = r2::hip_rc(hipMemcpy(offsets, d_row, row, hipMemcpyDeviceToHost));
+    (void)hipFree(d_row);
+    return rc;
+}

@@ -1,0 +1,69 @@
+"""Helpers of the GPU parity tests: run a workload through the C ABI and through the oracle."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import torch
+
+import workloads as wl
+
+FILL = 0xA5
+
+
+def say(msg: str) -> None:
+    """Name the case before its GPU work starts, so a fault can be attributed."""
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def codes(r2, oracle, w: wl.Workload):
+    dt = r2.F32 if w.dtype == "f32" else r2.BF16
+    ph = {"ar": r2.PHASE_AR, "rs": r2.PHASE_RS, "ag": r2.PHASE_AG}[w.phases]
+    odt = oracle.F32 if w.dtype == "f32" else oracle.BF16
+    oph = {"ar": oracle.PHASE_AR, "rs": oracle.PHASE_RS, "ag": oracle.PHASE_AG}[w.phases]
+    return dt, ph, odt, oph
+
+
+def to_device(x: np.ndarray) -> torch.Tensor:
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda()
+    return torch.from_numpy(x).cuda()
+
+
+def to_host(t: torch.Tensor, like: np.ndarray) -> np.ndarray:
+    a = t.cpu().numpy()
+    return a.view(like.dtype)
+
+
+def run_gpu_sim(r2, w: wl.Workload, xs, fill_stage: bool = False, stepwise: bool = False):
+    """Returns (rank buffers as numpy, offsets log [T, C+1] uint64, workspace tensor, desc)."""
+    dt = r2.F32 if w.dtype == "f32" else r2.BF16
+    ph = {"ar": r2.PHASE_AR, "rs": r2.PHASE_RS, "ag": r2.PHASE_AG}[w.phases]
+    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, dt, ph)
+    bufs = [to_device(x) for x in xs]
+    ws_bytes = r2.r2_sim_workspace_bytes(desc)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    if fill_stage:
+        ws.fill_(FILL)
+    T = r2.r2_sim_num_transmissions(desc)
+    log = torch.full((max(T, 1), w.C + 1), -1, dtype=torch.int64, device="cuda")
+    if stepwise:
+        r2.r2_sim_prepare(desc, w.epochs, ws, log)
+        for j in range(r2.r2_sim_num_steps(desc)):
+            r2.r2_sim_step(desc, bufs, j, ws)
+    else:
+        r2.r2_ring_allreduce_sim(desc, bufs, w.epochs, ws, log)
+    torch.cuda.synchronize()
+    outs = [to_host(b, x) for b, x in zip(bufs, xs)]
+    return outs, log.cpu().numpy().view(np.uint64)[:T], ws, desc
+
+
+def expected_log(oracle, w: wl.Workload) -> np.ndarray:
+    T = w.S * w.transmissions_per_slab
+    rows = []
+    for t in range(T):
+        ep = [e for e in w.epochs if e[0] <= t][-1]
+        rows.append(oracle.partition(ep[2], ep[1], w.chunk_bytes, w.align))
+    return np.array(rows, dtype=np.uint64).reshape(T, w.C + 1)

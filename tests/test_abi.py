@@ -1,0 +1,143 @@
+"""The C ABI without a GPU: the library loads, exports what the header declares, and rejects bad
+arguments before any device work."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "r2ccl.h")
+
+
+@pytest.fixture(scope="module")
+def r2():
+    import paper_2512_25059_amd as pkg
+    from paper_2512_25059_amd import build as hip_build
+
+    if hip_build.is_stale():
+        hip_build.build()
+    pkg.load_library()
+    return pkg
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(r2_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(r2):
+    names = _declared_functions()
+    assert {"r2_partition", "r2_partition_device", "r2_reduce_copy", "r2_ring_allreduce_sim",
+            "r2_sim_prepare", "r2_sim_step", "r2_sim_workspace_bytes", "r2_strerror"} <= set(names)
+    lib = C.CDLL(r2.library_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in r2ccl.h but not exported"
+
+
+def test_strerror(r2):
+    assert r2.r2_strerror(0) == "success"
+    for code in (-1, -2, -3, -4, -5):
+        assert r2.r2_strerror(code) not in ("success", "unknown r2ccl error code")
+    assert r2.r2_strerror(-99) == "unknown r2ccl error code"
+
+
+def test_sim_shape_arithmetic(r2):
+    d = r2.SimDesc(n_ranks=8, n_slabs=1, n_channels=8, align=256, n_elems=1 << 26, dtype=r2.BF16,
+                   phases=r2.PHASE_AR)
+    assert r2.r2_sim_num_steps(d) == 15
+    assert r2.r2_sim_num_transmissions(d) == 14
+    cap = r2.r2_sim_stage_capacity(d)
+    assert cap == 16 << 20
+    off = r2.r2_sim_stage_offset(d)
+    assert off % 256 == 0 and off >= 14 * 9 * 8
+    assert r2.r2_sim_workspace_bytes(d) == off + 2 * 8 * 1 * 8 * cap
+    rs = r2.SimDesc(16, 4, 8, 256, 1 << 26, r2.F32, r2.PHASE_RS)
+    assert r2.r2_sim_num_steps(rs) == 16 and r2.r2_sim_num_transmissions(rs) == 60
+    assert r2.r2_sim_stage_capacity(rs) == 4 << 20
+
+
+@pytest.mark.parametrize("bad", [
+    dict(n_ranks=1), dict(n_ranks=65), dict(n_channels=0), dict(n_channels=65), dict(n_slabs=0),
+    dict(align=0), dict(align=8), dict(align=24), dict(n_elems=(1 << 20) + 1), dict(dtype=7),
+    dict(phases=0), dict(phases=4), dict(n_slabs=8192, n_elems=8192 * 8 * 4),
+])
+def test_invalid_descriptors(r2, bad):
+    base = dict(n_ranks=8, n_slabs=1, n_channels=8, align=256, n_elems=1 << 20, dtype=r2.BF16,
+                phases=r2.PHASE_AR)
+    base.update(bad)
+    d = r2.SimDesc(**base)
+    assert r2.r2_sim_num_steps(d) == 0
+    assert r2.r2_sim_workspace_bytes(d) == 0
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_ring_allreduce_sim(d, [256] * base["n_ranks"], [(0, 0, [1] * max(base["n_channels"], 1))],
+                                 4096, workspace_bytes=1 << 40)
+    assert e.value.code == -1
+
+
+def test_sim_rejects_bad_epochs_and_buffers_before_any_device_work(r2):
+    d = r2.SimDesc(4, 1, 4, 256, 4096, r2.F32, r2.PHASE_AR)
+    need = r2.r2_sim_workspace_bytes(d)
+    bufs = [4096 * (i + 1) for i in range(4)]  # fake but aligned addresses: never dereferenced
+    ok_ep = [(0, 0, [1, 1, 1, 1])]
+    cases = [
+        ([], -1),                                               # no epoch
+        ([(1, 0, [1, 1, 1, 1])], -1),                           # first epoch must start at 0
+        ([(0, 0, [1] * 4), (5, 0, [1] * 4), (5, 0, [1] * 4)], -1),  # not strictly increasing
+        ([(0, 0b1111, [1, 1, 1, 1])], -2),                      # all failed
+        ([(0, 0, [0, 0, 0, 0])], -2),                           # all zero bandwidth
+        ([(0, 0, [1] * 4), (3, 0b1111, [1] * 4)], -2),          # fails later, still before any launch
+    ]
+    for eps, code in cases:
+        with pytest.raises(r2.R2Error) as e:
+            r2.r2_ring_allreduce_sim(d, bufs, eps, 4096, workspace_bytes=need)
+        assert e.value.code == code, eps
+    # an epoch that starts after the last transmission is never in force
+    # (checked through the workspace error that comes next)
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_ring_allreduce_sim(d, bufs, [(0, 0, [1] * 4), (6, 0b1111, [1] * 4)], 4096, workspace_bytes=need - 1)
+    assert e.value.code == -4
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_ring_allreduce_sim(d, bufs, ok_ep, 4096 + 16, workspace_bytes=need)  # workspace not 256-aligned
+    assert e.value.code == -1
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_ring_allreduce_sim(d, [4096, 8192, 12288 + 4, 16384], ok_ep, 4096, workspace_bytes=need)
+    assert e.value.code == -1
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_sim_step(d, bufs, 7, 4096, workspace_bytes=need)  # J = 7: steps are 0..6
+    assert e.value.code == -1
+
+
+def test_reduce_copy_and_partition_argument_checks(r2):
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_reduce_copy(4096, r2.F32, r2.OP_SUM, None, None, None, None, 4, 1024, nbytes=64)
+    assert e.value.code == -1  # neither incoming nor outgoing
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_reduce_copy(4096, r2.F32, r2.OP_SUM, [256] * 4, 512, None, None, 4, 1024, nbytes=66)
+    assert e.value.code == -1  # not a whole number of fp32 elements
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_reduce_copy(4096, r2.F32, r2.OP_SUM, [256, 256, 264, 256], 512, None, None, 4, 1024, nbytes=64)
+    assert e.value.code == -1  # stage buffer not 16-byte aligned
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_reduce_copy(4096, r2.F32, 5, [256] * 4, 512, None, None, 4, 1024, nbytes=64)
+    assert e.value.code == -1
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_partition([1, 2, 3], 0b111, 4096, 256)
+    assert e.value.code == -2  # decided on the host, offsets zeroed
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_partition([1, 2, 3], 0, 4096, 0)
+    assert e.value.code == -1
+
+
+def test_product_package_does_not_import_the_oracle():
+    """The product path must not route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2512_25059_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".hpp", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+    for f in ("r2_oracle.c", "r2_oracle.py", "__init__.py"):
+        text = open(os.path.join(ROOT, "oracle", f)).read()
+        assert "paper_2512_25059_amd" not in text and "r2ccl" not in text, f

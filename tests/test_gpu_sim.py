@@ -1,0 +1,188 @@
+"""GPU parity: the ring all-reduce simulation through the C ABI vs the oracle.
+
+Small sizes: rank buffers, offsets log and the whole stage area are compared byte for byte with the
+step-by-step oracle.  Full sizes (the five benchmark configurations, in the launch configuration the
+benchmark times): every element of every rank buffer is compared with the oracle's plain-definition
+result, and the offsets log with the oracle's partition of the state in force.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import FILL, codes, expected_log, run_gpu_sim, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def r2():
+    import paper_2512_25059_amd as pkg
+
+    pkg.load_library()
+    assert torch.cuda.is_available()
+    return pkg
+
+
+def _stage_of(ws: torch.Tensor, r2, desc, w):
+    off = r2.r2_sim_stage_offset(desc)
+    cap = r2.r2_sim_stage_capacity(desc)
+    n = 2 * w.R * w.S * w.C * cap
+    return ws[off:off + n].cpu().numpy().reshape(2, w.R, w.S, w.C, cap), cap
+
+
+def _full_compare_small(r2, oracle, w, stepwise=False):
+    _, _, odt, oph = codes(r2, oracle, w)
+    xs = wl.make_inputs(w)
+    say(f"sim small {w.name} R={w.R} N={w.N} S={w.S} C={w.C} {w.dtype} {w.phases} stepwise={stepwise}")
+    outs, log, ws, desc = run_gpu_sim(r2, w, xs, fill_stage=True, stepwise=stepwise)
+    stage, cap = _stage_of(ws, r2, desc, w)
+    o_bufs = [x.copy() for x in xs]
+    o_log, o_stage = oracle.ring_sim(o_bufs, odt, w.S, w.C, w.align, list(w.epochs), oph, cap=cap, stage_fill=FILL)
+    for r in range(w.R):
+        assert outs[r].tobytes() == o_bufs[r].tobytes(), f"{w.name}: rank {r} buffer"
+    assert log.tolist() == o_log.tolist(), f"{w.name}: offsets log"
+    assert stage.tobytes() == o_stage.tobytes(), f"{w.name}: stage area"
+    want = oracle.expected(xs, odt, w.S, oph)
+    for r in range(w.R):
+        assert outs[r].tobytes() == want[r].tobytes()
+
+
+SMALL = [
+    lambda: wl.scaled(wl.cfg1(), 4 * 4096 * 3 + 4 * 8),        # several tiles + tail, fp32
+    lambda: wl.scaled(wl.cfg1(), 4 * 5),                        # chunk of 20 B: not a multiple of 16
+    lambda: wl.scaled(wl.cfg2(), 8 * 8192 * 2 + 8 * 24),        # bf16, failure at t=3
+    lambda: wl.scaled(wl.cfg2(), 8 * 3),                        # 6-byte chunks, element path only
+    lambda: wl.scaled(wl.cfg3(S=4), 16 * 4 * 5000),             # R=16 reduce-scatter only, 4 slabs
+    lambda: wl.scaled(wl.cfg4(S=32), 8 * 32 * 1100),            # flapping channel, 32 slabs
+    lambda: wl.cfg5(1),
+    lambda: wl.cfg5(16),
+]
+
+
+@pytest.mark.parametrize("make", SMALL, ids=lambda f: f().name)
+def test_sim_small_full_state(r2, oracle, make):
+    _full_compare_small(r2, oracle, make())
+
+
+def test_sim_stepwise_equals_one_call(r2, oracle):
+    _full_compare_small(r2, oracle, wl.scaled(wl.cfg2(), 8 * 4096 + 8 * 8), stepwise=True)
+
+
+@pytest.mark.parametrize("phases", ["rs", "ag", "ar"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("R", [2, 3, 5])
+def test_sim_phases_and_ring_sizes(r2, oracle, phases, dtype, R):
+    from dataclasses import replace
+
+    rng = np.random.default_rng(R * 10 + len(phases))
+    S, C = 3, 5
+    E = 777
+    T = S * ((2 * R - 2) if phases == "ar" else (R - 1))
+    eps = [(0, 0b00010, (3, 9, 1, 0, 4))]
+    if T > 2:
+        eps.append((T // 2, 0b01001, (3, 9, 1, 7, 4)))
+        eps.append((T - 1, 0, (1, 1, 1, 1, 100)))
+    w = replace(wl.cfg1(), name=f"ring_R{R}_{dtype}_{phases}", R=R, dtype=dtype, N=R * S * E, S=S, C=C, align=32,
+                phases=phases, sigma=1.0, seed=int(rng.integers(1, 1000)), epochs=tuple(eps))
+    _full_compare_small(r2, oracle, w)
+
+
+def test_sim_many_channels_and_single_channel(r2, oracle):
+    from dataclasses import replace
+
+    base = wl.scaled(wl.cfg1(), 4 * 30000)
+    w64 = replace(base, name="C64", C=64, align=16,
+                  epochs=((0, 0xF0F0, tuple(range(1, 65))), (2, 1 << 63, tuple([7] * 64))))
+    _full_compare_small(r2, oracle, w64)
+    w1 = replace(base, name="C1", C=1, epochs=((0, 0, (5,)),))
+    _full_compare_small(r2, oracle, w1)
+
+
+def test_sim_result_independent_of_schedule(r2, oracle):
+    """Lossless whatever the failure timing: different schedules, same bits."""
+    from dataclasses import replace
+
+    base = wl.scaled(wl.cfg2(), 8 * 10000)
+    xs = wl.make_inputs(base)
+    ref = None
+    for i, eps in enumerate([
+        ((0, 0, tuple([50000] * 8)),),
+        ((0, 0b11111110, tuple([50000] * 8)),),
+        ((0, 0, tuple([1, 2, 3, 4, 5, 6, 7, 8])), (1, 0b1, tuple([8, 7, 6, 5, 4, 3, 2, 1])), (9, 0b10000000, tuple([1] * 8))),
+    ]):
+        w = replace(base, epochs=eps, name=f"sched{i}")
+        say(f"sim schedule independence {i}")
+        outs, _, _, _ = run_gpu_sim(r2, w, xs)
+        blob = b"".join(o.tobytes() for o in outs)
+        ref = ref or blob
+        assert blob == ref
+
+
+def test_sim_empty_input(r2):
+    say("sim N=0")
+    desc = r2.SimDesc(4, 1, 4, 256, 0, r2.F32, r2.PHASE_AR)
+    ws = torch.empty(max(r2.r2_sim_workspace_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    r2.r2_ring_allreduce_sim(desc, [None] * 4, [(0, 0, [1, 1, 1, 1])], ws)
+    torch.cuda.synchronize()
+
+
+def test_sim_all_failed_touches_nothing(r2):
+    say("sim all channels failed at t=2")
+    w = wl.scaled(wl.cfg1(), 4 * 1024)
+    xs = wl.make_inputs(w)
+    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, r2.F32, r2.PHASE_AR)
+    bufs = [torch.from_numpy(x).cuda() for x in xs]
+    ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_ring_allreduce_sim(desc, bufs, [(0, 0, [1] * 4), (2, 0b1111, [1] * 4)], ws)
+    assert e.value.code == -2
+    torch.cuda.synchronize()
+    for b, x in zip(bufs, xs):
+        assert b.cpu().numpy().tobytes() == x.tobytes()
+    assert bool((ws == FILL).all())
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+
+def _full_size(r2, oracle, w, check_bound=False):
+    _, _, odt, oph = codes(r2, oracle, w)
+    say(f"sim full {w.name}: generating inputs")
+    xs = wl.make_inputs(w)
+    say(f"sim full {w.name}: GPU run")
+    outs, log, _, _ = run_gpu_sim(r2, w, xs)
+    say(f"sim full {w.name}: oracle")
+    want = oracle.expected(xs, odt, w.S, oph)
+    for r in range(w.R):
+        assert np.array_equal(outs[r], want[r]), f"{w.name}: rank {r}"
+    assert log.tolist() == expected_log(oracle, w).tolist()
+    if check_bound and w.dtype == "bf16":
+        # acceptance bound against the exact sum, on a sample: normwise 1e-2, and elementwise the
+        # a-priori bound for R-1 roundings of unit 2^-9
+        idx = np.random.default_rng(0).integers(0, w.N, size=200000)
+        x64 = np.stack([wl.bf16_bits_to_f64(x[idx]) for x in xs])
+        exact, absum = x64.sum(axis=0), np.abs(x64).sum(axis=0)
+        y = wl.bf16_bits_to_f64(outs[0][idx])
+        assert np.linalg.norm(y - exact) / np.linalg.norm(exact) <= 1e-2
+        assert np.all(np.abs(y - exact) <= 1e-2 * np.abs(exact) + (w.R - 1) * 2.0 ** -9 * absum)
+
+
+def test_full_cfg1(r2, oracle):
+    _full_size(r2, oracle, wl.cfg1())
+
+
+def test_full_cfg2(r2, oracle):
+    _full_size(r2, oracle, wl.cfg2(), check_bound=True)
+
+
+def test_full_cfg3(r2, oracle):
+    _full_size(r2, oracle, wl.cfg3())
+
+
+def test_full_cfg4(r2, oracle):
+    _full_size(r2, oracle, wl.cfg4(), check_bound=True)
+
+
+@pytest.mark.parametrize("tokens", wl.CFG5_TOKENS)
+def test_full_cfg5(r2, oracle, tokens):
+    _full_size(r2, oracle, wl.cfg5(tokens), check_bound=True)
