@@ -173,7 +173,7 @@ def test_reduce_copy_bad_tables_move_nothing(r2, oracle):
     good = oracle.partition([1, 1, 1, 1], 0, nbytes, 16)
     bad_tables = {
         "does not start at 0": (good + np.uint64(16)).astype(np.uint64),
-        "does not end at bytes": np.array([0, 1024, 2048, 4096, nbytes - 16], dtype=np.uint64),
+        "does not end at bytes": np.array([0, 4096, 8192, 12288, nbytes - 16], dtype=np.uint64),
         "decreasing": np.array([0, 8192, 4096, 12288, nbytes], dtype=np.uint64),
         "cut not on 16 bytes": np.array([0, 4100, 8192, 12288, nbytes], dtype=np.uint64),
         "all zero (failed partition)": np.zeros(5, dtype=np.uint64),
