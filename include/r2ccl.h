@@ -135,7 +135,11 @@ int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int op,
  * uses the writer's table.  A failure "at step k" is an epoch with t_start = k; a recovery is a
  * later epoch with the bit cleared.  The result in the rank buffers does not depend on the epochs.
  *
- * One fused step of all ranks and all slabs is one kernel launch (slabs are independent).
+ * Slabs are independent of each other, and so are the bytes of a chunk.  The run is therefore cut
+ * into passes -- groups of whole slabs, or, when one slab is too large, byte ranges of its chunks --
+ * such that the stage bytes one step writes (over all ranks) stay within stage_window_bytes and can
+ * be read back from the Infinity Cache by the next step.  All J steps of a pass run before the next
+ * pass starts; one fused step of one pass, for all ranks, is one kernel launch.
  * --------------------------------------------------------------------------------------------- */
 
 typedef struct {
@@ -153,6 +157,9 @@ typedef struct {
     uint64_t n_elems;    /* elements per rank, a multiple of R*S (0 is allowed: nothing to do)   */
     int32_t dtype;       /* r2_dtype                                                             */
     int32_t phases;      /* R2_PHASE_RS, R2_PHASE_AG or both                                     */
+    uint64_t stage_window_bytes; /* stage bytes one launch may write, summed over ranks; 0 = the
+                                    library's default (128 MiB, half the Infinity Cache).  Only
+                                    changes how the run is cut into passes, never the result.   */
 } r2_sim_desc;
 
 /* Pure host arithmetic on a descriptor (0 if the descriptor is invalid). */
@@ -175,12 +182,16 @@ uint64_t r2_sim_stage_capacity(const r2_sim_desc *desc);    /* bytes per channel
 int r2_sim_prepare(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs,
                    void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log, void *stream);
 
-/* Fused step j (0 <= j < J) of every rank and every slab: one launch.  rank_bufs is a HOST array of
- * R device pointers.  Needs the tables of r2_sim_prepare and, for j > 0, the stage of step j-1. */
-int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step,
+/* Number of passes the run is cut into (0 if the descriptor is invalid). */
+uint64_t r2_sim_num_passes(const r2_sim_desc *desc);
+
+/* Fused step j (0 <= j < J) of pass p, for every rank: one launch.  rank_bufs is a HOST array of
+ * R device pointers.  Needs the tables of r2_sim_prepare and, for j > 0, the stage that step j-1 of
+ * the same pass left. */
+int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint64_t pass, uint32_t step,
                 void *workspace, uint64_t workspace_bytes, void *stream);
 
-/* r2_sim_prepare followed by steps 0..J-1, in place on the rank buffers. */
+/* r2_sim_prepare, then for every pass the steps 0..J-1, in place on the rank buffers. */
 int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           const r2_epoch *epochs, uint32_t n_epochs,
                           void *workspace, uint64_t workspace_bytes,

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     r2_partition_device,
     r2_reduce_copy,
     r2_ring_allreduce_sim,
+    r2_sim_num_passes,
     r2_sim_num_steps,
     r2_sim_num_transmissions,
     r2_sim_prepare,

@@ -42,7 +42,7 @@ class _Epoch(C.Structure):
 class _SimDesc(C.Structure):
     _fields_ = [("n_ranks", C.c_uint32), ("n_slabs", C.c_uint32), ("n_channels", C.c_uint32),
                 ("align", C.c_uint32), ("n_elems", C.c_uint64), ("dtype", C.c_int32),
-                ("phases", C.c_int32)]
+                ("phases", C.c_int32), ("stage_window_bytes", C.c_uint64)]
 
 
 @dataclass(frozen=True)
@@ -54,10 +54,11 @@ class SimDesc:
     n_elems: int
     dtype: int
     phases: int
+    stage_window_bytes: int = 0  # 0 = library default
 
     def c(self) -> _SimDesc:
         return _SimDesc(self.n_ranks, self.n_slabs, self.n_channels, self.align, self.n_elems,
-                        self.dtype, self.phases)
+                        self.dtype, self.phases, self.stage_window_bytes)
 
 
 _lib = None
@@ -90,13 +91,13 @@ def load_library():
     lib.r2_sim_num_steps.restype = u32
     lib.r2_sim_num_steps.argtypes = [pd]
     for name in ("r2_sim_num_transmissions", "r2_sim_workspace_bytes", "r2_sim_stage_offset",
-                 "r2_sim_stage_capacity"):
+                 "r2_sim_stage_capacity", "r2_sim_num_passes"):
         getattr(lib, name).restype = u64
         getattr(lib, name).argtypes = [pd]
     lib.r2_sim_prepare.restype = i32
     lib.r2_sim_prepare.argtypes = [pd, vp, u32, vp, u64, vp, vp]
     lib.r2_sim_step.restype = i32
-    lib.r2_sim_step.argtypes = [pd, vp, u32, vp, u64, vp]
+    lib.r2_sim_step.argtypes = [pd, vp, u64, u32, vp, u64, vp]
     lib.r2_ring_allreduce_sim.restype = i32
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     _lib = lib
@@ -193,6 +194,10 @@ def r2_sim_num_transmissions(desc: SimDesc) -> int:
     return int(load_library().r2_sim_num_transmissions(C.byref(desc.c())))
 
 
+def r2_sim_num_passes(desc: SimDesc) -> int:
+    return int(load_library().r2_sim_num_passes(C.byref(desc.c())))
+
+
 def r2_sim_workspace_bytes(desc: SimDesc) -> int:
     return int(load_library().r2_sim_workspace_bytes(C.byref(desc.c())))
 
@@ -221,11 +226,11 @@ def r2_sim_prepare(desc: SimDesc, epochs, workspace, offsets_log: Optional[torch
     _check(rc, "r2_sim_prepare")
 
 
-def r2_sim_step(desc: SimDesc, rank_bufs: Sequence, step: int, workspace, stream=None,
+def r2_sim_step(desc: SimDesc, rank_bufs: Sequence, pass_index: int, step: int, workspace, stream=None,
                 workspace_bytes: Optional[int] = None) -> None:
     arr, p = _ptr_array(rank_bufs)
     wp, wb = _ws(workspace, workspace_bytes)
-    rc = load_library().r2_sim_step(C.byref(desc.c()), p, int(step), wp, wb, _stream(stream))
+    rc = load_library().r2_sim_step(C.byref(desc.c()), p, int(pass_index), int(step), wp, wb, _stream(stream))
     del arr
     _check(rc, "r2_sim_step")
 

@@ -14,10 +14,55 @@
 namespace r2 {
 namespace {
 
-constexpr unsigned kThreads = 256;
-constexpr unsigned kUnroll = 4;        // 16-byte vectors in flight per lane and stream
-constexpr unsigned kBlocksPerCU = 8;   // grid target: this many workgroups per compute unit
-constexpr unsigned kComputeUnits = 256;
+// Launch shape and cache policy; the defaults are the measured best on MI355X.
+#ifndef R2_THREADS
+#define R2_THREADS 256
+#endif
+#ifndef R2_UNROLL
+#define R2_UNROLL 2
+#endif
+#ifndef R2_NT_LOCAL_LOAD
+#define R2_NT_LOCAL_LOAD 1
+#endif
+#ifndef R2_NT_LOCAL_STORE
+#define R2_NT_LOCAL_STORE 1
+#endif
+#ifndef R2_NT_STAGE_LOAD
+#define R2_NT_STAGE_LOAD 1
+#endif
+#ifndef R2_NT_STAGE_STORE
+#define R2_NT_STAGE_STORE 0
+#endif
+constexpr unsigned kThreads = R2_THREADS;
+constexpr unsigned kUnroll = R2_UNROLL;             // 16-byte vectors in flight per lane and stream
+
+// A 16-byte vector as the compiler's native type, so that one access is one dwordx4 instruction.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Addresses are kept as integers; they all point into device (global) memory, and saying so gives
+// global_load/global_store instead of the slower flat (generic address) instructions.
+#define R2_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ inline R2_GLOBAL T *gptr(uint64_t addr)
+{
+    return (R2_GLOBAL T *)addr;
+}
+
+// Every byte is touched once per launch: stream past the caches (non-temporal hint).
+template <bool NT>
+__device__ inline u32x4 load16(uint64_t addr)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(gptr<const u32x4>(addr));
+    else return *gptr<const u32x4>(addr);
+}
+template <bool NT>
+__device__ inline void store16(uint64_t addr, u32x4 v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, gptr<u32x4>(addr));
+    else *gptr<u32x4>(addr) = v;
+}
+constexpr bool kNtLocalLoad = R2_NT_LOCAL_LOAD, kNtLocalStore = R2_NT_LOCAL_STORE;
+constexpr bool kNtStageLoad = R2_NT_STAGE_LOAD, kNtStageStore = R2_NT_STAGE_STORE;
 
 enum Mode : int { kSend = 0, kSumF32 = 1, kSumBF16 = 2, kCopy = 3 };
 
@@ -26,33 +71,37 @@ enum Mode : int { kSend = 0, kSumF32 = 1, kSumBF16 = 2, kCopy = 3 };
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 
-// fp32 -> bf16, round to nearest even; NaN stays NaN (quiet).
-__device__ inline uint32_t to_bf16(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// Two bf16 sums at once: widen (exact), add in fp32, narrow with round-to-nearest-even.  The
+// narrowing is the hardware's packed convert (v_cvt_pk_bf16_f32 on gfx950).
 __device__ inline uint32_t add_bf16x2(uint32_t a, uint32_t b)
 {
-    const uint32_t lo = to_bf16(bf16_lo(a) + bf16_lo(b));
-    const uint32_t hi = to_bf16(bf16_hi(a) + bf16_hi(b));
-    return lo | (hi << 16);
+    f32x2 s;
+    s.x = bf16_lo(a) + bf16_lo(b);
+    s.y = bf16_hi(a) + bf16_hi(b);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(s, bf16x2));
+}
+
+__device__ inline uint16_t add_bf16(uint16_t a, uint16_t b)
+{
+    const float s = bf16_lo(a) + bf16_lo(b);
+    return __builtin_bit_cast(uint16_t, (__bf16)s);
 }
 
 template <Mode M>
-__device__ inline uint4 combine(const uint4 &incoming, const uint4 &local)
+__device__ inline u32x4 combine(const u32x4 &incoming, const u32x4 &local)
 {
     if constexpr (M == kSumF32) {
-        uint4 v;
+        u32x4 v;
         v.x = __float_as_uint(__uint_as_float(incoming.x) + __uint_as_float(local.x));
         v.y = __float_as_uint(__uint_as_float(incoming.y) + __uint_as_float(local.y));
         v.z = __float_as_uint(__uint_as_float(incoming.z) + __uint_as_float(local.z));
         v.w = __float_as_uint(__uint_as_float(incoming.w) + __uint_as_float(local.w));
         return v;
     } else if constexpr (M == kSumBF16) {
-        uint4 v;
+        u32x4 v;
         v.x = add_bf16x2(incoming.x, local.x);
         v.y = add_bf16x2(incoming.y, local.y);
         v.z = add_bf16x2(incoming.z, local.z);
@@ -83,6 +132,28 @@ __device__ inline uint32_t find_channel(const uint64_t *off, uint32_t C, uint64_
     return lo;
 }
 
+__device__ inline uint64_t uniform64(uint64_t x)  // tell the compiler the value is wave-uniform
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// The slice that holds chunk byte b0, remembered from tile to tile: a workgroup walks the chunk
+// front to back and slices are long, so the table is searched only when a cut is crossed.
+struct Span {
+    uint64_t lo = 0, hi = 0, delta = 0;
+};
+__device__ inline void locate(const ChannelTable &t, uint32_t C, uint64_t b0, Span &s)
+{
+    if (b0 < s.lo || b0 >= s.hi) {
+        const uint32_t c = find_channel(t.off, C, b0);
+        s.lo = uniform64(t.off[c]);
+        s.hi = uniform64(t.off[c + 1]);
+        s.delta = uniform64(t.delta[c]);
+    }
+}
+
 // Lanes 0..C of the workgroup copy one table to LDS and check it.  Returns 0 or an R2_ERR code
 // (per lane; the caller combines them).
 __device__ inline int load_table(ChannelTable &t, const uint64_t *__restrict__ g_off,
@@ -110,7 +181,9 @@ __device__ inline int load_table(ChannelTable &t, const uint64_t *__restrict__ g
 
 struct ChunkJob {
     uint8_t *local;
-    uint64_t bytes;
+    uint64_t bytes;           // the whole chunk: what the tables partition
+    uint64_t lo, hi;          // the part of it this launch moves; lo is a multiple of 16, and so
+                              // is hi unless hi == bytes
     const uint64_t *in_off;   // device table or null
     const uint64_t *out_off;  // device table or null
     uint64_t cap;
@@ -143,21 +216,57 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
 
     uint8_t *const local = job.local;
     const bool aligned = (reinterpret_cast<uintptr_t>(local) & 15u) == 0;
-    const uint64_t nvec = aligned ? job.bytes / 16 : 0;
+    const uint64_t vbegin = job.lo / 16;
+    const uint64_t nvec = aligned ? job.hi / 16 : vbegin;  // vectors [vbegin, nvec)
 
+    // Whole 16-byte vectors, a tile of kThreads*kUnroll consecutive vectors per iteration.  If one
+    // slice holds the whole tile (nearly always) its address delta is wave-uniform; a tile that
+    // straddles a cut lets every lane look its own vector up.
+    const uint64_t local_addr = reinterpret_cast<uint64_t>(local);
     const uint64_t tile = (uint64_t)kThreads * kUnroll;
-    for (uint64_t v0 = (uint64_t)blockIdx.x * tile; v0 < nvec; v0 += (uint64_t)gridDim.x * tile) {
-        uint4 inc[kUnroll], loc[kUnroll];
+    Span sin, sout;
+    for (uint64_t v0 = vbegin + (uint64_t)blockIdx.x * tile; v0 < nvec; v0 += (uint64_t)gridDim.x * tile) {
+        const uint64_t b0 = v0 * 16;
+        const uint64_t b1 = (v0 + tile < nvec ? v0 + tile : nvec) * 16;
+        bool in_one = true, out_one = true;
+        if constexpr (HAS_IN) {
+            locate(tin, C, b0, sin);
+            in_one = b1 <= sin.hi;
+        }
+        if constexpr (HAS_OUT) {
+            locate(tout, C, b0, sout);
+            out_one = b1 <= sout.hi;
+        }
+        u32x4 inc[kUnroll], loc[kUnroll];
+        if (v0 + tile <= nvec && in_one && out_one) {
+            // Full tile inside one slice of either table: straight-line code, all loads of the
+            // tile in flight together.
+            const uint64_t b = (v0 + threadIdx.x) * 16;
+#pragma unroll
+            for (unsigned u = 0; u < kUnroll; ++u) {
+                if constexpr (HAS_IN) inc[u] = load16<kNtStageLoad>(sin.delta + b + u * (kThreads * 16));
+                if constexpr (NEED_LOCAL) loc[u] = load16<kNtLocalLoad>(local_addr + b + u * (kThreads * 16));
+            }
+#pragma unroll
+            for (unsigned u = 0; u < kUnroll; ++u) {
+                const u32x4 r = combine<M>(inc[u], loc[u]);
+                if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b + u * (kThreads * 16), r);
+                if constexpr (HAS_OUT) store16<kNtStageStore>(sout.delta + b + u * (kThreads * 16), r);
+            }
+            continue;
+        }
+        // The chunk's last, partial tile, or a tile that straddles a cut: every lane checks its
+        // bounds and, where needed, looks its channel up.
 #pragma unroll
         for (unsigned u = 0; u < kUnroll; ++u) {
             const uint64_t v = v0 + u * kThreads + threadIdx.x;
             if (v < nvec) {
                 const uint64_t b = v * 16;
                 if constexpr (HAS_IN) {
-                    const uint32_t c = find_channel(tin.off, C, b);
-                    inc[u] = *reinterpret_cast<const uint4 *>(tin.delta[c] + b);
+                    const uint64_t d = in_one ? sin.delta : tin.delta[find_channel(tin.off, C, b)];
+                    inc[u] = load16<kNtStageLoad>(d + b);
                 }
-                if constexpr (NEED_LOCAL) loc[u] = *reinterpret_cast<const uint4 *>(local + b);
+                if constexpr (NEED_LOCAL) loc[u] = load16<kNtLocalLoad>(local_addr + b);
             }
         }
 #pragma unroll
@@ -165,39 +274,39 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
             const uint64_t v = v0 + u * kThreads + threadIdx.x;
             if (v < nvec) {
                 const uint64_t b = v * 16;
-                const uint4 r = combine<M>(inc[u], loc[u]);
-                if constexpr (HAS_IN) *reinterpret_cast<uint4 *>(local + b) = r;
+                const u32x4 r = combine<M>(inc[u], loc[u]);
+                if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b, r);
                 if constexpr (HAS_OUT) {
-                    const uint32_t c = find_channel(tout.off, C, b);
-                    *reinterpret_cast<uint4 *>(tout.delta[c] + b) = r;
+                    const uint64_t d = out_one ? sout.delta : tout.delta[find_channel(tout.off, C, b)];
+                    store16<kNtStageStore>(d + b, r);
                 }
             }
         }
     }
 
     // What the vectors did not cover, one element at a time: the last bytes % 16 of an aligned
-    // chunk, or all of a chunk whose address is only element-aligned.
+    // chunk, or everything if the chunk's address is only element-aligned.
     using Elem = typename std::conditional<M == kSumF32, uint32_t, uint16_t>::type;
     const uint64_t first = nvec * 16;
-    const uint64_t n_el = (job.bytes - first) / sizeof(Elem);
+    const uint64_t n_el = (job.hi - first) / sizeof(Elem);
     for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < n_el;
          i += (uint64_t)gridDim.x * kThreads) {
         const uint64_t b = first + i * sizeof(Elem);
         Elem x_in = 0, x_loc = 0;
         if constexpr (HAS_IN) {
             const uint32_t c = find_channel(tin.off, C, b);
-            x_in = *reinterpret_cast<const Elem *>(tin.delta[c] + b);
+            x_in = *gptr<const Elem>(tin.delta[c] + b);
         }
-        if constexpr (NEED_LOCAL) x_loc = *reinterpret_cast<const Elem *>(local + b);
+        if constexpr (NEED_LOCAL) x_loc = *gptr<const Elem>(local_addr + b);
         Elem r;
         if constexpr (M == kSumF32) r = __float_as_uint(__uint_as_float(x_in) + __uint_as_float(x_loc));
-        else if constexpr (M == kSumBF16) r = (Elem)to_bf16(bf16_lo(x_in) + bf16_lo(x_loc));
+        else if constexpr (M == kSumBF16) r = add_bf16(x_in, x_loc);
         else if constexpr (M == kCopy) r = x_in;
         else r = x_loc;
-        if constexpr (HAS_IN) *reinterpret_cast<Elem *>(local + b) = r;
+        if constexpr (HAS_IN) *gptr<Elem>(local_addr + b) = r;
         if constexpr (HAS_OUT) {
             const uint32_t c = find_channel(tout.off, C, b);
-            *reinterpret_cast<Elem *>(tout.delta[c] + b) = r;
+            *gptr<Elem>(tout.delta[c] + b) = r;
         }
     }
 }
@@ -229,14 +338,16 @@ struct StepArgs {
     uint32_t step;         // fused step j
     uint32_t T_slab;       // transmissions per slab
     uint32_t chunk_start;  // 1 when the run is an all-gather alone, else 0
+    uint32_t slab_begin, slab_count;  // the slabs this launch covers
+    uint64_t lo, hi;                  // and the byte range of every ring chunk it moves
 };
 
-// blockIdx.y = rank * S + slab, blockIdx.x = workgroup within that chunk.
+// blockIdx.y = rank * slab_count + (slab - slab_begin), blockIdx.x = workgroup within the range.
 template <Mode M, bool HAS_OUT>
 __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
 {
     __shared__ ChannelTable tin, tout;
-    const uint32_t r = blockIdx.y / a.S, l = blockIdx.y - r * a.S;
+    const uint32_t r = blockIdx.y / a.slab_count, l = a.slab_begin + (blockIdx.y - r * a.slab_count);
     const uint32_t j = a.step;
     const uint32_t chunk = (r + a.chunk_start + 2 * a.R - j) % a.R;  // j <= 2R-2
     const uint32_t peer = (r + a.R - 1) % a.R;
@@ -246,6 +357,8 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
     ChunkJob job;
     job.local = reinterpret_cast<uint8_t *>(a.rank_buf[r]) + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
     job.bytes = a.chunk_bytes;
+    job.lo = a.lo;
+    job.hi = a.hi;
     job.in_off = M != kSend ? a.tables + (t_out - 1) * row : nullptr;
     job.out_off = HAS_OUT ? a.tables + t_out * row : nullptr;
     job.cap = a.cap;
@@ -260,13 +373,15 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
 
 // ---------------------------------------------------------------- host side
 
-unsigned blocks_for(uint64_t bytes, uint64_t n_chunks)
+// One workgroup per tile of kThreads*kUnroll vectors: consecutive workgroups stream consecutive
+// memory, which measured faster than fewer workgroups striding through the range.  (The kernels
+// loop, so the cap only matters for ranges beyond 8 GiB.)
+unsigned blocks_for(uint64_t range_bytes)
 {
     const uint64_t tile_bytes = (uint64_t)kThreads * kUnroll * 16;
-    uint64_t want = (bytes + tile_bytes - 1) / tile_bytes;
+    uint64_t want = (range_bytes + tile_bytes - 1) / tile_bytes;
     if (want == 0) want = 1;
-    uint64_t limit = ((uint64_t)kComputeUnits * kBlocksPerCU + n_chunks - 1) / n_chunks;
-    if (limit == 0) limit = 1;
+    const uint64_t limit = 1u << 20;
     return (unsigned)(want < limit ? want : limit);
 }
 
@@ -280,10 +395,17 @@ Mode mode_of(bool has_in, int op, int dtype)
     return dtype == R2_F32 ? kSumF32 : kSumBF16;
 }
 
+// The stage bytes one launch writes are read back by the next launch.  Keeping that window well
+// inside the 256 MiB Infinity Cache lets the read be served from it.
+constexpr uint64_t kDefaultStageWindow = 128ull << 20;
+
 struct SimShape {
     uint32_t R, S, C, J, T_slab;
     uint64_t chunk_bytes, cap, n_tx;
     uint64_t tables_bytes, stage_off, total_bytes;
+    // passes: the run is cut into groups of slabs, or one slab's chunks into byte ranges
+    uint32_t slabs_per_pass, n_sub;
+    uint64_t sub_bytes, n_passes;
 };
 
 uint64_t round_up(uint64_t x, uint64_t m) { return (x + m - 1) / m * m; }
@@ -315,6 +437,23 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     const unsigned __int128 stage = (unsigned __int128)2 * s.R * s.S * s.C * s.cap;
     if (stage > ((unsigned __int128)1 << 62)) return R2_ERR_OVERFLOW;
     s.total_bytes = s.stage_off + (uint64_t)stage;
+
+    const uint64_t window = d->stage_window_bytes ? d->stage_window_bytes : kDefaultStageWindow;
+    const uint64_t per_slab = (uint64_t)s.R * s.chunk_bytes;  // stage bytes a step writes per slab
+    if (per_slab > window) {
+        const uint64_t tile_bytes = (uint64_t)kThreads * kUnroll * 16;
+        const uint64_t parts = (per_slab + window - 1) / window;
+        s.slabs_per_pass = 1;
+        s.sub_bytes = round_up((s.chunk_bytes + parts - 1) / parts, tile_bytes);
+        s.n_sub = (uint32_t)((s.chunk_bytes + s.sub_bytes - 1) / s.sub_bytes);
+        s.n_passes = (uint64_t)s.S * s.n_sub;
+    } else {
+        const uint64_t fit = per_slab ? window / per_slab : s.S;
+        s.slabs_per_pass = (uint32_t)(fit < 1 ? 1 : (fit > s.S ? s.S : fit));
+        s.sub_bytes = s.chunk_bytes;
+        s.n_sub = 1;
+        s.n_passes = (s.S + s.slabs_per_pass - 1) / s.slabs_per_pass;
+    }
     return R2_OK;
 }
 
@@ -383,8 +522,8 @@ extern "C" int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int o
             if (!out.p[c] || (out.p[c] & 15u)) return R2_ERR_INVALID;
         }
     }
-    ChunkJob job{static_cast<uint8_t *>(local), bytes, in_offsets, out_offsets, stage_capacity, n_channels};
-    const unsigned blocks = blocks_for(bytes, 1);
+    ChunkJob job{static_cast<uint8_t *>(local), bytes, 0, bytes, in_offsets, out_offsets, stage_capacity, n_channels};
+    const unsigned blocks = blocks_for(bytes);
     hipStream_t st = (hipStream_t)stream;
     const Mode m = mode_of(in_stage != nullptr, op, dtype);
     const bool has_out = out_stage != nullptr;
@@ -450,13 +589,19 @@ extern "C" int r2_sim_prepare(const r2_sim_desc *desc, const r2_epoch *epochs, u
                                    static_cast<uint64_t *>(workspace), offsets_log, (hipStream_t)stream);
 }
 
-extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step,
-                           void *workspace, uint64_t workspace_bytes, void *stream)
+extern "C" uint64_t r2_sim_num_passes(const r2_sim_desc *desc)
+{
+    SimShape s;
+    return shape_of(desc, s) == R2_OK ? s.n_passes : 0;
+}
+
+extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint64_t pass,
+                           uint32_t step, void *workspace, uint64_t workspace_bytes, void *stream)
 {
     SimShape s;
     int rc = shape_of(desc, s);
     if (rc) return rc;
-    if (!rank_bufs || step >= s.J) return R2_ERR_INVALID;
+    if (!rank_bufs || step >= s.J || pass >= s.n_passes) return R2_ERR_INVALID;
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
     StepArgs a{};
     for (uint32_t r = 0; r < s.R; ++r) {
@@ -474,6 +619,17 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     a.step = step;
     a.T_slab = s.T_slab;
     a.chunk_start = desc->phases == R2_PHASE_AG ? 1 : 0;
+    if (s.n_sub > 1) {  // one slab, one byte range of its chunks
+        a.slab_begin = (uint32_t)(pass / s.n_sub);
+        a.slab_count = 1;
+        a.lo = (pass % s.n_sub) * s.sub_bytes;
+        a.hi = a.lo + s.sub_bytes < s.chunk_bytes ? a.lo + s.sub_bytes : s.chunk_bytes;
+    } else {  // a group of whole slabs
+        a.slab_begin = (uint32_t)(pass * s.slabs_per_pass);
+        a.slab_count = s.S - a.slab_begin < s.slabs_per_pass ? s.S - a.slab_begin : s.slabs_per_pass;
+        a.lo = 0;
+        a.hi = s.chunk_bytes;
+    }
 
     const bool has_in = step > 0, has_out = step < s.J - 1;
     int op;
@@ -482,8 +638,7 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     else op = step <= s.R - 1 ? R2_OP_SUM : R2_OP_COPY;
     const Mode m = mode_of(has_in, op, desc->dtype);
 
-    const uint64_t n_chunks = (uint64_t)s.R * s.S;
-    const dim3 grid(blocks_for(s.chunk_bytes, n_chunks), (unsigned)n_chunks);
+    const dim3 grid(blocks_for(a.hi - a.lo), s.R * a.slab_count);
     hipStream_t st = (hipStream_t)stream;
     switch (m) {
     case kSend: launch_step<kSend, true>(a, grid, st); break;
@@ -514,8 +669,9 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
     }
     if ((rc = r2_sim_prepare(desc, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream)))
         return rc;
-    for (uint32_t j = 0; j < s.J; ++j)
-        if ((rc = r2_sim_step(desc, rank_bufs, j, workspace, workspace_bytes, stream))) return rc;
+    for (uint64_t p = 0; p < s.n_passes; ++p)
+        for (uint32_t j = 0; j < s.J; ++j)
+            if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
     return R2_OK;
 }
 

@@ -58,6 +58,24 @@ def test_sim_shape_arithmetic(r2):
     assert r2.r2_sim_stage_capacity(rs) == 4 << 20
 
 
+def test_pass_planning(r2):
+    """Passes bound the stage bytes one step writes (over all ranks) by the window."""
+    mib = 1 << 20
+    # 8 ranks x 16 MiB chunks = 128 MiB per step: exactly the default window, one pass
+    d = r2.SimDesc(8, 1, 8, 256, 1 << 26, r2.BF16, r2.PHASE_AR)
+    assert r2.r2_sim_num_passes(d) == 1
+    # 16 ranks x 4 MiB = 64 MiB per slab: two slabs per pass
+    assert r2.r2_sim_num_passes(r2.SimDesc(16, 4, 8, 256, 1 << 26, r2.F32, r2.PHASE_RS)) == 2
+    # a 32 MiB window cuts the 16 MiB chunks into four byte ranges
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 1, 8, 256, 1 << 26, r2.BF16, r2.PHASE_AR, 32 * mib)) == 4
+    # 32 slabs of 8 x 256 KiB = 2 MiB each: all in one pass by default, one per pass at 2 MiB
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 32, 8, 256, 1 << 25, r2.BF16, r2.PHASE_AR)) == 1
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 32, 8, 256, 1 << 25, r2.BF16, r2.PHASE_AR, 2 * mib)) == 32
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 32, 8, 256, 1 << 25, r2.BF16, r2.PHASE_AR, 5 * mib)) == 16
+    # empty input: one empty pass
+    assert r2.r2_sim_num_passes(r2.SimDesc(4, 1, 4, 256, 0, r2.F32, r2.PHASE_AR)) == 1
+
+
 @pytest.mark.parametrize("bad", [
     dict(n_ranks=1), dict(n_ranks=65), dict(n_channels=0), dict(n_channels=65), dict(n_slabs=0),
     dict(align=0), dict(align=8), dict(align=24), dict(n_elems=(1 << 20) + 1), dict(dtype=7),
@@ -105,7 +123,10 @@ def test_sim_rejects_bad_epochs_and_buffers_before_any_device_work(r2):
         r2.r2_ring_allreduce_sim(d, [4096, 8192, 12288 + 4, 16384], ok_ep, 4096, workspace_bytes=need)
     assert e.value.code == -1
     with pytest.raises(r2.R2Error) as e:
-        r2.r2_sim_step(d, bufs, 7, 4096, workspace_bytes=need)  # J = 7: steps are 0..6
+        r2.r2_sim_step(d, bufs, 0, 7, 4096, workspace_bytes=need)  # J = 7: steps are 0..6
+    assert e.value.code == -1
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_sim_step(d, bufs, 1, 0, 4096, workspace_bytes=need)  # a single pass
     assert e.value.code == -1
 
 

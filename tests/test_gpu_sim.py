@@ -31,18 +31,19 @@ def _stage_of(ws: torch.Tensor, r2, desc, w):
     return ws[off:off + n].cpu().numpy().reshape(2, w.R, w.S, w.C, cap), cap
 
 
-def _full_compare_small(r2, oracle, w, stepwise=False):
+def _full_compare_small(r2, oracle, w, stepwise=False, window=0, check_stage=True):
     _, _, odt, oph = codes(r2, oracle, w)
     xs = wl.make_inputs(w)
     say(f"sim small {w.name} R={w.R} N={w.N} S={w.S} C={w.C} {w.dtype} {w.phases} stepwise={stepwise}")
-    outs, log, ws, desc = run_gpu_sim(r2, w, xs, fill_stage=True, stepwise=stepwise)
+    outs, log, ws, desc = run_gpu_sim(r2, w, xs, fill_stage=True, stepwise=stepwise, window=window)
     stage, cap = _stage_of(ws, r2, desc, w)
     o_bufs = [x.copy() for x in xs]
     o_log, o_stage = oracle.ring_sim(o_bufs, odt, w.S, w.C, w.align, list(w.epochs), oph, cap=cap, stage_fill=FILL)
     for r in range(w.R):
         assert outs[r].tobytes() == o_bufs[r].tobytes(), f"{w.name}: rank {r} buffer"
     assert log.tolist() == o_log.tolist(), f"{w.name}: offsets log"
-    assert stage.tobytes() == o_stage.tobytes(), f"{w.name}: stage area"
+    if check_stage:
+        assert stage.tobytes() == o_stage.tobytes(), f"{w.name}: stage area"
     want = oracle.expected(xs, odt, w.S, oph)
     for r in range(w.R):
         assert outs[r].tobytes() == want[r].tobytes()
@@ -67,6 +68,30 @@ def test_sim_small_full_state(r2, oracle, make):
 
 def test_sim_stepwise_equals_one_call(r2, oracle):
     _full_compare_small(r2, oracle, wl.scaled(wl.cfg2(), 8 * 4096 + 8 * 8), stepwise=True)
+    _full_compare_small(r2, oracle, wl.scaled(wl.cfg2(), 8 * 40000 + 8 * 8), stepwise=True, window=100000,
+                        check_stage=False)
+
+
+@pytest.mark.parametrize("window", [1, 8192, 70000, 1 << 20])
+def test_sim_passes_leave_the_same_state(r2, oracle, window):
+    """Cutting the run into passes (byte ranges of a chunk, or groups of slabs) changes the launch
+    order only: buffers and log still match the oracle byte for byte.  So does the stage area,
+    except where byte ranges of one slab meet a channel state that changes mid-run: then a stage
+    location can be written by different transmissions in different passes, and which one is left
+    over at the end depends on the pass order (what each step READS is unaffected: a pass runs its
+    steps back to back)."""
+    from dataclasses import replace
+
+    w2 = wl.scaled(wl.cfg2(), 8 * 8192 * 3 + 8 * 24)
+    ranges_in_use = 8 * w2.chunk_bytes > window
+    _full_compare_small(r2, oracle, w2, window=window, check_stage=not ranges_in_use)            # ranges of one slab
+    _full_compare_small(r2, oracle, replace(w2, epochs=w2.epochs[1:2] and ((0,) + w2.epochs[1][1:],)),
+                        window=window)                                                           # same, one state
+    _full_compare_small(r2, oracle, wl.scaled(wl.cfg1(), 4 * 4096 * 3 + 4 * 9), window=window)    # fp32, 36-byte tail
+    _full_compare_small(r2, oracle, wl.scaled(wl.cfg4(S=32), 8 * 32 * 1100), window=window,
+                        check_stage=8 * 2200 <= window)                                          # slab groups
+    _full_compare_small(r2, oracle, wl.scaled(wl.cfg3(S=4), 16 * 4 * 5001), window=window,
+                        check_stage=16 * 20004 <= window)                                        # element path
 
 
 @pytest.mark.parametrize("phases", ["rs", "ag", "ar"])
