@@ -22,6 +22,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure (8 TB/s)
 
+# Bytes per launch between L2 and the memory fabric for the dominant kernel, from two
+# `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled
+# by what the same counter reads for a plain 128 MiB device-to-device copy in the same run
+# (FETCH_SIZE reads half the copied bytes there, WRITE_SIZE all of them).  The figures and the
+# commands are in profiles/ring_step_sum_bf16_cfg2_pmc.md.  Not measured for other workloads.
+MEASURED_TRAFFIC = {
+    ("cfg2", "sum"): int((131117.2 * (131072.0 / 65550.7) + 262158.5 * (131072.0 / 131072.0)) * 1024),
+}
+
 
 def _workload(name: str):
     import workloads as wl
@@ -76,25 +85,37 @@ class Runner:
         return time.perf_counter() - t0
 
     def kernel_times(self, reps: int):
-        """Per fused step j: the duration in ms of its launches summed over the passes of one run,
-        averaged over `reps` runs driven launch by launch in the order r2_ring_allreduce_sim uses.
-        HIP events are recorded on the stream the kernels run on."""
+        """Average launch duration in ms per kind of fused step, over `reps` runs driven launch by
+        launch in the order r2_ring_allreduce_sim uses.  Steps of one kind are consecutive within a
+        pass (send | sum ... | copy ... | last); each such group is bracketed by one pair of HIP
+        events, recorded on the stream the kernels run on, so the figure holds the kernels and the
+        dispatch gaps between them, as in the real run.  Returns {kind: (avg_ms, launches)}."""
         torch, r2 = self.torch, self.r2
-        sums = [0.0] * self.J
+        kinds = [_step_units(self.w, j)[0] for j in range(self.J)]
+        groups = []  # (kind, first step, last step)
+        for j, k in enumerate(kinds):
+            if groups and groups[-1][0] == k:
+                groups[-1][2] = j
+            else:
+                groups.append([k, j, j])
+        total, count = {}, {}
         for _ in range(reps):
             self.restore()
             r2.r2_sim_prepare(self.desc, self.w.epochs, self.ws)
-            n = self.P * self.J
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
-            ev[0].record()
+            pairs = []
             for p in range(self.P):
-                for j in range(self.J):
-                    r2.r2_sim_step(self.desc, self.bufs, p, j, self.ws)
-                    ev[p * self.J + j + 1].record()
+                for k, j0, j1 in groups:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for j in range(j0, j1 + 1):
+                        r2.r2_sim_step(self.desc, self.bufs, p, j, self.ws)
+                    e1.record()
+                    pairs.append((k, j1 - j0 + 1, e0, e1))
             torch.cuda.synchronize()
-            for i in range(n):
-                sums[i % self.J] += ev[i].elapsed_time(ev[i + 1])
-        return [s / reps for s in sums]
+            for k, n, e0, e1 in pairs:
+                total[k] = total.get(k, 0.0) + e0.elapsed_time(e1)
+                count[k] = count.get(k, 0) + n
+        return {k: (total[k] / count[k], count[k]) for k in total}
 
 
 def _step_units(w, j):
@@ -183,17 +204,17 @@ def main() -> int:
     gbps = w.algorithmic_bytes / (secs / args.steps) / 1e9
 
     # dominant kernel: the fused reducing step that also stages (two reads, two writes per element)
-    per_step_ms = run.kernel_times(args.kernel_reps)
-    kinds = [_step_units(w, j) for j in range(run.J)]
-    dom = "sum" if any(k == "sum" for k, _ in kinds) else "copy"
-    dom_ms = [per_step_ms[j] for j in range(run.J) if kinds[j][0] == dom]
+    ktimes = run.kernel_times(args.kernel_reps)
+    dom = "sum" if "sum" in ktimes else "copy"
     dom_units = 4 if dom == "sum" else 3
-    # one step j over all passes moves, for every rank and slab, one ring chunk through dom_units streams
+    dom_avg_ms, dom_launches = ktimes[dom]
+    # one fused step moves, for every rank and slab, one ring chunk through dom_units streams; it is
+    # spread over the run's passes, one launch each
     launch_bytes = dom_units * w.N * w.elem_bytes / run.P
-    dom_avg_ms = sum(dom_ms) / len(dom_ms) / run.P
     achieved = launch_bytes / (dom_avg_ms * 1e-3) / 1e9
     kernel_name = {"sum": "ring_step_kernel<Sum%s, staged>" % ("BF16" if w.dtype == "bf16" else "F32"),
                    "copy": "ring_step_kernel<Copy, staged>"}[dom]
+    traffic = MEASURED_TRAFFIC.get((w.name, dom))
 
     out = {
         "metric": "reduce-copy effective HBM GB/s",
@@ -223,12 +244,12 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": traffic,
             "bytes_per_launch": launch_bytes,
             "avg_launch_ms": round(dom_avg_ms, 5),
-            "launches_timed": len(dom_ms) * run.P * args.kernel_reps,
+            "launches_timed": dom_launches,
         },
-        "per_step_ms": [round(x, 5) for x in per_step_ms],
+        "launch_ms_by_kind": {k: round(v[0], 5) for k, v in ktimes.items()},
         "context": "paper reports <1% training and <3% inference failover overhead on 2x8 H100 InfiniBand "
                    "servers; it gives no kernel-level number, so vs_baseline is null",
     }
