@@ -41,10 +41,10 @@ def _workload(name: str):
     return {"cfg1": wl.cfg1, "cfg2": wl.cfg2, "cfg3": wl.cfg3, "cfg4": wl.cfg4}[name]()
 
 
-def _desc(r2, w, window=0):
+def _desc(r2, w, window=0, schedule=0):
     dt = r2.F32 if w.dtype == "f32" else r2.BF16
     ph = {"ar": r2.PHASE_AR, "rs": r2.PHASE_RS, "ag": r2.PHASE_AG}[w.phases]
-    return r2.SimDesc(w.R, w.S, w.C, w.align, w.N, dt, ph, window)
+    return r2.SimDesc(w.R, w.S, w.C, w.align, w.N, dt, ph, window, schedule)
 
 
 def _to_device(torch, np, x):
@@ -54,21 +54,40 @@ def _to_device(torch, np, x):
 class Runner:
     """Device state of one workload: pristine inputs, working buffers, workspace."""
 
-    def __init__(self, r2, torch, np, w, xs, window=0):
+    def __init__(self, r2, torch, np, w, xs, window=0, schedule=0):
         self.r2, self.torch, self.w = r2, torch, w
-        self.desc = _desc(r2, w, window)
+        self.desc = _desc(r2, w, window, schedule)
+        self.fused = r2.r2_sim_resolve_schedule(self.desc, w.epochs) == r2.SCHED_FUSED
         self.pristine = [_to_device(torch, np, x) for x in xs]
         self.bufs = [p.clone() for p in self.pristine]
         self.ws = torch.empty(r2.r2_sim_workspace_bytes(self.desc), dtype=torch.uint8, device="cuda")
         self.J = r2.r2_sim_num_steps(self.desc)
         self.P = r2.r2_sim_num_passes(self.desc)
+        self.call = r2.SimCall(self.desc, self.bufs, w.epochs, self.ws)  # arguments marshalled once
+
+    def _fused_times(self, reps: int):
+        """Fused-column schedule: all launches of a run between one pair of events."""
+        torch, r2 = self.torch, self.r2
+        segs = _fused_segments(self.w)
+        total = 0.0
+        for _ in range(reps):
+            self.restore()
+            r2.r2_sim_prepare(self.desc, self.w.epochs, self.ws)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for j0, j1 in segs:
+                r2.r2_sim_fused_steps(self.desc, self.bufs, j0, j1, self.ws)
+            e1.record()
+            torch.cuda.synchronize()
+            total += e0.elapsed_time(e1)
+        return {"fused": (total / (reps * len(segs)), reps * len(segs))}
 
     def restore(self):
         for b, p in zip(self.bufs, self.pristine):
             b.copy_(p)
 
     def step(self):
-        self.r2.r2_ring_allreduce_sim(self.desc, self.bufs, self.w.epochs, self.ws)
+        self.call.run()
 
     def time_steps(self, steps: int, warmup: int) -> float:
         """Seconds for `steps` back-to-back passes (in place: values grow by R per all-reduce, which
@@ -91,6 +110,8 @@ class Runner:
         events, recorded on the stream the kernels run on, so the figure holds the kernels and the
         dispatch gaps between them, as in the real run.  Returns {kind: (avg_ms, launches)}."""
         torch, r2 = self.torch, self.r2
+        if self.fused:
+            return self._fused_times(reps)
         kinds = [_step_units(self.w, j)[0] for j in range(self.J)]
         groups = []  # (kind, first step, last step)
         for j, k in enumerate(kinds):
@@ -116,6 +137,16 @@ class Runner:
                 total[k] = total.get(k, 0.0) + e0.elapsed_time(e1)
                 count[k] = count.get(k, 0) + n
         return {k: (total[k] / count[k], count[k]) for k in total}
+
+
+def _fused_segments(w):
+    """The step ranges the library launches in the fused schedule: a channel-state change at step c
+    of some slab ends a launch before step c and before step c+1."""
+    T = w.transmissions_per_slab
+    starts = {e[0] % T for e in w.epochs[1:] if e[0] < w.S * T and e[0] % T != 0}
+    cuts = sorted({j for c in starts for j in (c, c + 1) if j < T})
+    edges = [0] + cuts + [w.steps_per_slab]
+    return list(zip(edges[:-1], edges[1:]))
 
 
 def _step_units(w, j):
@@ -170,6 +201,7 @@ def main() -> int:
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg4 or cfg5_tok{1,16,64,256}")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=5)
+    ap.add_argument("--schedule", choices=["auto", "steps", "fused"], default="auto")
     ap.add_argument("--stage-window-mib", type=float, default=0.0,
                     help="stage bytes one launch may write (0 = library default)")
     ap.add_argument("--all", action="store_true", help="also print a table of every configuration to stderr")
@@ -192,7 +224,8 @@ def main() -> int:
 
     w = _workload(args.config)
     xs = wl.make_inputs(w)
-    run = Runner(r2, torch, np, w, xs, int(args.stage_window_mib * (1 << 20)))
+    run = Runner(r2, torch, np, w, xs, int(args.stage_window_mib * (1 << 20)),
+                 {"auto": 0, "steps": 1, "fused": 2}[args.schedule])
 
     # one pass from pristine inputs, kept for the correctness check
     run.step()
@@ -205,15 +238,21 @@ def main() -> int:
 
     # dominant kernel: the fused reducing step that also stages (two reads, two writes per element)
     ktimes = run.kernel_times(args.kernel_reps)
-    dom = "sum" if "sum" in ktimes else "copy"
-    dom_units = 4 if dom == "sum" else 3
-    dom_avg_ms, dom_launches = ktimes[dom]
-    # one fused step moves, for every rank and slab, one ring chunk through dom_units streams; it is
-    # spread over the run's passes, one launch each
-    launch_bytes = dom_units * w.N * w.elem_bytes / run.P
+    if run.fused:
+        dom = "fused"
+        dom_avg_ms, dom_launches = ktimes[dom]
+        launch_bytes = w.algorithmic_bytes / len(_fused_segments(w))
+        kernel_name = "ring_fused_kernel<%s> (stage round trip served by L2: not an HBM figure)" % w.dtype
+    else:
+        dom = "sum" if "sum" in ktimes else "copy"
+        dom_units = 4 if dom == "sum" else 3
+        dom_avg_ms, dom_launches = ktimes[dom]
+        # one fused step moves, for every rank and slab, one ring chunk through dom_units streams; it
+        # is spread over the run's passes, one launch each
+        launch_bytes = dom_units * w.N * w.elem_bytes / run.P
+        kernel_name = {"sum": "ring_step_kernel<Sum%s, staged>" % ("BF16" if w.dtype == "bf16" else "F32"),
+                       "copy": "ring_step_kernel<Copy, staged>"}[dom]
     achieved = launch_bytes / (dom_avg_ms * 1e-3) / 1e9
-    kernel_name = {"sum": "ring_step_kernel<Sum%s, staged>" % ("BF16" if w.dtype == "bf16" else "F32"),
-                   "copy": "ring_step_kernel<Copy, staged>"}[dom]
     traffic = MEASURED_TRAFFIC.get((w.name, dom))
 
     out = {
@@ -233,8 +272,9 @@ def main() -> int:
             "workload": f"{w.name}: R={w.R} simulated ranks, {w.dtype}, {w.N} elements/rank, S={w.S} slab(s), "
                         f"C={w.C} channels, {w.phases}, {w.note}",
             "algorithmic_bytes_per_step": w.algorithmic_bytes,
+            "schedule": "fused columns" if run.fused else "one launch per ring step",
             "passes": run.P,
-            "launches_per_step": run.P * run.J + 1,
+            "launches_per_step": (len(_fused_segments(w)) if run.fused else run.P * run.J) + 1,
         },
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "roofline": {

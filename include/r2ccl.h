@@ -51,6 +51,7 @@ enum {
 typedef enum { R2_F32 = 0, R2_BF16 = 1 } r2_dtype;
 enum { R2_OP_SUM = 0, R2_OP_COPY = 1 };
 enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2 }; /* both = all-reduce */
+enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2 };
 
 /* Static, human-readable text for a return code. */
 const char *r2_strerror(int code);
@@ -160,6 +161,12 @@ typedef struct {
     uint64_t stage_window_bytes; /* stage bytes one launch may write, summed over ranks; 0 = the
                                     library's default (128 MiB, half the Infinity Cache).  Only
                                     changes how the run is cut into passes, never the result.   */
+    int32_t schedule;    /* R2_SCHED_STEPS: one launch per fused step and pass.
+                            R2_SCHED_FUSED: one launch takes every column (2 KiB of each ring chunk)
+                            through all steps between two channel-state changes; needs chunks that
+                            are a multiple of 16 bytes.
+                            R2_SCHED_AUTO (0): FUSED for launch-bound sizes, else STEPS.           */
+    int32_t reserved;    /* 0 */
 } r2_sim_desc;
 
 /* Pure host arithmetic on a descriptor (0 if the descriptor is invalid). */
@@ -191,7 +198,25 @@ uint64_t r2_sim_num_passes(const r2_sim_desc *desc);
 int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint64_t pass, uint32_t step,
                 void *workspace, uint64_t workspace_bytes, void *stream);
 
-/* r2_sim_prepare, then for every pass the steps 0..J-1, in place on the rank buffers. */
+/* Fused-column schedule: the steps [step_begin, step_end) of every rank and slab in ONE launch.  A
+ * workgroup takes a 2 KiB column of the ring chunks of one slab through all these steps, one wave
+ * per rank, with a workgroup barrier between steps; columns are independent of each other and
+ * drift apart in time.  Only valid if, for every slab, the transmissions t of equal parity with
+ * step_begin-1 <= t <= step_end-1 all use one channel state: otherwise a column that is ahead could
+ * overwrite stage data that another column has not read yet.  (An epoch starting at step c of a
+ * slab therefore needs a launch boundary before step c and one before step c+1;
+ * r2_ring_allreduce_sim places them.)  The caller is trusted on this.  Needs the tables of
+ * r2_sim_prepare and chunk sizes that are a multiple of 16 bytes (R2_ERR_INVALID otherwise). */
+int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step_begin,
+                       uint32_t step_end, void *workspace, uint64_t workspace_bytes, void *stream);
+
+/* Which schedule r2_ring_allreduce_sim will use for this descriptor and epoch list: R2_SCHED_STEPS
+ * or R2_SCHED_FUSED (desc->schedule itself unless that is R2_SCHED_AUTO), or a negative R2_ERR code.
+ * Host arithmetic only. */
+int r2_sim_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs);
+
+/* r2_sim_prepare, then the whole ring in place on the rank buffers, by desc->schedule: for every
+ * pass the steps 0..J-1, or fused launches cut wherever a channel state changes mid-slab. */
 int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           const r2_epoch *epochs, uint32_t n_epochs,
                           void *workspace, uint64_t workspace_bytes,

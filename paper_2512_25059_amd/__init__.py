@@ -13,6 +13,10 @@ from .binding import (  # noqa: F401
     PHASE_AR,
     PHASE_RS,
     R2Error,
+    SCHED_AUTO,
+    SCHED_FUSED,
+    SCHED_STEPS,
+    SimCall,
     SimDesc,
     library_path,
     load_library,
@@ -20,10 +24,12 @@ from .binding import (  # noqa: F401
     r2_partition_device,
     r2_reduce_copy,
     r2_ring_allreduce_sim,
+    r2_sim_fused_steps,
     r2_sim_num_passes,
     r2_sim_num_steps,
     r2_sim_num_transmissions,
     r2_sim_prepare,
+    r2_sim_resolve_schedule,
     r2_sim_stage_capacity,
     r2_sim_stage_offset,
     r2_sim_step,

@@ -20,6 +20,7 @@ F32, BF16 = 0, 1
 OP_SUM, OP_COPY = 0, 1
 PHASE_RS, PHASE_AG = 1, 2
 PHASE_AR = PHASE_RS | PHASE_AG
+SCHED_AUTO, SCHED_STEPS, SCHED_FUSED = 0, 1, 2
 
 R2_OK = 0
 R2_ERR_INVALID = -1
@@ -42,7 +43,8 @@ class _Epoch(C.Structure):
 class _SimDesc(C.Structure):
     _fields_ = [("n_ranks", C.c_uint32), ("n_slabs", C.c_uint32), ("n_channels", C.c_uint32),
                 ("align", C.c_uint32), ("n_elems", C.c_uint64), ("dtype", C.c_int32),
-                ("phases", C.c_int32), ("stage_window_bytes", C.c_uint64)]
+                ("phases", C.c_int32), ("stage_window_bytes", C.c_uint64), ("schedule", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -55,10 +57,11 @@ class SimDesc:
     dtype: int
     phases: int
     stage_window_bytes: int = 0  # 0 = library default
+    schedule: int = 0            # SCHED_AUTO
 
     def c(self) -> _SimDesc:
         return _SimDesc(self.n_ranks, self.n_slabs, self.n_channels, self.align, self.n_elems,
-                        self.dtype, self.phases, self.stage_window_bytes)
+                        self.dtype, self.phases, self.stage_window_bytes, self.schedule, 0)
 
 
 _lib = None
@@ -98,6 +101,10 @@ def load_library():
     lib.r2_sim_prepare.argtypes = [pd, vp, u32, vp, u64, vp, vp]
     lib.r2_sim_step.restype = i32
     lib.r2_sim_step.argtypes = [pd, vp, u64, u32, vp, u64, vp]
+    lib.r2_sim_resolve_schedule.restype = i32
+    lib.r2_sim_resolve_schedule.argtypes = [pd, vp, u32]
+    lib.r2_sim_fused_steps.restype = i32
+    lib.r2_sim_fused_steps.argtypes = [pd, vp, u32, u32, vp, u64, vp]
     lib.r2_ring_allreduce_sim.restype = i32
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     _lib = lib
@@ -233,6 +240,47 @@ def r2_sim_step(desc: SimDesc, rank_bufs: Sequence, pass_index: int, step: int, 
     rc = load_library().r2_sim_step(C.byref(desc.c()), p, int(pass_index), int(step), wp, wb, _stream(stream))
     del arr
     _check(rc, "r2_sim_step")
+
+
+def r2_sim_resolve_schedule(desc: SimDesc, epochs) -> int:
+    ep, keep = _epoch_array(epochs)
+    rc = load_library().r2_sim_resolve_schedule(C.byref(desc.c()), C.cast(ep, C.c_void_p), len(epochs))
+    del keep
+    if rc < 0:
+        raise R2Error(rc, "r2_sim_resolve_schedule")
+    return rc
+
+
+class SimCall:
+    """The arguments of r2_ring_allreduce_sim marshalled once, for callers that issue the same
+    collective many times (a serving loop): ``run()`` is then a single foreign call."""
+
+    def __init__(self, desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
+                 offsets_log: Optional[torch.Tensor] = None, stream=None,
+                 workspace_bytes: Optional[int] = None):
+        self._fn = load_library().r2_ring_allreduce_sim
+        self._desc = desc.c()
+        self._bufs, bufs_p = _ptr_array(rank_bufs)
+        self._epochs, self._keep = _epoch_array(epochs)
+        wp, wb = _ws(workspace, workspace_bytes)
+        self._refs = (rank_bufs, workspace, offsets_log)  # keep the device memory alive
+        self._args = (C.byref(self._desc), bufs_p, C.cast(self._epochs, C.c_void_p), len(epochs), wp, wb,
+                      _ptr(offsets_log), _stream(stream))
+
+    def run(self) -> None:
+        rc = self._fn(*self._args)
+        if rc != R2_OK:
+            raise R2Error(rc, "r2_ring_allreduce_sim")
+
+
+def r2_sim_fused_steps(desc: SimDesc, rank_bufs: Sequence, step_begin: int, step_end: int, workspace,
+                       stream=None, workspace_bytes: Optional[int] = None) -> None:
+    arr, p = _ptr_array(rank_bufs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_sim_fused_steps(C.byref(desc.c()), p, int(step_begin), int(step_end), wp, wb,
+                                           _stream(stream))
+    del arr
+    _check(rc, "r2_sim_fused_steps")
 
 
 def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,

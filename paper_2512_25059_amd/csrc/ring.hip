@@ -42,6 +42,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // Addresses are kept as integers; they all point into device (global) memory, and saying so gives
 // global_load/global_store instead of the slower flat (generic address) instructions.
 #define R2_GLOBAL __attribute__((address_space(1)))
+#define R2_LDS __attribute__((address_space(3)))
 template <typename T>
 __device__ inline R2_GLOBAL T *gptr(uint64_t addr)
 {
@@ -371,6 +372,313 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
         [&](unsigned c) { return out_base + c * a.cap; }, nullptr, tin, tout);
 }
 
+// ---------------------------------------------------------------- front end 3: fused columns
+//
+// Element position b of a ring chunk travels round the ring on its own: what step j of rank r does
+// at b depends only on what step j-1 of rank r-1 did at b.  A "column" is a byte range of the ring
+// chunks of one slab, taken through several consecutive steps of ALL ranks by one workgroup: wave w
+// plays rank w (w + 16, ... if there are more ranks than waves), a workgroup barrier separates the
+// steps, and the stage round trip between two steps stays in that compute unit's L2.  One launch
+// then replaces one launch per step.  It is only valid while the channel state of every slab stays
+// the same over the steps of the launch: then a stage location belongs to one column, and columns
+// may drift apart in time without overwriting each other's unread data (see plan_schedule).
+
+constexpr unsigned kColUnroll = 2;                     // vectors per lane: a column is 2 KiB wide
+constexpr unsigned kColBytes = kWave * 16 * kColUnroll;
+constexpr unsigned kMaxFusedWaves = 16;
+
+struct ColInfo {  // the slice of one transmission's table that holds the column's first byte
+    uint64_t lo, hi;
+    uint32_t c, pad;
+};
+
+struct FusedArgs {
+    uint64_t rank_buf[R2_MAX_RANKS];
+    const uint64_t *tables;  // [S*T_slab][C+1]
+    uint64_t stage;          // [2][R][S][C][cap]
+    uint64_t chunk_bytes, cap;
+    uint64_t cols_per_chunk;
+    uint32_t R, S, C, J, T_slab;
+    uint32_t chunk_start;  // 1 when the run is an all-gather alone, else 0
+    uint32_t sum_last;     // last fused step that adds (R-1 in an all-reduce); 0 = none
+    uint32_t j0, j1;       // the steps of this launch: [j0, j1)
+    uint32_t rows_in_lds;  // the table rows of the launch fit the dynamic LDS block
+};
+
+constexpr uint32_t kFusedLdsRowBytes = 48 * 1024;  // at most this much LDS for table rows
+
+// One wave's share of one step on a full-width column, with every choice fixed at compile time so
+// that the code is straight-line: all loads of the step are issued before the first use, and
+// nothing waits for the stores.  KIND: 0 copy-send, 1 sum, 2 copy.  The caller supplies, per vector
+// of the lane, the addresses in the incoming stage, the outgoing stage and the local buffer.
+template <int KIND, bool HAS_OUT, bool BF16>
+__device__ inline void column_step(const uint64_t (&ain)[kColUnroll], const uint64_t (&aout)[kColUnroll],
+                                   const uint64_t (&aloc)[kColUnroll])
+{
+    constexpr bool HAS_IN = KIND != 0, READS_LOCAL = KIND != 2;
+    u32x4 inc[kColUnroll], loc[kColUnroll];
+#pragma unroll
+    for (unsigned u = 0; u < kColUnroll; ++u) {
+        if constexpr (HAS_IN) inc[u] = load16<false>(ain[u]);
+        if constexpr (READS_LOCAL) loc[u] = load16<kNtLocalLoad>(aloc[u]);
+    }
+#pragma unroll
+    for (unsigned u = 0; u < kColUnroll; ++u) {
+        u32x4 v;
+        if constexpr (KIND == 0) v = loc[u];
+        else if constexpr (KIND == 2) v = inc[u];
+        else v = combine<BF16 ? kSumBF16 : kSumF32>(inc[u], loc[u]);
+        if constexpr (HAS_IN) store16<kNtLocalStore>(aloc[u], v);
+        if constexpr (HAS_OUT) store16<false>(aout[u], v);
+    }
+}
+
+// find_channel without a data-dependent branch (every lane runs the same number of rounds, and the
+// lookups of independent vectors interleave): the last c < C with off[c] <= b.  Since off never
+// decreases, that is the slice with off[c+1] > b.  top = the largest power of two below C (0 if C=1).
+template <typename RowPtr>
+__device__ inline uint32_t find_channel_flat(RowPtr off, uint32_t C, uint32_t top, uint64_t b)
+{
+    uint32_t c = 0;
+    for (uint32_t s = top; s; s >>= 1) {
+        const uint32_t m = c + s;
+        const uint32_t mm = m < C ? m : C - 1;
+        c = (m < C && off[mm] <= b) ? m : c;
+    }
+    return c;
+}
+
+#ifdef R2_FUSED_TIMING
+__device__ uint64_t g_dbg[256];
+#define R2_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_dbg[i] = wall_clock64(); } while (0)
+#else
+#define R2_STAMP(i) do {} while (0)
+#endif
+
+template <bool BF16>
+__global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_kernel(const FusedArgs a)
+{
+    R2_STAMP(0);
+    __shared__ ColInfo info[2 * R2_MAX_RANKS];  // by transmission within the slab
+    const uint32_t l = (uint32_t)(blockIdx.x / a.cols_per_chunk);
+    const uint64_t k = blockIdx.x - (uint64_t)l * a.cols_per_chunk;
+    const uint64_t b0 = k * kColBytes;
+    const uint64_t b1 = b0 + kColBytes < a.chunk_bytes ? b0 + kColBytes : a.chunk_bytes;
+    const uint32_t C = a.C;
+    const uint64_t row = (uint64_t)C + 1;
+    const uint64_t *slab_tables = a.tables + (uint64_t)l * a.T_slab * row;
+
+    // The table rows of the transmissions this launch reads or writes, [t_first, t_end), are copied
+    // to LDS when they fit: a column that straddles a cut looks its vectors up there every step.
+    extern __shared__ uint64_t s_rows[];
+    const uint32_t t_first = a.j0 ? a.j0 - 1 : 0;
+    const uint32_t t_end = a.j1 < a.T_slab ? a.j1 : a.T_slab;
+    const uint64_t *rows = slab_tables;  // rows + t * row = table of transmission t
+    if (a.rows_in_lds) {
+        const uint32_t n = (t_end - t_first) * (uint32_t)row;
+        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_rows[i] = slab_tables[(uint64_t)t_first * row + i];
+        __syncthreads();
+        rows = s_rows - (uint64_t)t_first * row;
+    }
+
+    // Which slice holds the column's first byte, for every such transmission.
+    const bool ragged_width = b0 + kColBytes > a.chunk_bytes;  // the chunk's last, narrower column
+    for (uint32_t t = t_first + threadIdx.x; t < t_end; t += blockDim.x) {
+        const uint64_t *off = rows + t * row;
+        const uint32_t c = find_channel(off, C, b0);
+        info[t].lo = off[c];
+        info[t].hi = off[c + 1];
+        info[t].c = c;
+    }
+    __syncthreads();
+    R2_STAMP(1);
+
+    // The wave index is made visibly wave-uniform: everything indexed by rank (the kernel-argument
+    // array of rank buffers above all) then goes through scalar loads and the scalar cache instead
+    // of a vector load from the argument block, which lives in host memory.
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t lane = threadIdx.x % kWave, n_waves = blockDim.x / kWave;
+    const uint64_t per_rank = (uint64_t)a.S * C * a.cap;  // stage bytes of one (parity, rank)
+    const uint64_t slab_stage = a.stage + (uint64_t)l * C * a.cap;
+    auto local_of = [&](uint32_t r, uint32_t j) {
+        const uint32_t chunk = (r + a.chunk_start + 2 * a.R - j) % a.R;
+        return a.rank_buf[r] + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
+    };
+
+    // Straddling columns need the rows in LDS for the fast loop; otherwise they take the slow one.
+    int straddles = 0;
+    if (!a.rows_in_lds)
+        for (uint32_t t = t_first + threadIdx.x; t < t_end; t += blockDim.x)
+            if (b1 > info[t].hi) straddles = 1;
+    const bool slow = ragged_width || __syncthreads_or(straddles);
+    const R2_LDS uint64_t *lds_rows = (const R2_LDS uint64_t *)s_rows;
+
+    if (!slow) {
+        // Full-width column: straight-line steps and barriers only.  Where the column lies inside
+        // one slice of a table its stage delta is uniform; where it straddles a cut every lane
+        // looks its vectors up in the (LDS) row, without branching.
+        uint32_t top = 0;
+        while ((top ? top * 2 : 1) < C) top = top ? top * 2 : 1;
+        uint64_t bu[kColUnroll];
+#pragma unroll
+        for (unsigned u = 0; u < kColUnroll; ++u) bu[u] = b0 + (uint64_t)(u * kWave + lane) * 16;
+
+        // Stage offset (within one rank's stage of one parity) of each of the lane's vectors under
+        // the table of transmission t.
+        auto deltas_for = [&](uint32_t t, uint64_t(&d)[kColUnroll]) {
+            if (b1 <= info[t].hi) {
+                const uint64_t base = (uint64_t)info[t].c * a.cap - info[t].lo;
+#pragma unroll
+                for (unsigned u = 0; u < kColUnroll; ++u) d[u] = base + bu[u];
+            } else {  // only reached with the rows in LDS
+                const R2_LDS uint64_t *off = lds_rows + (uint64_t)(t - t_first) * row;
+#pragma unroll
+                for (unsigned u = 0; u < kColUnroll; ++u) {
+                    const uint32_t c = find_channel_flat(off, C, top, bu[u]);
+                    d[u] = (uint64_t)c * a.cap - off[c] + bu[u];
+                }
+            }
+        };
+        // Two transmissions with the same table have the same offsets (lane c compares entry c).
+        auto same_table = [&](uint32_t ta, uint32_t tb) {
+            if (!a.rows_in_lds) return false;
+            bool eq = true;
+            if (lane < C)
+                eq = lds_rows[(uint64_t)(ta - t_first) * row + lane] == lds_rows[(uint64_t)(tb - t_first) * row + lane];
+            return (bool)__all(eq);
+        };
+
+        // The table a step reads with is the one the step before wrote with, and tables mostly
+        // repeat from step to step, so the offsets are carried along and looked up only on change.
+        uint64_t dcur[kColUnroll];
+        uint32_t t_cur = ~0u;  // the transmission dcur belongs to
+        for (uint32_t j = a.j0; j < a.j1; ++j) {
+            const bool has_in = j > 0, has_out = j + 1 < a.J;
+            const bool summing = has_in && j <= a.sum_last;
+            uint64_t din[kColUnroll], dout[kColUnroll];
+            if (has_in && t_cur != j - 1) {  // first step of the launch
+                deltas_for(j - 1, dcur);
+                t_cur = j - 1;
+            }
+#pragma unroll
+            for (unsigned u = 0; u < kColUnroll; ++u) din[u] = dcur[u];
+            if (has_out) {
+                if (t_cur == ~0u || !same_table(j, t_cur)) deltas_for(j, dcur);
+                t_cur = j;
+            }
+#pragma unroll
+            for (unsigned u = 0; u < kColUnroll; ++u) dout[u] = dcur[u];
+            for (uint32_t rv = wave; rv < a.R; rv += n_waves) {
+                const uint32_t r = __builtin_amdgcn_readfirstlane(rv);
+                const uint32_t peer = (r + a.R - 1) % a.R;
+                const uint64_t local_addr = local_of(r, j);
+                const uint64_t in_base = slab_stage + ((uint64_t)((j + 1) & 1) * a.R + peer) * per_rank;
+                const uint64_t out_base = slab_stage + ((uint64_t)(j & 1) * a.R + r) * per_rank;
+                uint64_t ain[kColUnroll], aout[kColUnroll], aloc[kColUnroll];
+#pragma unroll
+                for (unsigned u = 0; u < kColUnroll; ++u) {
+                    ain[u] = in_base + din[u];
+                    aout[u] = out_base + dout[u];
+                    aloc[u] = local_addr + bu[u];
+                }
+                if (!has_in) {
+                    column_step<0, true, BF16>(ain, aout, aloc);
+                } else if (summing) {
+                    if (has_out) column_step<1, true, BF16>(ain, aout, aloc);
+                    else column_step<1, false, BF16>(ain, aout, aloc);
+                } else {
+                    if (has_out) column_step<2, true, BF16>(ain, aout, aloc);
+                    else column_step<2, false, BF16>(ain, aout, aloc);
+                }
+            }
+            __syncthreads();  // the next step reads what other waves of this workgroup just staged
+            R2_STAMP(2 + j);
+        }
+        return;
+    }
+
+    // The chunk's last column when the chunk is not a whole number of columns (or, if the rows did
+    // not fit LDS, a column that straddles a cut): per-lane bounds and lookups.
+    for (uint32_t j = a.j0; j < a.j1; ++j) {
+        const bool has_in = j > 0, has_out = j + 1 < a.J;
+        const bool summing = has_in && j <= a.sum_last;
+        uint64_t in_lo = 0, out_lo = 0;
+        uint32_t in_c = 0, out_c = 0;
+        bool in_one = true, out_one = true;
+        if (has_in) {
+            in_lo = info[j - 1].lo;
+            in_c = info[j - 1].c;
+            in_one = b1 <= info[j - 1].hi;
+        }
+        if (has_out) {
+            out_lo = info[j].lo;
+            out_c = info[j].c;
+            out_one = b1 <= info[j].hi;
+        }
+        const uint64_t *in_row = rows + (uint64_t)(has_in ? j - 1 : t_first) * row;
+        const uint64_t *out_row = rows + (uint64_t)(has_out ? j : t_first) * row;
+
+        for (uint32_t rv = wave; rv < a.R; rv += n_waves) {
+            const uint32_t r = __builtin_amdgcn_readfirstlane(rv);
+            const uint32_t peer = (r + a.R - 1) % a.R;
+            const uint64_t local_addr = local_of(r, j);
+            const uint64_t in_base = slab_stage + ((uint64_t)((j + 1) & 1) * a.R + peer) * per_rank;
+            const uint64_t out_base = slab_stage + ((uint64_t)(j & 1) * a.R + r) * per_rank;
+
+            u32x4 inc[kColUnroll], loc[kColUnroll];
+#pragma unroll
+            for (unsigned u = 0; u < kColUnroll; ++u) {
+                const uint64_t b = b0 + (uint64_t)(u * kWave + lane) * 16;
+                if (b < b1) {
+                    if (has_in) {
+                        uint64_t d;
+                        if (in_one) {
+                            d = in_base + (uint64_t)in_c * a.cap - in_lo;
+                        } else {
+                            const uint32_t c = find_channel(in_row, C, b);
+                            d = in_base + (uint64_t)c * a.cap - in_row[c];
+                        }
+                        inc[u] = load16<false>(d + b);
+                    }
+                    if (!has_in || summing) loc[u] = load16<kNtLocalLoad>(local_addr + b);
+                }
+            }
+#pragma unroll
+            for (unsigned u = 0; u < kColUnroll; ++u) {
+                const uint64_t b = b0 + (uint64_t)(u * kWave + lane) * 16;
+                if (b < b1) {
+                    u32x4 v;
+                    if (!has_in) v = loc[u];
+                    else if (!summing) v = inc[u];
+                    else v = BF16 ? combine<kSumBF16>(inc[u], loc[u]) : combine<kSumF32>(inc[u], loc[u]);
+                    if (has_in) store16<kNtLocalStore>(local_addr + b, v);
+                    if (has_out) {
+                        uint64_t d;
+                        if (out_one) {
+                            d = out_base + (uint64_t)out_c * a.cap - out_lo;
+                        } else {
+                            const uint32_t c = find_channel(out_row, C, b);
+                            d = out_base + (uint64_t)c * a.cap - out_row[c];
+                        }
+                        store16<false>(d + b, v);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+#ifdef R2_FUSED_TIMING
+}  // namespace
+}  // namespace r2
+extern "C" int r2_debug_read(uint64_t *out, int n)
+{
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(r2::g_dbg), n * 8) == hipSuccess ? 0 : -5;
+}
+namespace r2 {
+namespace {
+#endif
+
 // ---------------------------------------------------------------- host side
 
 // One workgroup per tile of kThreads*kUnroll vectors: consecutive workgroups stream consecutive
@@ -399,6 +707,10 @@ Mode mode_of(bool has_in, int op, int dtype)
 // inside the 256 MiB Infinity Cache lets the read be served from it.
 constexpr uint64_t kDefaultStageWindow = 128ull << 20;
 
+// R2_SCHED_AUTO picks the fused-column schedule when one ring step moves at most this many bytes
+// per stream (summed over ranks and slabs): below it a launch per step is launch-bound.
+constexpr uint64_t kFusedAutoBytes = 8ull << 20;
+
 struct SimShape {
     uint32_t R, S, C, J, T_slab;
     uint64_t chunk_bytes, cap, n_tx;
@@ -420,6 +732,8 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     if (d->align == 0 || d->align % 16 != 0) return R2_ERR_INVALID;
     if (!valid_dtype(d->dtype)) return R2_ERR_INVALID;
     if (d->phases != R2_PHASE_RS && d->phases != R2_PHASE_AG && d->phases != (R2_PHASE_RS | R2_PHASE_AG))
+        return R2_ERR_INVALID;
+    if (d->schedule != R2_SCHED_AUTO && d->schedule != R2_SCHED_STEPS && d->schedule != R2_SCHED_FUSED)
         return R2_ERR_INVALID;
     const uint64_t per = (uint64_t)d->n_slabs * d->n_ranks;
     if (d->n_elems % per != 0) return R2_ERR_INVALID;
@@ -482,6 +796,43 @@ template <Mode M, bool HAS_OUT>
 void launch_step(const StepArgs &a, dim3 grid, hipStream_t st)
 {
     hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT>), grid, dim3(kThreads), 0, st, a);
+}
+
+// The fused-column schedule needs whole 16-byte vectors everywhere and a grid that fits.
+bool fused_eligible(const SimShape &s)
+{
+    if (s.chunk_bytes == 0 || s.chunk_bytes % 16 != 0) return false;
+    const uint64_t cols = (s.chunk_bytes + kColBytes - 1) / kColBytes;
+    return cols * s.S <= 0x7fffffffull;
+}
+
+// Decides between one launch per step and fused columns, and marks the steps before which a fused
+// launch must end.  Inside a fused launch columns drift apart in time, so the data of transmission
+// t (consumed at step t+1) and of transmission t+2 (same stage parity, written at step t+2) may
+// only share a launch if both use the same table.  An epoch that starts at step c of some slab
+// therefore forces a launch boundary before step c and another before step c+1.
+int plan_schedule(const r2_sim_desc *desc, const SimShape &s, const r2_epoch *epochs, uint32_t n_epochs,
+                  bool *cut /* [2*R2_MAX_RANKS] */)
+{
+    uint32_t n_cuts = 0;
+    for (uint32_t j = 0; j < 2 * R2_MAX_RANKS; ++j) cut[j] = false;
+    for (uint32_t i = 1; i < n_epochs && epochs[i].t_start < s.n_tx; ++i) {
+        const uint32_t c = (uint32_t)(epochs[i].t_start % s.T_slab);
+        if (c == 0) continue;  // a slab starts here: its stage buffers are its own
+        for (uint32_t j = c; j <= c + 1 && j < s.T_slab; ++j) {
+            if (!cut[j]) {
+                cut[j] = true;
+                ++n_cuts;
+            }
+        }
+    }
+    if (desc->schedule != R2_SCHED_AUTO) return desc->schedule;
+    if (!fused_eligible(s)) return R2_SCHED_STEPS;
+    // Launch-bound sizes gain from fewer launches; large ones keep one launch per ring step, the
+    // schedule whose stage traffic really goes through memory.
+    const uint64_t step_bytes = (uint64_t)s.R * s.S * s.chunk_bytes;
+    const bool fewer = (uint64_t)(n_cuts + 1) * 2 <= s.n_passes * s.J;
+    return step_bytes <= kFusedAutoBytes && fewer ? R2_SCHED_FUSED : R2_SCHED_STEPS;
 }
 
 template <Mode M, bool HAS_OUT>
@@ -655,6 +1006,61 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     return hip_rc(hipGetLastError());
 }
 
+extern "C" int r2_sim_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs)
+{
+    SimShape s;
+    int rc = shape_of(desc, s);
+    if (rc) return rc;
+    if ((rc = check_epochs(epochs, n_epochs, s))) return rc;
+    if (desc->schedule == R2_SCHED_FUSED && s.chunk_bytes && !fused_eligible(s)) return R2_ERR_INVALID;
+    bool cut[2 * R2_MAX_RANKS];
+    return plan_schedule(desc, s, epochs, n_epochs, cut);
+}
+
+extern "C" int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step_begin,
+                                  uint32_t step_end, void *workspace, uint64_t workspace_bytes,
+                                  void *stream)
+{
+    SimShape s;
+    int rc = shape_of(desc, s);
+    if (rc) return rc;
+    if (!rank_bufs || step_begin >= step_end || step_end > s.J) return R2_ERR_INVALID;
+    if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
+    FusedArgs a{};
+    for (uint32_t r = 0; r < s.R; ++r) {
+        a.rank_buf[r] = reinterpret_cast<uint64_t>(rank_bufs[r]);
+        if (s.chunk_bytes && (!a.rank_buf[r] || (a.rank_buf[r] & 15u))) return R2_ERR_INVALID;
+    }
+    if (s.chunk_bytes == 0) return R2_OK;
+    if (!fused_eligible(s)) return R2_ERR_INVALID;
+    a.tables = static_cast<const uint64_t *>(workspace);
+    a.stage = reinterpret_cast<uint64_t>(workspace) + s.stage_off;
+    a.chunk_bytes = s.chunk_bytes;
+    a.cap = s.cap;
+    a.cols_per_chunk = (s.chunk_bytes + kColBytes - 1) / kColBytes;
+    a.R = s.R;
+    a.S = s.S;
+    a.C = s.C;
+    a.J = s.J;
+    a.T_slab = s.T_slab;
+    a.chunk_start = desc->phases == R2_PHASE_AG ? 1 : 0;
+    a.sum_last = desc->phases == R2_PHASE_AG ? 0 : s.R - 1;
+    a.j0 = step_begin;
+    a.j1 = step_end;
+    const uint32_t t_first = step_begin ? step_begin - 1 : 0;
+    const uint32_t t_end = step_end < s.T_slab ? step_end : s.T_slab;
+    const uint64_t row_bytes = t_end > t_first ? (uint64_t)(t_end - t_first) * (s.C + 1) * 8 : 0;
+    a.rows_in_lds = row_bytes <= kFusedLdsRowBytes;
+    const unsigned lds = a.rows_in_lds ? (unsigned)row_bytes : 0;
+    const unsigned waves = s.R < kMaxFusedWaves ? s.R : kMaxFusedWaves;
+    const dim3 grid((unsigned)(a.cols_per_chunk * s.S)), block(waves * kWave);
+    if (desc->dtype == R2_BF16)
+        hipLaunchKernelGGL((ring_fused_kernel<true>), grid, block, lds, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL((ring_fused_kernel<false>), grid, block, lds, (hipStream_t)stream, a);
+    return hip_rc(hipGetLastError());
+}
+
 extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                                      const r2_epoch *epochs, uint32_t n_epochs, void *workspace,
                                      uint64_t workspace_bytes, uint64_t *offsets_log, void *stream)
@@ -667,8 +1073,24 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
         if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
     }
+    if (desc->schedule == R2_SCHED_FUSED && s.chunk_bytes && !fused_eligible(s)) return R2_ERR_INVALID;
     if ((rc = r2_sim_prepare(desc, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream)))
         return rc;
+    if (s.chunk_bytes == 0) return R2_OK;
+
+    bool cut[2 * R2_MAX_RANKS];
+    const bool fused = plan_schedule(desc, s, epochs, n_epochs, cut) == R2_SCHED_FUSED;
+    if (fused) {
+        uint32_t j0 = 0;
+        for (uint32_t j = 1; j <= s.J; ++j) {
+            if (j == s.J || cut[j]) {
+                if ((rc = r2_sim_fused_steps(desc, rank_bufs, j0, j, workspace, workspace_bytes, stream)))
+                    return rc;
+                j0 = j;
+            }
+        }
+        return R2_OK;
+    }
     for (uint64_t p = 0; p < s.n_passes; ++p)
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;

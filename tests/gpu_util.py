@@ -36,11 +36,12 @@ def to_host(t: torch.Tensor, like: np.ndarray) -> np.ndarray:
     return a.view(like.dtype)
 
 
-def run_gpu_sim(r2, w: wl.Workload, xs, fill_stage: bool = False, stepwise: bool = False, window: int = 0):
+def run_gpu_sim(r2, w: wl.Workload, xs, fill_stage: bool = False, stepwise: bool = False, window: int = 0,
+                schedule: int = 0):
     """Returns (rank buffers as numpy, offsets log [T, C+1] uint64, workspace tensor, desc)."""
     dt = r2.F32 if w.dtype == "f32" else r2.BF16
     ph = {"ar": r2.PHASE_AR, "rs": r2.PHASE_RS, "ag": r2.PHASE_AG}[w.phases]
-    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, dt, ph, window)
+    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, dt, ph, window, schedule)
     bufs = [to_device(x) for x in xs]
     ws_bytes = r2.r2_sim_workspace_bytes(desc)
     assert ws_bytes > 0

@@ -79,7 +79,7 @@ def test_pass_planning(r2):
 @pytest.mark.parametrize("bad", [
     dict(n_ranks=1), dict(n_ranks=65), dict(n_channels=0), dict(n_channels=65), dict(n_slabs=0),
     dict(align=0), dict(align=8), dict(align=24), dict(n_elems=(1 << 20) + 1), dict(dtype=7),
-    dict(phases=0), dict(phases=4), dict(n_slabs=8192, n_elems=8192 * 8 * 4),
+    dict(phases=0), dict(phases=4), dict(n_slabs=8192, n_elems=8192 * 8 * 4), dict(schedule=3),
 ])
 def test_invalid_descriptors(r2, bad):
     base = dict(n_ranks=8, n_slabs=1, n_channels=8, align=256, n_elems=1 << 20, dtype=r2.BF16,

@@ -31,11 +31,13 @@ def _stage_of(ws: torch.Tensor, r2, desc, w):
     return ws[off:off + n].cpu().numpy().reshape(2, w.R, w.S, w.C, cap), cap
 
 
-def _full_compare_small(r2, oracle, w, stepwise=False, window=0, check_stage=True):
+def _full_compare_small(r2, oracle, w, stepwise=False, window=0, check_stage=True, schedule=1):
     _, _, odt, oph = codes(r2, oracle, w)
     xs = wl.make_inputs(w)
-    say(f"sim small {w.name} R={w.R} N={w.N} S={w.S} C={w.C} {w.dtype} {w.phases} stepwise={stepwise}")
-    outs, log, ws, desc = run_gpu_sim(r2, w, xs, fill_stage=True, stepwise=stepwise, window=window)
+    say(f"sim small {w.name} R={w.R} N={w.N} S={w.S} C={w.C} {w.dtype} {w.phases} stepwise={stepwise} "
+        f"window={window} schedule={schedule}")
+    outs, log, ws, desc = run_gpu_sim(r2, w, xs, fill_stage=True, stepwise=stepwise, window=window,
+                                      schedule=schedule)
     stage, cap = _stage_of(ws, r2, desc, w)
     o_bufs = [x.copy() for x in xs]
     o_log, o_stage = oracle.ring_sim(o_bufs, odt, w.S, w.C, w.align, list(w.epochs), oph, cap=cap, stage_fill=FILL)
@@ -64,6 +66,72 @@ SMALL = [
 @pytest.mark.parametrize("make", SMALL, ids=lambda f: f().name)
 def test_sim_small_full_state(r2, oracle, make):
     _full_compare_small(r2, oracle, make())
+
+
+# sizes whose ring chunks are whole 16-byte vectors: the fused-column schedule applies
+SMALL_FUSED = [
+    lambda: wl.scaled(wl.cfg1(), 4 * 4096 * 3 + 4 * 8),        # 3.0 columns of 2 KiB... plus a ragged one
+    lambda: wl.scaled(wl.cfg1(), 4 * 4),                        # one 16-byte vector per chunk
+    lambda: wl.scaled(wl.cfg2(), 8 * 8192 * 2 + 8 * 24),        # state change at t=3: two launches
+    lambda: wl.scaled(wl.cfg3(S=4), 16 * 4 * 5000),             # 16 ranks = 16 waves, epochs at slab starts
+    lambda: wl.scaled(wl.cfg4(S=32), 8 * 32 * 1104),            # flapping: a cut at almost every step
+    lambda: wl.cfg5(1),
+    lambda: wl.cfg5(16),
+    lambda: wl.cfg5(64),
+]
+
+
+@pytest.mark.parametrize("make", SMALL_FUSED, ids=lambda f: f().name)
+def test_sim_fused_schedule_full_state(r2, oracle, make):
+    """One launch takes every 2 KiB column through all steps between two channel-state changes:
+    buffers, log and the whole stage area still match the oracle byte for byte."""
+    _full_compare_small(r2, oracle, make(), schedule=2)
+
+
+@pytest.mark.parametrize("phases", ["rs", "ag", "ar"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("R", [2, 3, 5, 16, 23])
+def test_sim_fused_phases_and_ring_sizes(r2, oracle, phases, dtype, R):
+    """More ranks than the 16 waves of a workgroup, odd ring sizes, all three phase sets."""
+    from dataclasses import replace
+
+    S, C, E = 2, 5, 776  # 776 elements: fp32 3104 B, bf16 1552 B, both multiples of 16
+    T = S * ((2 * R - 2) if phases == "ar" else (R - 1))
+    eps = [(0, 0b00010, (3, 9, 1, 0, 4))]
+    if T > 2:
+        eps.append((T // 2, 0b01001, (3, 9, 1, 7, 4)))
+        eps.append((T - 1, 0, (1, 1, 1, 1, 100)))
+    w = replace(wl.cfg1(), name=f"fused_R{R}_{dtype}_{phases}", R=R, dtype=dtype, N=R * S * E, S=S, C=C,
+                align=32, phases=phases, sigma=1.0, seed=R, epochs=tuple(eps))
+    _full_compare_small(r2, oracle, w, schedule=2)
+
+
+def test_sim_fused_many_columns_state_changes(r2, oracle):
+    """More columns than the GPU holds at once, so that columns really drift apart in time, with
+    channel states that change mid-slab (the launch boundaries around a change are what keeps a
+    column that is ahead from overwriting stage data another column has not read yet)."""
+    from dataclasses import replace
+
+    base = wl.scaled(wl.cfg2(), 8 * (1 << 21))  # 4 MiB chunks: 2048 columns of 8 waves
+    eq = tuple([50000] * 8)
+    for i, eps in enumerate([
+        ((0, 0, eq), (3, 0b00100100, eq)),
+        ((0, 0b1, eq), (1, 0, eq), (2, 0b10, eq), (7, 0b11110000, eq), (13, 0, eq)),
+        ((0, 0, (1, 2, 3, 4, 5, 6, 7, 8)), (5, 0, (8, 7, 6, 5, 4, 3, 2, 1)), (6, 0, (1, 1, 1, 1, 1, 1, 1, 1))),
+    ]):
+        w = replace(base, epochs=eps, name=f"fused_drift{i}")
+        _full_size(r2, oracle, w, schedule=2)
+
+
+def test_sim_fused_needs_whole_vectors(r2):
+    say("sim fused with 20-byte chunks is refused")
+    w = wl.scaled(wl.cfg1(), 4 * 5)
+    xs = wl.make_inputs(w)
+    with pytest.raises(r2.R2Error) as e:
+        run_gpu_sim(r2, w, xs, schedule=2)
+    assert e.value.code == -1
+    outs, _, _, _ = run_gpu_sim(r2, w, xs, schedule=0)  # AUTO falls back to one launch per step
+    assert len(outs) == 4
 
 
 def test_sim_stepwise_equals_one_call(r2, oracle):
@@ -170,12 +238,12 @@ def test_sim_all_failed_touches_nothing(r2):
 
 # ------------------------------------------------------------------ full benchmark sizes
 
-def _full_size(r2, oracle, w, check_bound=False):
+def _full_size(r2, oracle, w, check_bound=False, schedule=0):
     _, _, odt, oph = codes(r2, oracle, w)
     say(f"sim full {w.name}: generating inputs")
     xs = wl.make_inputs(w)
-    say(f"sim full {w.name}: GPU run")
-    outs, log, _, _ = run_gpu_sim(r2, w, xs)
+    say(f"sim full {w.name}: GPU run, schedule={schedule}")
+    outs, log, _, _ = run_gpu_sim(r2, w, xs, schedule=schedule)
     say(f"sim full {w.name}: oracle")
     want = oracle.expected(xs, odt, w.S, oph)
     for r in range(w.R):
@@ -198,6 +266,14 @@ def test_full_cfg1(r2, oracle):
 
 def test_full_cfg2(r2, oracle):
     _full_size(r2, oracle, wl.cfg2(), check_bound=True)
+
+
+def test_full_cfg2_fused(r2, oracle):
+    _full_size(r2, oracle, wl.cfg2(), schedule=2)
+
+
+def test_full_cfg4_fused(r2, oracle):
+    _full_size(r2, oracle, wl.cfg4(), schedule=2)
 
 
 def test_full_cfg3(r2, oracle):
