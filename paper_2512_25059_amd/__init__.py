@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     PHASE_AR,
     PHASE_RS,
     R2Error,
+    ReduceCopyCall,
     SCHED_AUTO,
     SCHED_FUSED,
     SCHED_STEPS,

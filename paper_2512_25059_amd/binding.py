@@ -251,6 +251,27 @@ def r2_sim_resolve_schedule(desc: SimDesc, epochs) -> int:
     return rc
 
 
+class ReduceCopyCall:
+    """The arguments of r2_reduce_copy marshalled once; ``run()`` is a single foreign call."""
+
+    def __init__(self, local: torch.Tensor, dtype: int, op: int, in_stage, in_offsets, out_stage, out_offsets,
+                 n_channels: int, stage_capacity: int, status: Optional[torch.Tensor] = None, stream=None,
+                 nbytes: Optional[int] = None):
+        self._fn = load_library().r2_reduce_copy
+        if nbytes is None:
+            nbytes = local.numel() * local.element_size()
+        self._in, in_p = _ptr_array(in_stage)
+        self._out, out_p = _ptr_array(out_stage)
+        self._refs = (local, in_stage, in_offsets, out_stage, out_offsets, status)
+        self._args = (_ptr(local), int(nbytes), int(dtype), int(op), in_p, _ptr(in_offsets), out_p,
+                      _ptr(out_offsets), int(n_channels), int(stage_capacity), _ptr(status), _stream(stream))
+
+    def run(self) -> None:
+        rc = self._fn(*self._args)
+        if rc != R2_OK:
+            raise R2Error(rc, "r2_reduce_copy")
+
+
 class SimCall:
     """The arguments of r2_ring_allreduce_sim marshalled once, for callers that issue the same
     collective many times (a serving loop): ``run()`` is then a single foreign call."""
