@@ -88,6 +88,29 @@ int r2_partition_device(const uint32_t *weights, const uint64_t *fail_mask, cons
 int r2_partition(const uint32_t *weights, uint64_t fail_mask, uint32_t n_channels, uint64_t bytes,
                  uint32_t align, uint64_t *offsets);
 
+/* In-flight failover plan -- Sec. 4.3 (live migration: every NIC is registered on every buffer, and
+ * send buffers stay intact until completion, so the unfinished part is retransmitted from where it
+ * lies) with the proportional shares of Sec. 5.1.
+ *
+ * A chunk was staged with table `offsets` while the channels of mask_before were down; during the
+ * transmission the channels of mask_after (a superset) are down.  No data moves: for every newly
+ * failed channel f, its slice -- bytes [0, len_f) of stage buffer f -- is shared out over the channels
+ * still healthy by the partition rule above (weights, mask_after, align), so that healthy NIC c
+ * carries bytes [plan[f][c], plan[f][c+1]) of buffer f.  The receiver's layout does not change.
+ *   offsets     device [n_problems][n_channels+1]
+ *   weights     device [n_problems][n_channels]
+ *   mask_before, mask_after  device [n_problems]
+ *   plan        device [n_problems][n_channels][n_channels+1] out; rows of channels that did not
+ *               newly fail, or whose slice is empty, are all zero
+ *   status      device [n_problems], optional; the kernel lowers it to R2_ERR_NO_HEALTHY_CHANNEL if a
+ *               non-empty slice has nobody left to carry it (that row is zero).  It never writes
+ *               R2_OK: clear it beforehand.
+ * One wavefront per (problem, channel); asynchronous; allocates nothing. */
+int r2_rollback_plan_device(const uint64_t *offsets, const uint32_t *weights,
+                            const uint64_t *mask_before, const uint64_t *mask_after,
+                            uint32_t n_channels, uint32_t align, uint32_t n_problems,
+                            uint64_t *plan, int32_t *status, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * (b) Fused reduce-copy on one chunk -- Sec. 2.1 (collective kernels over channels), Sec. 4.3
  *     Technique II (send/receive staging buffers).

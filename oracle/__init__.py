@@ -23,6 +23,7 @@ from .r2_oracle import (  # noqa: F401
     partition,
     reduce_copy,
     ring_sim,
+    rollback_plan,
     set_threads,
     threads,
 )

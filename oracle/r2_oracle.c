@@ -119,6 +119,41 @@ int r2o_partition(const uint32_t *weights, uint64_t fail_mask, uint32_t C,
 }
 
 /* ------------------------------------------------------------------ */
+/* In-flight failover plan (Sec. 4.3 live migration + Sec. 5.1 shares)  */
+/* ------------------------------------------------------------------ */
+/*
+ * A chunk was staged with table `off` while the channels of mask_before were
+ * down.  During the transmission the channels of mask_after (a superset) are
+ * down.  The data stays where it is: every NIC is registered on every stage
+ * buffer and send buffers stay intact until completion (Sec. 4.3, Techniques
+ * I and II), so only the carrier changes.  The slice of each newly failed
+ * channel f, bytes [0, len_f) of stage buffer f, is shared out over the
+ * channels still healthy, in proportion to their bandwidth (Sec. 5.1), by the
+ * same cumulative-floor rule as the partition itself.
+ * plan: C rows of C+1 cut points; row f is relative to the start of slice f,
+ * NIC c carries bytes [plan[f][c], plan[f][c+1]) of buffer f.  Rows of channels
+ * that did not newly fail are all zero.
+ */
+int r2o_rollback_plan(const uint64_t *off, const uint32_t *weights, uint64_t mask_before,
+                      uint64_t mask_after, uint32_t C, uint32_t align, uint64_t *plan)
+{
+    if (!off || !weights || !plan || C == 0 || C > R2O_MAX_CHANNELS || align == 0)
+        return R2O_INVALID;
+    if ((mask_before & ~mask_after) != 0) return R2O_INVALID; /* a recovery is not a rollback */
+    int rc = R2O_OK;
+    for (uint32_t f = 0; f < C; ++f) {
+        uint64_t *row = plan + (uint64_t)f * (C + 1);
+        for (uint32_t c = 0; c <= C; ++c) row[c] = 0;
+        int newly = ((mask_after >> f) & 1u) && !((mask_before >> f) & 1u);
+        uint64_t len = off[f + 1] - off[f];
+        if (!newly || len == 0) continue;
+        int r = r2o_partition(weights, mask_after, C, len, align, row);
+        if (r != R2O_OK) rc = r;
+    }
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
 /* One fused reduce-copy on one chunk (Sec. 2.1 kernels; Sec. 4.3      */
 /* staging buffers)                                                    */
 /* ------------------------------------------------------------------ */

@@ -59,6 +59,9 @@ def _load():
         lib.r2o_partition.restype = C.c_int
         lib.r2o_partition.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint64,
                                       C.c_uint32, C.c_void_p]
+        lib.r2o_rollback_plan.restype = C.c_int
+        lib.r2o_rollback_plan.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint32,
+                                          C.c_uint32, C.c_void_p]
         lib.r2o_reduce_copy.restype = C.c_int
         lib.r2o_reduce_copy.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_int,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -129,6 +132,20 @@ def partition(weights: Sequence[int], fail_mask: int, nbytes: int, align: int) -
     rc = _load().r2o_partition(w.ctypes.data, fail_mask, len(w), nbytes, align, off.ctypes.data)
     _check(rc, "partition")
     return off
+
+
+def rollback_plan(offsets: Sequence[int], weights: Sequence[int], mask_before: int, mask_after: int,
+                  align: int) -> np.ndarray:
+    """Cut points [C, C+1] of every newly failed channel's slice over the channels still healthy."""
+    w = np.ascontiguousarray(weights, dtype=np.uint32)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    n = len(w)
+    assert off.shape == (n + 1,)
+    plan = np.zeros((n, n + 1), dtype=np.uint64)
+    rc = _load().r2o_rollback_plan(off.ctypes.data, w.ctypes.data, mask_before, mask_after, n, align,
+                                   plan.ctypes.data)
+    _check(rc, "rollback_plan")
+    return plan
 
 
 def reduce_copy(local: np.ndarray, dtype: int, op: int,

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     r2_partition,
     r2_partition_device,
     r2_reduce_copy,
+    r2_rollback_plan_device,
     r2_ring_allreduce_sim,
     r2_sim_fused_steps,
     r2_sim_num_passes,

@@ -88,6 +88,8 @@ def load_library():
     lib.r2_partition.argtypes = [vp, u64, u32, u64, u32, vp]
     lib.r2_partition_device.restype = i32
     lib.r2_partition_device.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp]
+    lib.r2_rollback_plan_device.restype = i32
+    lib.r2_rollback_plan_device.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, vp, vp]
     lib.r2_reduce_copy.restype = i32
     lib.r2_reduce_copy.argtypes = [vp, u64, i32, i32, vp, vp, vp, vp, u32, u64, vp, vp]
     pd = C.POINTER(_SimDesc)
@@ -175,6 +177,21 @@ def r2_partition_device(weights: torch.Tensor, fail_mask: torch.Tensor, nbytes: 
     rc = load_library().r2_partition_device(_ptr(weights), _ptr(fail_mask), _ptr(nbytes), n_channels,
                                             int(align), T, _ptr(offsets), _ptr(status), _stream(stream))
     _check(rc, "r2_partition_device")
+
+
+def r2_rollback_plan_device(offsets: torch.Tensor, weights: torch.Tensor, mask_before: torch.Tensor,
+                            mask_after: torch.Tensor, align: int, plan: torch.Tensor,
+                            status: Optional[torch.Tensor] = None, stream=None) -> None:
+    """offsets [T, C+1], weights [T, C], masks [T], plan [T, C, C+1] (8-byte ints except the 4-byte
+    weights), status [T] int32 or None; all on the device."""
+    T, n_channels = weights.shape
+    assert weights.element_size() == 4 and weights.is_contiguous()
+    assert offsets.numel() == T * (n_channels + 1) and plan.numel() == T * n_channels * (n_channels + 1)
+    assert mask_before.numel() == T and mask_after.numel() == T
+    rc = load_library().r2_rollback_plan_device(_ptr(offsets), _ptr(weights), _ptr(mask_before),
+                                                _ptr(mask_after), n_channels, int(align), T, _ptr(plan),
+                                                _ptr(status), _stream(stream))
+    _check(rc, "r2_rollback_plan_device")
 
 
 def r2_reduce_copy(local: torch.Tensor, dtype: int, op: int,

@@ -114,6 +114,34 @@ __global__ __launch_bounds__(kBlock) void partition_epochs_kernel(
                    log ? log + t * (C + 1) : nullptr, nullptr);
 }
 
+// In-flight failover plan: wave (p, f) shares the slice of channel f of problem p out over the
+// channels that are still healthy, if f is among the channels that have just failed.
+__global__ __launch_bounds__(kBlock) void rollback_plan_kernel(
+    const uint64_t *__restrict__ offsets, const uint32_t *__restrict__ weights,
+    const uint64_t *__restrict__ mask_before, const uint64_t *__restrict__ mask_after, uint32_t C,
+    uint32_t align, uint32_t n_problems, uint64_t *__restrict__ plan, int32_t *__restrict__ status)
+{
+    const uint64_t w_id = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (w_id >= (uint64_t)n_problems * C) return;  // whole wavefront leaves together
+    const uint32_t p = (uint32_t)(w_id / C), f = (uint32_t)(w_id - (uint64_t)p * C);
+    const unsigned lane = threadIdx.x & (kWave - 1);
+    const uint64_t before = mask_before[p], after = mask_after[p];
+    const uint64_t *off = offsets + (uint64_t)p * (C + 1);
+    uint64_t *row = plan + ((uint64_t)p * C + f) * (C + 1);
+    const uint64_t len = off[f + 1] - off[f];
+    const bool newly = ((after >> f) & 1u) && !((before >> f) & 1u);
+    if (!newly || len == 0) {
+        if (lane <= C) row[lane] = 0;
+        if (C == kWave && lane == 0) row[C] = 0;
+        return;
+    }
+    const uint32_t w = lane < C ? weights[(uint64_t)p * C + lane] : 0;
+    int32_t st = R2_OK;
+    partition_wave(w, (after >> lane) & 1u, C, len, align, row, nullptr, &st);
+    // a problem's status only ever goes from R2_OK to an error (the caller clears it beforehand)
+    if (lane == 0 && status && st != R2_OK) atomicMin(status + p, st);
+}
+
 }  // namespace
 
 int launch_partition_epochs(const r2_epoch *epochs, uint32_t n_epochs, uint32_t C, uint32_t align,
@@ -159,6 +187,23 @@ extern "C" int r2_partition_device(const uint32_t *weights, const uint64_t *fail
     hipLaunchKernelGGL(r2::partition_arrays_kernel, dim3(blocks), dim3(r2::kBlock), 0,
                        (hipStream_t)stream, weights, fail_mask, bytes, n_channels, align, n_problems,
                        offsets, status);
+    return r2::hip_rc(hipGetLastError());
+}
+
+extern "C" int r2_rollback_plan_device(const uint64_t *offsets, const uint32_t *weights,
+                                       const uint64_t *mask_before, const uint64_t *mask_after,
+                                       uint32_t n_channels, uint32_t align, uint32_t n_problems,
+                                       uint64_t *plan, int32_t *status, void *stream)
+{
+    if (n_channels == 0 || n_channels > R2_MAX_CHANNELS || align == 0) return R2_ERR_INVALID;
+    if (n_problems == 0) return R2_OK;
+    if (!offsets || !weights || !mask_before || !mask_after || !plan) return R2_ERR_INVALID;
+    const uint64_t waves = (uint64_t)n_problems * n_channels;
+    const uint64_t blocks = (waves + r2::kWavesPerBlock - 1) / r2::kWavesPerBlock;
+    if (blocks > 0x7fffffffull) return R2_ERR_OVERFLOW;
+    hipLaunchKernelGGL(r2::rollback_plan_kernel, dim3((unsigned)blocks), dim3(r2::kBlock), 0,
+                       (hipStream_t)stream, offsets, weights, mask_before, mask_after, n_channels, align,
+                       n_problems, plan, status);
     return r2::hip_rc(hipGetLastError());
 }
 
