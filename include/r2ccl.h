@@ -245,6 +245,20 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           void *workspace, uint64_t workspace_bytes,
                           uint64_t *offsets_log, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Bridge-based logical re-ranking -- Sec. 6 "Topology-Aware Logical Re-ranking", Appendix D Alg. 1.
+ *
+ * HOST integer work, no device involved.  `ring` is a permutation of 0..n-1 (the logical ring order);
+ * rails[node] is the set of rails (NICs) node still has, as a bit mask.  The capacity of a ring edge is
+ * the number of rails its ends share; B_global is the smallest rail count of any node.  Edges with
+ * capacity < B_global are repaired, worst gap first (ties in ring order): the first node w (in the
+ * ring's current order, other than the pair u, v) with min(|S_u & S_w|, |S_w & S_v|) >= B_global and
+ * whose own neighbours x, y satisfy |S_x & S_y| >= B_global is moved to sit right after u.  A pair
+ * that is no longer adjacent when its turn comes is skipped.  Writes the new order to out_ring[n] and
+ * the number of relocations to *n_relocated (optional).  R2_ERR_INVALID unless ring is a permutation. */
+int r2_bridge_rerank(const uint32_t *ring, const uint64_t *rails, uint32_t n, uint32_t *out_ring,
+                     uint32_t *n_relocated);
+
 #ifdef __cplusplus
 }
 #endif

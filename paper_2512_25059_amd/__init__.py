@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     SimCall,
     SimDesc,
     library_path,
+    r2_bridge_rerank,
     load_library,
     r2_partition,
     r2_partition_device,

@@ -90,6 +90,8 @@ def load_library():
     lib.r2_partition_device.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp]
     lib.r2_rollback_plan_device.restype = i32
     lib.r2_rollback_plan_device.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, vp, vp]
+    lib.r2_bridge_rerank.restype = i32
+    lib.r2_bridge_rerank.argtypes = [vp, vp, u32, vp, vp]
     lib.r2_reduce_copy.restype = i32
     lib.r2_reduce_copy.argtypes = [vp, u64, i32, i32, vp, vp, vp, vp, u32, u64, vp, vp]
     pd = C.POINTER(_SimDesc)
@@ -177,6 +179,19 @@ def r2_partition_device(weights: torch.Tensor, fail_mask: torch.Tensor, nbytes: 
     rc = load_library().r2_partition_device(_ptr(weights), _ptr(fail_mask), _ptr(nbytes), n_channels,
                                             int(align), T, _ptr(offsets), _ptr(status), _stream(stream))
     _check(rc, "r2_partition_device")
+
+
+def r2_bridge_rerank(ring: Sequence[int], rails: Sequence[int]) -> Tuple[List[int], int]:
+    """Host call: ring is a permutation of 0..n-1, rails[node] a bit mask.  Returns (new ring, relocations)."""
+    n = len(ring)
+    r = (C.c_uint32 * max(n, 1))(*[int(x) for x in ring])
+    m = (C.c_uint64 * max(n, 1))(*[int(x) for x in rails])
+    out = (C.c_uint32 * max(n, 1))()
+    moved = C.c_uint32(0)
+    rc = load_library().r2_bridge_rerank(C.cast(r, C.c_void_p), C.cast(m, C.c_void_p), n,
+                                         C.cast(out, C.c_void_p), C.cast(C.pointer(moved), C.c_void_p))
+    _check(rc, "r2_bridge_rerank")
+    return list(out)[:n], int(moved.value)
 
 
 def r2_rollback_plan_device(offsets: torch.Tensor, weights: torch.Tensor, mask_before: torch.Tensor,

@@ -1,0 +1,135 @@
+"""Bridge-based logical re-ranking (Sec. 6; Appendix D, Algorithm 1): pins for the oracle and
+parity of the product's host implementation against it.  No GPU involved."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle.rerank import bridge_rerank
+
+
+@pytest.fixture(scope="module")
+def r2():
+    import paper_2512_25059_amd as pkg
+    from paper_2512_25059_amd import build as hip_build
+
+    if hip_build.is_stale():
+        hip_build.build()
+    pkg.load_library()
+    return pkg
+
+
+def _narrow_edges(ring, rails):
+    b = min(len(rails[x]) for x in ring)
+    n = len(ring)
+    return sum(1 for i in range(n) if len(rails[ring[i]] & rails[ring[(i + 1) % n]]) < b)
+
+
+def test_paper_scenario_adjacent_nodes_lose_different_rails():
+    """Sec. 6: node A loses rail 1, its neighbour B loses rail 2; their overlap (6 rails) is below what
+    either could sustain (7).  A node with all 8 rails is moved in between: both new edges carry 7."""
+    all8 = set(range(8))
+    rails = {0: all8 - {1}, 1: all8 - {2}, 2: set(all8), 3: set(all8)}
+    ring, moved = bridge_rerank([0, 1, 2, 3], rails)
+    assert moved == 1
+    assert ring == [0, 2, 1, 3]  # pencil: H1 (node 2) qualifies first; its old neighbours B and H2 share 7
+    assert _narrow_edges(ring, rails) == 0
+
+
+def test_healthy_ring_is_left_alone():
+    rails = {i: {0, 1, 2, 3} for i in range(6)}
+    assert bridge_rerank(list(range(6)), rails) == (list(range(6)), 0)
+    rails[3] = {0, 1, 2}  # one degraded node, nobody mismatched: every edge still carries 3 = B_global
+    assert bridge_rerank(list(range(6)), rails) == (list(range(6)), 0)
+
+
+def test_no_bridge_available():
+    """Three nodes: the only other node's neighbours are the broken pair itself."""
+    rails = {0: {0, 1}, 1: {1, 2}, 2: {0, 1, 2}}
+    ring, moved = bridge_rerank([0, 1, 2], rails)
+    assert (ring, moved) == ([0, 1, 2], 0)
+
+
+def test_invariants_exhaustive_tiny():
+    """Every ring of up to 5 nodes over 3 rails (every non-empty rail set per node): the result is a
+    permutation of the input, and every relocation removes at least one narrow edge and creates none."""
+    sets = [set(s) for k in (1, 2, 3) for s in itertools.combinations(range(3), k)]
+    for n in (2, 3, 4, 5):
+        for combo in itertools.product(range(len(sets)), repeat=n):
+            rails = {i: sets[combo[i]] for i in range(n)}
+            ring = list(range(n))
+            out, moved = bridge_rerank(ring, rails)
+            assert sorted(out) == ring
+            before, after = _narrow_edges(ring, rails), _narrow_edges(out, rails)
+            assert after <= before - moved
+            if before == 0:
+                assert out == ring and moved == 0
+
+
+def test_worst_gap_is_repaired_first():
+    """The pair with the largest gap is served first, on the untouched ring: it ends up separated
+    exactly when some node qualifies as its bridge there.  (Its bridge can never be taken away again:
+    closing the gap would re-create the narrow edge.)"""
+    rng = np.random.default_rng(31)
+    checked = 0
+    for _ in range(4000):
+        n = int(rng.integers(4, 10))
+        rails = {i: set(range(6)) - set(int(x) for x in rng.integers(0, 6, size=int(rng.integers(0, 3)))) for i in range(n)}
+        ring = list(range(n))
+        b = min(len(rails[i]) for i in ring)
+        gaps = [(b - len(rails[ring[i]] & rails[ring[(i + 1) % n]]), i) for i in range(n)]
+        worst_gap = max(g for g, _ in gaps)
+        if worst_gap <= 0:
+            continue
+        i = min(i for g, i in gaps if g == worst_gap)
+        u, v = ring[i], ring[(i + 1) % n]
+        feasible = False
+        for k, w in enumerate(ring):
+            if w in (u, v):
+                continue
+            x, y = ring[k - 1], ring[(k + 1) % n]
+            if min(len(rails[u] & rails[w]), len(rails[w] & rails[v])) >= b and len(rails[x] & rails[y]) >= b:
+                feasible = True
+        out, moved = bridge_rerank(ring, rails)
+        still_adjacent = out[(out.index(u) + 1) % n] == v
+        assert still_adjacent == (not feasible)
+        checked += 1
+    assert checked > 500
+
+
+def _as_masks(rails, n):
+    return [sum(1 << r for r in rails[i]) for i in range(n)]
+
+
+def test_product_matches_oracle_exhaustive_tiny(r2):
+    sets = [set(s) for k in (1, 2, 3) for s in itertools.combinations(range(3), k)]
+    for n in (1, 2, 3, 4, 5):
+        for combo in itertools.product(range(len(sets)), repeat=n):
+            rails = {i: sets[combo[i]] for i in range(n)}
+            for ring in ([*range(n)], [*range(n)][::-1]):
+                assert r2.r2_bridge_rerank(ring, _as_masks(rails, n)) == bridge_rerank(ring, rails)
+
+
+def test_product_matches_oracle_random(r2):
+    rng = np.random.default_rng(66)
+    for _ in range(3000):
+        n = int(rng.integers(1, 33))
+        n_rails = int(rng.integers(1, 65))
+        rails = {}
+        for i in range(n):
+            lost = set(int(x) for x in rng.integers(0, n_rails, size=int(rng.integers(0, 3))))
+            s = set(range(n_rails)) - lost
+            rails[i] = s if s else {0}
+        ring = [int(x) for x in rng.permutation(n)]
+        got = r2.r2_bridge_rerank(ring, _as_masks(rails, n))
+        want = bridge_rerank(ring, rails)
+        assert got == want, (ring, rails)
+        assert sorted(got[0]) == sorted(ring)
+        assert _narrow_edges(got[0], rails) <= _narrow_edges(ring, rails) - got[1]
+
+
+def test_product_rejects_non_permutations(r2):
+    for bad in ([0, 0, 1], [0, 1, 3], []):
+        with pytest.raises(r2.R2Error) as e:
+            r2.r2_bridge_rerank(bad, [1] * max(len(bad), 1))
+        assert e.value.code == -1
