@@ -235,6 +235,35 @@ def reduce_copy_sweep(r2, torch, out=sys.stderr):
                 torch.cuda.empty_cache()
 
 
+def split_line(r2, torch, np, wl, out=sys.stderr):
+    """R2CCL-AllReduce on the cfg2 shape: 8 ranks, bf16, 128 MiB per rank, rank 0 has lost half of its
+    NICs (X = 0.5): the planner's share goes through partial all-reduce + broadcast."""
+    w = wl.cfg2()
+    R, N, C = w.R, w.N, w.C
+    use, y, thr = r2.r2_split_plan(R, 1, 0.5)
+    granule = R * (R - 1) * 8 * 64
+    npart = int(round(y * N / granule)) * granule
+    desc = r2.SplitDesc(R, 0, C, w.align, N, npart, r2.BF16)
+    xs = wl.make_inputs(w)
+    bufs = [_to_device(torch, np, x) for x in xs]
+    ws = torch.empty(r2.r2_split_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    weights, mask = [50000] * C, 0b00001111
+    for _ in range(3):
+        r2.r2_split_allreduce_sim(desc, bufs, weights, mask, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = 20
+    for _ in range(n):
+        r2.r2_split_allreduce_sim(desc, bufs, weights, mask, ws)
+    torch.cuda.synchronize()
+    s = (time.perf_counter() - t0) / n
+    e = 2
+    alg = ((7 * R - 6) * (N - npart) + (7 * (R - 1) - 6) * npart + 4 * R * npart) * e
+    print(f"split        X=0.5 -> Y*={y:.4f} (threshold {thr:.4f}), {npart} of {N} elements partial: "
+          f"{s * 1e6:10.1f} us/op  {alg / s / 1e9:9.1f} GB/s  {100 * alg / s / 1e9 / HBM_PEAK_GBPS:6.2f} % of HBM peak "
+          f"({alg} algorithmic bytes)", file=out, flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -373,6 +402,7 @@ def main() -> int:
             print(line, file=sys.stderr, flush=True)
             del rk
             torch.cuda.empty_cache()
+        split_line(r2, torch, np, wl)
     if args.sweep:
         reduce_copy_sweep(r2, torch)
     return 0

@@ -49,7 +49,7 @@ enum {
 #define R2_MAX_RANKS 64
 
 typedef enum { R2_F32 = 0, R2_BF16 = 1 } r2_dtype;
-enum { R2_OP_SUM = 0, R2_OP_COPY = 1 };
+enum { R2_OP_SUM = 0, R2_OP_COPY = 1, R2_OP_SUM_FORWARD = 2 };
 enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2 }; /* both = all-reduce */
 enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2 };
 
@@ -124,6 +124,9 @@ int r2_rollback_plan_device(const uint64_t *offsets, const uint32_t *weights,
  *     op == R2_OP_COPY              : v = incoming
  *     in_stage != NULL              : local <- v
  *     out_stage != NULL             : v is cut by out_offsets and slice c written to out_stage[c]+0
+ *     op == R2_OP_SUM_FORWARD       : as R2_OP_SUM for local, but the outgoing stage gets `incoming`
+ *                                     itself, not the sum (the relay step of the broadcast of
+ *                                     Sec. 5.2); needs both stages
  * in_stage and out_stage may not both be NULL.
  *   local       device, `bytes` bytes (a whole number of elements), 16-byte aligned for full speed;
  *               an address that is only element-aligned is handled one element at a time
@@ -244,6 +247,62 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           const r2_epoch *epochs, uint32_t n_epochs,
                           void *workspace, uint64_t workspace_bytes,
                           uint64_t *offsets_log, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * R2CCL-AllReduce -- Sec. 5.2 ("Partial AllReduce", "R2CCL-AllReduce", "Data Partition Analysis") and
+ * Appendix A.
+ *
+ * Planner (host arithmetic).  n servers of g GPUs; one server has lost the fraction X (0 < X < 1) of
+ * its bandwidth.  With the share Y of the data going through partial all-reduce + broadcast the paper's
+ * completion time (B = D = 1) is T(Y) = max(T1, T2) + T3, T1 = a(1-Y)/(1-X), T2 = bY/X, T3 = Y/X,
+ * a = 2(ng-1)/(ng), b = 2((n-1)g-1)/((n-1)g).  Appendix A: the plain ring is best while
+ * X <= ng/(3ng-2); beyond that T is minimal at Y* = X + X(1-X)/(X + (g(n-1)-1)n).
+ *   r2_split_plan   writes Y* to *y_star, the threshold to *threshold and whether to split
+ *                   (X > threshold, and at least two healthy GPUs remain) to *use_split; any of the
+ *                   three may be NULL.  R2_ERR_INVALID for n < 2, g < 1 or X outside (0, 1).
+ *   r2_split_time   T(Y) as above (no argument checks).
+ * --------------------------------------------------------------------------------------------- */
+int r2_split_plan(uint32_t n_servers, uint32_t gpus_per_server, double lost_fraction,
+                  int32_t *use_split, double *y_star, double *threshold);
+double r2_split_time(uint32_t n_servers, uint32_t gpus_per_server, double lost_fraction, double y);
+
+/* The schedule, over R simulated ranks of which `degraded_rank` d is the one with failed NICs.  Every
+ * rank buffer is cut in two: the first n_elems - n_partial elements go through a global ring
+ * all-reduce over all R ranks (r2_ring_allreduce_sim, channel state of the degraded server, since the
+ * ring passes through it); the last n_partial elements go through
+ *   1. a partial ring all-reduce over the R-1 healthy ranks, taken in ring order d+1, d+2, ...
+ *      (all channels up), and
+ *   2. the tailored broadcast: d stages its own tail; each healthy rank in that order adds it to its
+ *      partial result and relays it unchanged (R2_OP_SUM_FORWARD); the last healthy rank sends its
+ *      finished result back to d, which copies it.  Transfers to or from d are cut by d's channel
+ *      state, transfers between healthy ranks by the full state.
+ * Afterwards every rank holds, in the tail, fold(healthy ranks in ring order) + x_d, rounded to the
+ * buffer type after every addition, and in the head the plain ring all-reduce.
+ * n_partial = 0 is the plain all-reduce.  (n_elems - n_partial) * element size must be a multiple
+ * of 16; the head must divide into n_slabs_global * R chunks and the tail into
+ * n_slabs_partial * (R-1) chunks.  The two stage-1 runs are issued one after the other on `stream`. */
+typedef struct {
+    uint32_t n_ranks;         /* R, 3..R2_MAX_RANKS                          */
+    uint32_t degraded_rank;   /* d < R                                       */
+    uint32_t n_channels;      /* C                                           */
+    uint32_t align;           /* partition alignment, a multiple of 16       */
+    uint64_t n_elems;         /* elements per rank                           */
+    uint64_t n_partial;       /* elements of the tail (partial all-reduce)   */
+    int32_t dtype;            /* r2_dtype                                    */
+    int32_t schedule;         /* R2_SCHED_* for the two ring runs            */
+    uint32_t n_slabs_global;  /* slabs of the global ring run, >= 1          */
+    uint32_t n_slabs_partial; /* slabs of the partial ring run, >= 1         */
+} r2_split_desc;
+
+/* Workspace (device, 256-byte aligned): the two ring workspaces, two offsets tables and a
+ * double-buffered stage for the broadcast.  0 if the descriptor is invalid. */
+uint64_t r2_split_workspace_bytes(const r2_split_desc *desc);
+
+/* weights: HOST array of n_channels bandwidth weights (the same NIC types on every server);
+ * degraded_fail_mask: the NICs server d has lost.  Asynchronous on `stream`; allocates nothing. */
+int r2_split_allreduce_sim(const r2_split_desc *desc, void *const *rank_bufs, const uint32_t *weights,
+                           uint64_t degraded_fail_mask, void *workspace, uint64_t workspace_bytes,
+                           void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Bridge-based logical re-ranking -- Sec. 6 "Topology-Aware Logical Re-ranking", Appendix D Alg. 1.

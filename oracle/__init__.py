@@ -9,6 +9,7 @@ from .r2_oracle import (  # noqa: F401
     F32,
     OP_COPY,
     OP_SUM,
+    OP_SUM_FORWARD,
     PHASE_AG,
     PHASE_AR,
     PHASE_RS,

@@ -39,7 +39,7 @@ enum {
 };
 
 enum { R2O_F32 = 0, R2O_BF16 = 1 };
-enum { R2O_OP_SUM = 0, R2O_OP_COPY = 1 };
+enum { R2O_OP_SUM = 0, R2O_OP_COPY = 1, R2O_OP_SUM_FORWARD = 2 };
 enum { R2O_PHASE_RS = 1, R2O_PHASE_AG = 2 };
 
 #define R2O_MAX_CHANNELS 64
@@ -165,6 +165,9 @@ int r2o_rollback_plan(const uint64_t *off, const uint32_t *weights, uint64_t mas
  *   op == COPY       : v = incoming
  * If something arrived, local <- v.  If out_stage != NULL, v is cut by
  * out_off and slice c is written at offset 0 of out_stage[c].
+ *   op == SUM_FORWARD: local <- incoming + local as for SUM, but what is
+ *                      staged onward is `incoming` itself (the relay step of
+ *                      the broadcast in Sec. 5.2, R2CCL-AllReduce stage 2).
  * cap = capacity in bytes of every stage buffer.
  */
 int r2o_reduce_copy(void *local, uint64_t bytes, int dtype, int op,
@@ -180,16 +183,23 @@ int r2o_reduce_copy(void *local, uint64_t bytes, int dtype, int op,
 
     uint8_t *v = (uint8_t *)malloc(bytes);
     if (!v) return R2O_NOMEM;
+    uint8_t *relay = NULL; /* the untouched incoming data, for SUM_FORWARD */
+    if (op == R2O_OP_SUM_FORWARD) {
+        if (!in_stage || !out_stage) { free(v); return R2O_INVALID; }
+        relay = (uint8_t *)malloc(bytes);
+        if (!relay) { free(v); return R2O_NOMEM; }
+    }
 
     if (in_stage) {
-        if (in_off[0] != 0 || in_off[C] != bytes) { free(v); return R2O_INVALID; }
+        if (in_off[0] != 0 || in_off[C] != bytes) { free(v); free(relay); return R2O_INVALID; }
         for (uint32_t c = 0; c < C; ++c) {
-            if (in_off[c + 1] < in_off[c]) { free(v); return R2O_INVALID; }
+            if (in_off[c + 1] < in_off[c]) { free(v); free(relay); return R2O_INVALID; }
             uint64_t len = in_off[c + 1] - in_off[c];
-            if (len > cap) { free(v); return R2O_CAPACITY; }
+            if (len > cap) { free(v); free(relay); return R2O_CAPACITY; }
             if (len) memcpy(v + in_off[c], in_stage[c], len);
         }
-        if (op == R2O_OP_SUM) {
+        if (relay) memcpy(relay, v, bytes);
+        if (op == R2O_OP_SUM || op == R2O_OP_SUM_FORWARD) {
             int64_t n = (int64_t)(bytes / es);
             if (dtype == R2O_F32) {
                 float *inc = (float *)v;
@@ -211,15 +221,16 @@ int r2o_reduce_copy(void *local, uint64_t bytes, int dtype, int op,
     }
 
     if (out_stage) {
-        if (out_off[0] != 0 || out_off[C] != bytes) { free(v); return R2O_INVALID; }
+        if (out_off[0] != 0 || out_off[C] != bytes) { free(v); free(relay); return R2O_INVALID; }
         for (uint32_t c = 0; c < C; ++c) {
-            if (out_off[c + 1] < out_off[c]) { free(v); return R2O_INVALID; }
+            if (out_off[c + 1] < out_off[c]) { free(v); free(relay); return R2O_INVALID; }
             uint64_t len = out_off[c + 1] - out_off[c];
-            if (len > cap) { free(v); return R2O_CAPACITY; }
-            if (len) memcpy(out_stage[c], v + out_off[c], len);
+            if (len > cap) { free(v); free(relay); return R2O_CAPACITY; }
+            if (len) memcpy(out_stage[c], (relay ? relay : v) + out_off[c], len);
         }
     }
     free(v);
+    free(relay);
     return R2O_OK;
 }
 

@@ -18,7 +18,7 @@ _SRC = os.path.join(_HERE, "r2_oracle.c")
 _LIB = os.path.join(_HERE, "libr2oracle.so")
 
 F32, BF16 = 0, 1
-OP_SUM, OP_COPY = 0, 1
+OP_SUM, OP_COPY, OP_SUM_FORWARD = 0, 1, 2
 PHASE_RS, PHASE_AG = 1, 2
 PHASE_AR = PHASE_RS | PHASE_AG
 

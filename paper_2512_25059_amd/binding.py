@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libr2ccl.so")
 
 F32, BF16 = 0, 1
-OP_SUM, OP_COPY = 0, 1
+OP_SUM, OP_COPY, OP_SUM_FORWARD = 0, 1, 2
 PHASE_RS, PHASE_AG = 1, 2
 PHASE_AR = PHASE_RS | PHASE_AG
 SCHED_AUTO, SCHED_STEPS, SCHED_FUSED = 0, 1, 2
@@ -38,6 +38,13 @@ class R2Error(RuntimeError):
 
 class _Epoch(C.Structure):
     _fields_ = [("t_start", C.c_uint64), ("fail_mask", C.c_uint64), ("weights", C.POINTER(C.c_uint32))]
+
+
+class _SplitDesc(C.Structure):
+    _fields_ = [("n_ranks", C.c_uint32), ("degraded_rank", C.c_uint32), ("n_channels", C.c_uint32),
+                ("align", C.c_uint32), ("n_elems", C.c_uint64), ("n_partial", C.c_uint64),
+                ("dtype", C.c_int32), ("schedule", C.c_int32), ("n_slabs_global", C.c_uint32),
+                ("n_slabs_partial", C.c_uint32)]
 
 
 class _SimDesc(C.Structure):
@@ -62,6 +69,25 @@ class SimDesc:
     def c(self) -> _SimDesc:
         return _SimDesc(self.n_ranks, self.n_slabs, self.n_channels, self.align, self.n_elems,
                         self.dtype, self.phases, self.stage_window_bytes, self.schedule, 0)
+
+
+@dataclass(frozen=True)
+class SplitDesc:
+    n_ranks: int
+    degraded_rank: int
+    n_channels: int
+    align: int
+    n_elems: int
+    n_partial: int
+    dtype: int
+    schedule: int = 0
+    n_slabs_global: int = 1
+    n_slabs_partial: int = 1
+
+    def c(self) -> _SplitDesc:
+        return _SplitDesc(self.n_ranks, self.degraded_rank, self.n_channels, self.align, self.n_elems,
+                          self.n_partial, self.dtype, self.schedule, self.n_slabs_global,
+                          self.n_slabs_partial)
 
 
 _lib = None
@@ -90,6 +116,14 @@ def load_library():
     lib.r2_partition_device.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp]
     lib.r2_rollback_plan_device.restype = i32
     lib.r2_rollback_plan_device.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, vp, vp]
+    lib.r2_split_plan.restype = i32
+    lib.r2_split_plan.argtypes = [u32, u32, C.c_double, vp, vp, vp]
+    lib.r2_split_time.restype = C.c_double
+    lib.r2_split_time.argtypes = [u32, u32, C.c_double, C.c_double]
+    lib.r2_split_workspace_bytes.restype = u64
+    lib.r2_split_workspace_bytes.argtypes = [C.POINTER(_SplitDesc)]
+    lib.r2_split_allreduce_sim.restype = i32
+    lib.r2_split_allreduce_sim.argtypes = [C.POINTER(_SplitDesc), vp, vp, u64, vp, u64, vp]
     lib.r2_bridge_rerank.restype = i32
     lib.r2_bridge_rerank.argtypes = [vp, vp, u32, vp, vp]
     lib.r2_reduce_copy.restype = i32
@@ -179,6 +213,35 @@ def r2_partition_device(weights: torch.Tensor, fail_mask: torch.Tensor, nbytes: 
     rc = load_library().r2_partition_device(_ptr(weights), _ptr(fail_mask), _ptr(nbytes), n_channels,
                                             int(align), T, _ptr(offsets), _ptr(status), _stream(stream))
     _check(rc, "r2_partition_device")
+
+
+def r2_split_plan(n_servers: int, gpus_per_server: int, lost_fraction: float) -> Tuple[bool, float, float]:
+    """Returns (use the split schedule?, Y*, threshold on the lost fraction)."""
+    use, y, thr = C.c_int32(0), C.c_double(0.0), C.c_double(0.0)
+    rc = load_library().r2_split_plan(int(n_servers), int(gpus_per_server), float(lost_fraction),
+                                      C.cast(C.pointer(use), C.c_void_p), C.cast(C.pointer(y), C.c_void_p),
+                                      C.cast(C.pointer(thr), C.c_void_p))
+    _check(rc, "r2_split_plan")
+    return bool(use.value), float(y.value), float(thr.value)
+
+
+def r2_split_time(n_servers: int, gpus_per_server: int, lost_fraction: float, y: float) -> float:
+    return float(load_library().r2_split_time(int(n_servers), int(gpus_per_server), float(lost_fraction), float(y)))
+
+
+def r2_split_workspace_bytes(desc: SplitDesc) -> int:
+    return int(load_library().r2_split_workspace_bytes(C.byref(desc.c())))
+
+
+def r2_split_allreduce_sim(desc: SplitDesc, rank_bufs: Sequence, weights: Sequence[int], degraded_fail_mask: int,
+                           workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    arr, p = _ptr_array(rank_bufs)
+    w = (C.c_uint32 * max(len(weights), 1))(*[int(x) for x in weights])
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_split_allreduce_sim(C.byref(desc.c()), p, C.cast(w, C.c_void_p),
+                                               int(degraded_fail_mask), wp, wb, _stream(stream))
+    del arr
+    _check(rc, "r2_split_allreduce_sim")
 
 
 def r2_bridge_rerank(ring: Sequence[int], rails: Sequence[int]) -> Tuple[List[int], int]:

@@ -191,7 +191,8 @@ struct ChunkJob {
     uint32_t C;
 };
 
-template <Mode M, bool HAS_OUT, typename InPtr, typename OutPtr>
+// FWD (sums only): the outgoing stage gets the incoming data unchanged instead of the sum.
+template <Mode M, bool HAS_OUT, bool FWD = false, typename InPtr, typename OutPtr>
 __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_ptr, int32_t *status,
                                  ChannelTable &tin, ChannelTable &tout)
 {
@@ -252,7 +253,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
             for (unsigned u = 0; u < kUnroll; ++u) {
                 const u32x4 r = combine<M>(inc[u], loc[u]);
                 if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b + u * (kThreads * 16), r);
-                if constexpr (HAS_OUT) store16<kNtStageStore>(sout.delta + b + u * (kThreads * 16), r);
+                if constexpr (HAS_OUT) store16<kNtStageStore>(sout.delta + b + u * (kThreads * 16), FWD ? inc[u] : r);
             }
             continue;
         }
@@ -279,7 +280,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
                 if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b, r);
                 if constexpr (HAS_OUT) {
                     const uint64_t d = out_one ? sout.delta : tout.delta[find_channel(tout.off, C, b)];
-                    store16<kNtStageStore>(d + b, r);
+                    store16<kNtStageStore>(d + b, FWD ? inc[u] : r);
                 }
             }
         }
@@ -307,7 +308,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
         if constexpr (HAS_IN) *gptr<Elem>(local_addr + b) = r;
         if constexpr (HAS_OUT) {
             const uint32_t c = find_channel(tout.off, C, b);
-            *gptr<Elem>(tout.delta[c] + b) = r;
+            *gptr<Elem>(tout.delta[c] + b) = FWD ? x_in : r;
         }
     }
 }
@@ -318,12 +319,12 @@ struct PtrList {
     uint64_t p[R2_MAX_CHANNELS];
 };
 
-template <Mode M, bool HAS_OUT>
+template <Mode M, bool HAS_OUT, bool FWD = false>
 __global__ __launch_bounds__(kThreads) void reduce_copy_kernel(ChunkJob job, const PtrList in_stage,
                                                                const PtrList out_stage, int32_t *status)
 {
     __shared__ ChannelTable tin, tout;
-    run_chunk<M, HAS_OUT>(
+    run_chunk<M, HAS_OUT, FWD>(
         job, [&](unsigned c) { return in_stage.p[c]; }, [&](unsigned c) { return out_stage.p[c]; },
         status, tin, tout);
 }
@@ -835,11 +836,11 @@ int plan_schedule(const r2_sim_desc *desc, const SimShape &s, const r2_epoch *ep
     return step_bytes <= kFusedAutoBytes && fewer ? R2_SCHED_FUSED : R2_SCHED_STEPS;
 }
 
-template <Mode M, bool HAS_OUT>
+template <Mode M, bool HAS_OUT, bool FWD = false>
 void launch_single(const ChunkJob &job, const PtrList &in, const PtrList &out, int32_t *status,
                    unsigned blocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT>), dim3(blocks), dim3(kThreads), 0, st, job, in,
+    hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD>), dim3(blocks), dim3(kThreads), 0, st, job, in,
                        out, status);
 }
 
@@ -854,9 +855,11 @@ extern "C" int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int o
                               uint32_t n_channels, uint64_t stage_capacity, int32_t *status,
                               void *stream)
 {
-    if (!valid_dtype(dtype) || (op != R2_OP_SUM && op != R2_OP_COPY)) return R2_ERR_INVALID;
+    if (!valid_dtype(dtype) || (op != R2_OP_SUM && op != R2_OP_COPY && op != R2_OP_SUM_FORWARD))
+        return R2_ERR_INVALID;
     if (n_channels == 0 || n_channels > R2_MAX_CHANNELS) return R2_ERR_INVALID;
     if (!in_stage && !out_stage) return R2_ERR_INVALID;
+    if (op == R2_OP_SUM_FORWARD && (!in_stage || !out_stage)) return R2_ERR_INVALID;
     if ((in_stage && !in_offsets) || (out_stage && !out_offsets)) return R2_ERR_INVALID;
     if (bytes % elem_bytes(dtype) != 0) return R2_ERR_INVALID;
     if (bytes == 0) return R2_OK;
@@ -881,11 +884,13 @@ extern "C" int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int o
     switch (m) {
     case kSend: launch_single<kSend, true>(job, in, out, status, blocks, st); break;
     case kSumF32:
-        if (has_out) launch_single<kSumF32, true>(job, in, out, status, blocks, st);
+        if (op == R2_OP_SUM_FORWARD) launch_single<kSumF32, true, true>(job, in, out, status, blocks, st);
+        else if (has_out) launch_single<kSumF32, true>(job, in, out, status, blocks, st);
         else launch_single<kSumF32, false>(job, in, out, status, blocks, st);
         break;
     case kSumBF16:
-        if (has_out) launch_single<kSumBF16, true>(job, in, out, status, blocks, st);
+        if (op == R2_OP_SUM_FORWARD) launch_single<kSumBF16, true, true>(job, in, out, status, blocks, st);
+        else if (has_out) launch_single<kSumBF16, true>(job, in, out, status, blocks, st);
         else launch_single<kSumBF16, false>(job, in, out, status, blocks, st);
         break;
     case kCopy:

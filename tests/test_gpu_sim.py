@@ -251,13 +251,13 @@ def _full_size(r2, oracle, w, check_bound=False, schedule=0):
     assert log.tolist() == expected_log(oracle, w).tolist()
     if check_bound and w.dtype == "bf16":
         # acceptance bound against the exact sum, on a sample: normwise 1e-2, and elementwise the
-        # a-priori bound for R-1 roundings of unit 2^-9
+        # a-priori bound for R-1 roundings of unit roundoff 2^-8
         idx = np.random.default_rng(0).integers(0, w.N, size=200000)
         x64 = np.stack([wl.bf16_bits_to_f64(x[idx]) for x in xs])
         exact, absum = x64.sum(axis=0), np.abs(x64).sum(axis=0)
         y = wl.bf16_bits_to_f64(outs[0][idx])
         assert np.linalg.norm(y - exact) / np.linalg.norm(exact) <= 1e-2
-        assert np.all(np.abs(y - exact) <= 1e-2 * np.abs(exact) + (w.R - 1) * 2.0 ** -9 * absum)
+        assert np.all(np.abs(y - exact) <= 1e-2 * np.abs(exact) + (w.R - 1) * 2.0 ** -8 * absum)
 
 
 def test_full_cfg1(r2, oracle):
