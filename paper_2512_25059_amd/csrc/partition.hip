@@ -3,71 +3,10 @@
 // Follows the R2CCL paper, Sec. 5.1 (R2CCL-Balance): the data a server must move is spread over
 // its healthy NICs in proportion to their bandwidth, a failed NIC carries nothing, and the volume
 // itself is unchanged ("Overhead Analysis").  The rounding rule is stated in r2ccl.h.
-#include "r2_internal.h"
+#include "partition_device.h"
 
 namespace r2 {
 namespace {
-
-// floor(r * p / w) for a 128-bit product, by restoring division; needs r*p < w * 2^64.
-__device__ inline uint64_t div128(uint64_t hi, uint64_t lo, uint64_t w)
-{
-    uint64_t rem = hi, quo = 0;
-    for (int i = 63; i >= 0; --i) {
-        const uint64_t carry = rem >> 63;
-        rem = (rem << 1) | ((lo >> i) & 1u);
-        if (carry || rem >= w) {
-            rem -= w;
-            quo |= 1ull << i;
-        }
-    }
-    return quo;
-}
-
-// floor(U * P / W) without overflow, for P <= W, W > 0.  U = q*W + r gives q*P + floor(r*P/W);
-// q*P <= U fits, and r*P < W^2 is divided in 128 bits when it does not fit 64.
-__device__ inline uint64_t mul_div_floor(uint64_t U, uint64_t P, uint64_t W)
-{
-    const uint64_t q = U / W, r = U - q * W;
-    const uint64_t lo = r * P, hi = __umul64hi(r, P);
-    const uint64_t frac = hi == 0 ? lo / W : div128(hi, lo, W);
-    return q * P + frac;
-}
-
-// The whole wavefront partitions one chunk.  Lane c carries channel c's weight (lanes >= C carry
-// nothing).  The cumulative bandwidth in front of each channel is a wavefront-wide inclusive scan.
-__device__ inline void partition_wave(uint32_t weight, bool failed, uint32_t C, uint64_t bytes,
-                                      uint32_t align, uint64_t *row, uint64_t *row2, int32_t *status)
-{
-    const unsigned lane = threadIdx.x & (kWave - 1);
-    const uint64_t e = (lane < C && !failed) ? weight : 0;
-    uint64_t incl = e;
-#pragma unroll
-    for (unsigned d = 1; d < kWave; d <<= 1) {
-        const uint64_t up = __shfl_up(incl, d, kWave);
-        if (lane >= d) incl += up;
-    }
-    const uint64_t W = __shfl(incl, kWave - 1, kWave);
-    const uint64_t P = incl - e;  // bandwidth of the channels before this one
-
-    uint64_t o;
-    if (W == 0) {
-        o = 0;
-    } else if (P == W) {
-        o = bytes;
-    } else {
-        o = (uint64_t)align * mul_div_floor(bytes / align, P, W);
-    }
-    if (lane < C) {
-        row[lane] = o;
-        if (row2) row2[lane] = o;
-    }
-    if (lane == 0) {
-        const uint64_t end = W == 0 ? 0 : bytes;
-        row[C] = end;
-        if (row2) row2[C] = end;
-        if (status) *status = W == 0 ? R2_ERR_NO_HEALTHY_CHANNEL : R2_OK;
-    }
-}
 
 constexpr unsigned kBlock = 256;  // four problems per workgroup
 constexpr unsigned kWavesPerBlock = kBlock / kWave;
@@ -86,27 +25,13 @@ __global__ __launch_bounds__(kBlock) void partition_arrays_kernel(
                    status ? status + p : nullptr);
 }
 
-// Channel states travel by value in the kernel argument block: no host-to-device copy, no
-// allocation.  A batch holds as many epochs as fit.
-constexpr uint32_t kBatchEpochs = 32;
-constexpr uint32_t kBatchWeights = 640;
-
-struct EpochBatch {
-    uint64_t t_start[kBatchEpochs];
-    uint64_t fail_mask[kBatchEpochs];
-    uint32_t weights[kBatchWeights];  // [n][C]
-    uint32_t n;
-};
-
 __global__ __launch_bounds__(kBlock) void partition_epochs_kernel(
     const EpochBatch batch, uint32_t C, uint32_t align, uint64_t bytes, uint64_t t_begin,
     uint64_t t_end, uint64_t *__restrict__ tables, uint64_t *__restrict__ log)
 {
     const uint64_t t = t_begin + (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
     if (t >= t_end) return;  // whole wavefront leaves together
-    uint32_t i = 0;          // state in force at t: the last epoch that started at or before t
-    for (uint32_t k = 1; k < batch.n; ++k)
-        if (batch.t_start[k] <= t) i = k;
+    const uint32_t i = epoch_at(batch, t);
     const unsigned lane = threadIdx.x & (kWave - 1);
     const uint32_t w = lane < C ? batch.weights[i * C + lane] : 0;
     const bool failed = (batch.fail_mask[i] >> lane) & 1u;
@@ -148,7 +73,7 @@ int launch_partition_epochs(const r2_epoch *epochs, uint32_t n_epochs, uint32_t 
                             uint64_t chunk_bytes, uint64_t n_tx, uint64_t *tables, uint64_t *log,
                             hipStream_t stream)
 {
-    const uint32_t per_batch = kBatchWeights / C < kBatchEpochs ? kBatchWeights / C : kBatchEpochs;
+    const uint32_t per_batch = epochs_per_batch(C);
     for (uint32_t i0 = 0; i0 < n_epochs; i0 += per_batch) {
         const uint32_t i1 = i0 + per_batch < n_epochs ? i0 + per_batch : n_epochs;
         const uint64_t t_begin = epochs[i0].t_start;
@@ -156,12 +81,7 @@ int launch_partition_epochs(const r2_epoch *epochs, uint32_t n_epochs, uint32_t 
         uint64_t t_end = i1 < n_epochs ? epochs[i1].t_start : n_tx;
         if (t_end > n_tx) t_end = n_tx;
         EpochBatch b;
-        b.n = i1 - i0;
-        for (uint32_t k = 0; k < b.n; ++k) {
-            b.t_start[k] = epochs[i0 + k].t_start;
-            b.fail_mask[k] = epochs[i0 + k].fail_mask;
-            for (uint32_t c = 0; c < C; ++c) b.weights[k * C + c] = epochs[i0 + k].weights[c];
-        }
+        fill_batch(b, epochs, i0, i1, C);
         const uint64_t n = t_end - t_begin;
         const uint64_t blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
         if (blocks > 0x7fffffffull) return R2_ERR_OVERFLOW;

@@ -9,7 +9,7 @@
 // channel of a vector is found by a short binary search in an LDS copy of the offsets table.
 #include <type_traits>
 
-#include "r2_internal.h"
+#include "partition_device.h"
 
 namespace r2 {
 namespace {
@@ -404,6 +404,9 @@ struct FusedArgs {
     uint32_t sum_last;     // last fused step that adds (R-1 in an all-reduce); 0 = none
     uint32_t j0, j1;       // the steps of this launch: [j0, j1)
     uint32_t rows_in_lds;  // the table rows of the launch fit the dynamic LDS block
+    uint32_t align;        // partition alignment (only used when the kernel partitions itself)
+    uint64_t *tables_out;  // where the first column of each slab records the rows it computed
+    uint64_t *log_out;     // ... and the caller's log, or null
 };
 
 constexpr uint32_t kFusedLdsRowBytes = 48 * 1024;  // at most this much LDS for table rows
@@ -456,8 +459,11 @@ __device__ uint64_t g_dbg[256];
 #define R2_STAMP(i) do {} while (0)
 #endif
 
-template <bool BF16>
-__global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_kernel(const FusedArgs a)
+// PARTITION: the kernel computes the table rows it needs itself, from the channel states in `eb`
+// (every workgroup for its own use, in LDS; the first column of each slab also records them in
+// the workspace and the log), so that no partition launch has to run in front of it.
+template <bool BF16, bool PARTITION>
+__device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
 {
     R2_STAMP(0);
     __shared__ ColInfo info[2 * R2_MAX_RANKS];  // by transmission within the slab
@@ -475,7 +481,29 @@ __global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_kernel(const
     const uint32_t t_first = a.j0 ? a.j0 - 1 : 0;
     const uint32_t t_end = a.j1 < a.T_slab ? a.j1 : a.T_slab;
     const uint64_t *rows = slab_tables;  // rows + t * row = table of transmission t
-    if (a.rows_in_lds) {
+    if constexpr (PARTITION) {  // always with the rows in LDS
+        const uint32_t w_id = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane_id = threadIdx.x % kWave;
+        for (uint32_t t = t_first + w_id; t < t_end; t += blockDim.x / kWave) {
+            const uint64_t tg = (uint64_t)l * a.T_slab + t;  // transmission index of the whole run
+            const uint32_t e = epoch_at(*eb, tg);
+            const uint32_t weight = lane_id < C ? eb->weights[e * C + lane_id] : 0;
+            uint64_t W;
+            const uint64_t o = partition_lane(weight, (eb->fail_mask[e] >> lane_id) & 1u, C, a.chunk_bytes, a.align, &W);
+            uint64_t *lds_row = s_rows + (uint64_t)(t - t_first) * row;
+            if (lane_id < C) lds_row[lane_id] = o;
+            if (lane_id == 0) lds_row[C] = a.chunk_bytes;
+            if (k == 0) {
+                if (lane_id < C) a.tables_out[tg * row + lane_id] = o;
+                if (lane_id == 0) a.tables_out[tg * row + C] = a.chunk_bytes;
+                if (a.log_out) {
+                    if (lane_id < C) a.log_out[tg * row + lane_id] = o;
+                    if (lane_id == 0) a.log_out[tg * row + C] = a.chunk_bytes;
+                }
+            }
+        }
+        __syncthreads();
+        rows = s_rows - (uint64_t)t_first * row;
+    } else if (a.rows_in_lds) {
         const uint32_t n = (t_end - t_first) * (uint32_t)row;
         for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_rows[i] = slab_tables[(uint64_t)t_first * row + i];
         __syncthreads();
@@ -669,6 +697,20 @@ __global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_kernel(const
         __syncthreads();
     }
 }
+template <bool BF16>
+__global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_kernel(const FusedArgs a)
+{
+    fused_body<BF16, false>(a, nullptr);
+}
+
+static_assert(sizeof(FusedArgs) + sizeof(EpochBatch) <= 4000, "kernel arguments must fit 4 KiB");
+
+template <bool BF16>
+__global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_partition_kernel(const FusedArgs a, const EpochBatch eb)
+{
+    fused_body<BF16, true>(a, &eb);
+}
+
 #ifdef R2_FUSED_TIMING
 }  // namespace
 }  // namespace r2
@@ -1022,23 +1064,31 @@ extern "C" int r2_sim_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *
     return plan_schedule(desc, s, epochs, n_epochs, cut);
 }
 
-extern "C" int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step_begin,
-                                  uint32_t step_end, void *workspace, uint64_t workspace_bytes,
-                                  void *stream)
+namespace r2 {
+namespace {
+
+// LDS bytes for the table rows of the steps [step_begin, step_end), or 0 if they do not fit.
+uint32_t fused_row_bytes(const SimShape &s, uint32_t step_begin, uint32_t step_end)
 {
-    SimShape s;
-    int rc = shape_of(desc, s);
-    if (rc) return rc;
-    if (!rank_bufs || step_begin >= step_end || step_end > s.J) return R2_ERR_INVALID;
-    if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
+    const uint32_t t_first = step_begin ? step_begin - 1 : 0;
+    const uint32_t t_end = step_end < s.T_slab ? step_end : s.T_slab;
+    const uint64_t row_bytes = t_end > t_first ? (uint64_t)(t_end - t_first) * (s.C + 1) * 8 : 8;
+    return row_bytes <= kFusedLdsRowBytes ? (uint32_t)row_bytes : 0;
+}
+
+// One fused launch.  With `eb` the kernel partitions on its own (needs the rows to fit LDS).
+int launch_fused(const r2_sim_desc *desc, const SimShape &s, void *const *rank_bufs, uint32_t step_begin,
+                 uint32_t step_end, void *workspace, const EpochBatch *eb, uint64_t *log, hipStream_t stream)
+{
     FusedArgs a{};
     for (uint32_t r = 0; r < s.R; ++r) {
         a.rank_buf[r] = reinterpret_cast<uint64_t>(rank_bufs[r]);
-        if (s.chunk_bytes && (!a.rank_buf[r] || (a.rank_buf[r] & 15u))) return R2_ERR_INVALID;
+        if (!a.rank_buf[r] || (a.rank_buf[r] & 15u)) return R2_ERR_INVALID;
     }
-    if (s.chunk_bytes == 0) return R2_OK;
-    if (!fused_eligible(s)) return R2_ERR_INVALID;
     a.tables = static_cast<const uint64_t *>(workspace);
+    a.tables_out = static_cast<uint64_t *>(workspace);
+    a.log_out = log;
+    a.align = desc->align;
     a.stage = reinterpret_cast<uint64_t>(workspace) + s.stage_off;
     a.chunk_bytes = s.chunk_bytes;
     a.cap = s.cap;
@@ -1052,18 +1102,44 @@ extern "C" int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_buf
     a.sum_last = desc->phases == R2_PHASE_AG ? 0 : s.R - 1;
     a.j0 = step_begin;
     a.j1 = step_end;
-    const uint32_t t_first = step_begin ? step_begin - 1 : 0;
-    const uint32_t t_end = step_end < s.T_slab ? step_end : s.T_slab;
-    const uint64_t row_bytes = t_end > t_first ? (uint64_t)(t_end - t_first) * (s.C + 1) * 8 : 0;
-    a.rows_in_lds = row_bytes <= kFusedLdsRowBytes;
-    const unsigned lds = a.rows_in_lds ? (unsigned)row_bytes : 0;
+    const uint32_t lds = fused_row_bytes(s, step_begin, step_end);
+    a.rows_in_lds = lds != 0;
+    if (eb && !lds) return R2_ERR_INVALID;
     const unsigned waves = s.R < kMaxFusedWaves ? s.R : kMaxFusedWaves;
     const dim3 grid((unsigned)(a.cols_per_chunk * s.S)), block(waves * kWave);
-    if (desc->dtype == R2_BF16)
-        hipLaunchKernelGGL((ring_fused_kernel<true>), grid, block, lds, (hipStream_t)stream, a);
-    else
-        hipLaunchKernelGGL((ring_fused_kernel<false>), grid, block, lds, (hipStream_t)stream, a);
+    if (eb) {
+        if (desc->dtype == R2_BF16)
+            hipLaunchKernelGGL((ring_fused_partition_kernel<true>), grid, block, lds, stream, a, *eb);
+        else
+            hipLaunchKernelGGL((ring_fused_partition_kernel<false>), grid, block, lds, stream, a, *eb);
+    } else {
+        if (desc->dtype == R2_BF16)
+            hipLaunchKernelGGL((ring_fused_kernel<true>), grid, block, lds, stream, a);
+        else
+            hipLaunchKernelGGL((ring_fused_kernel<false>), grid, block, lds, stream, a);
+    }
     return hip_rc(hipGetLastError());
+}
+
+}  // namespace
+}  // namespace r2
+
+extern "C" int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step_begin,
+                                  uint32_t step_end, void *workspace, uint64_t workspace_bytes,
+                                  void *stream)
+{
+    SimShape s;
+    int rc = shape_of(desc, s);
+    if (rc) return rc;
+    if (!rank_bufs || step_begin >= step_end || step_end > s.J) return R2_ERR_INVALID;
+    if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
+    if (s.chunk_bytes == 0) {
+        for (uint32_t r = 0; r < s.R; ++r)
+            if (reinterpret_cast<uint64_t>(rank_bufs[r]) & 15u) return R2_ERR_INVALID;
+        return R2_OK;
+    }
+    if (!fused_eligible(s)) return R2_ERR_INVALID;
+    return launch_fused(desc, s, rank_bufs, step_begin, step_end, workspace, nullptr, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
@@ -1079,23 +1155,39 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
     }
     if (desc->schedule == R2_SCHED_FUSED && s.chunk_bytes && !fused_eligible(s)) return R2_ERR_INVALID;
-    if ((rc = r2_sim_prepare(desc, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream)))
-        return rc;
-    if (s.chunk_bytes == 0) return R2_OK;
+    if ((rc = check_epochs(epochs, n_epochs, s))) return rc;
+    if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
 
     bool cut[2 * R2_MAX_RANKS];
-    const bool fused = plan_schedule(desc, s, epochs, n_epochs, cut) == R2_SCHED_FUSED;
+    const bool fused = s.chunk_bytes && plan_schedule(desc, s, epochs, n_epochs, cut) == R2_SCHED_FUSED;
     if (fused) {
+        // The fused kernels partition for themselves if the whole epoch list fits one argument
+        // block and every launch's rows fit LDS; otherwise the tables are prepared up front.
+        bool self = n_epochs <= epochs_per_batch(s.C);
         uint32_t j0 = 0;
+        for (uint32_t j = 1; j <= s.J && self; ++j)
+            if (j == s.J || cut[j]) {
+                self = fused_row_bytes(s, j0, j) != 0;
+                j0 = j;
+            }
+        EpochBatch eb;
+        if (self) fill_batch(eb, epochs, 0, n_epochs, s.C);
+        else if ((rc = r2_sim_prepare(desc, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream)))
+            return rc;
+        j0 = 0;
         for (uint32_t j = 1; j <= s.J; ++j) {
             if (j == s.J || cut[j]) {
-                if ((rc = r2_sim_fused_steps(desc, rank_bufs, j0, j, workspace, workspace_bytes, stream)))
+                if ((rc = launch_fused(desc, s, rank_bufs, j0, j, workspace, self ? &eb : nullptr,
+                                       self ? offsets_log : nullptr, (hipStream_t)stream)))
                     return rc;
                 j0 = j;
             }
         }
         return R2_OK;
     }
+    if ((rc = r2_sim_prepare(desc, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream)))
+        return rc;
+    if (s.chunk_bytes == 0) return R2_OK;
     for (uint64_t p = 0; p < s.n_passes; ++p)
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
