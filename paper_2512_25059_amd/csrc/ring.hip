@@ -534,13 +534,27 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         return a.rank_buf[r] + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
     };
 
+    // changed[t]: the table of transmission t differs from that of t-1 (lane c compares entry c).
+    // Tables mostly repeat, and then the stage offsets of a step can be carried over.
+    __shared__ uint32_t changed[2 * R2_MAX_RANKS];
+    const R2_LDS uint64_t *lds_rows = (const R2_LDS uint64_t *)s_rows;
+    for (uint32_t t = t_first + wave; t < t_end; t += n_waves) {
+        bool eq = false;
+        if (a.rows_in_lds && t > t_first) {
+            eq = true;
+            if (lane < C)
+                eq = lds_rows[(uint64_t)(t - t_first) * row + lane] == lds_rows[(uint64_t)(t - 1 - t_first) * row + lane];
+            eq = __all(eq);
+        }
+        if (lane == 0) changed[t] = !eq;
+    }
+
     // Straddling columns need the rows in LDS for the fast loop; otherwise they take the slow one.
     int straddles = 0;
     if (!a.rows_in_lds)
         for (uint32_t t = t_first + threadIdx.x; t < t_end; t += blockDim.x)
             if (b1 > info[t].hi) straddles = 1;
     const bool slow = ragged_width || __syncthreads_or(straddles);
-    const R2_LDS uint64_t *lds_rows = (const R2_LDS uint64_t *)s_rows;
 
     if (!slow) {
         // Full-width column: straight-line steps and barriers only.  Where the column lies inside
@@ -568,56 +582,65 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                 }
             }
         };
-        // Two transmissions with the same table have the same offsets (lane c compares entry c).
-        auto same_table = [&](uint32_t ta, uint32_t tb) {
-            if (!a.rows_in_lds) return false;
-            bool eq = true;
-            if (lane < C)
-                eq = lds_rows[(uint64_t)(ta - t_first) * row + lane] == lds_rows[(uint64_t)(tb - t_first) * row + lane];
-            return (bool)__all(eq);
+        // One rank's share of step j, given where its chunk and its stages are.
+        auto rank_step = [&](bool has_in, bool has_out, bool summing, uint64_t local_addr,
+                             uint64_t in_base, uint64_t out_base, const uint64_t(&din)[kColUnroll],
+                             const uint64_t(&dout)[kColUnroll]) {
+            uint64_t ain[kColUnroll], aout[kColUnroll], aloc[kColUnroll];
+#pragma unroll
+            for (unsigned u = 0; u < kColUnroll; ++u) {
+                ain[u] = in_base + din[u];
+                aout[u] = out_base + dout[u];
+                aloc[u] = local_addr + bu[u];
+            }
+            if (!has_in) {
+                column_step<0, true, BF16>(ain, aout, aloc);
+            } else if (summing) {
+                if (has_out) column_step<1, true, BF16>(ain, aout, aloc);
+                else column_step<1, false, BF16>(ain, aout, aloc);
+            } else {
+                if (has_out) column_step<2, true, BF16>(ain, aout, aloc);
+                else column_step<2, false, BF16>(ain, aout, aloc);
+            }
         };
+
+        // When a wave plays one rank, what it needs per step is hoisted out of the step loop: the
+        // slab of its buffer, its own stage and its predecessor's (parity 0; parity 1 is R ranks
+        // further), and the ring chunk it is at, which goes one down per step.
+        const bool one_rank = a.R <= n_waves;
+        const uint32_t my_peer = (wave + a.R - 1) % a.R;
+        const uint64_t my_slab = a.rank_buf[wave] + (uint64_t)l * a.R * a.chunk_bytes;
+        const uint64_t my_in0 = slab_stage + (uint64_t)my_peer * per_rank;
+        const uint64_t my_out0 = slab_stage + (uint64_t)wave * per_rank;
+        const uint64_t parity_stride = (uint64_t)a.R * per_rank;
+        uint32_t my_chunk = (wave + a.chunk_start + 2 * a.R - a.j0) % a.R;
 
         // The table a step reads with is the one the step before wrote with, and tables mostly
         // repeat from step to step, so the offsets are carried along and looked up only on change.
         uint64_t dcur[kColUnroll];
-        uint32_t t_cur = ~0u;  // the transmission dcur belongs to
+        bool have = false;  // dcur holds the offsets of the previous transmission
         for (uint32_t j = a.j0; j < a.j1; ++j) {
             const bool has_in = j > 0, has_out = j + 1 < a.J;
             const bool summing = has_in && j <= a.sum_last;
             uint64_t din[kColUnroll], dout[kColUnroll];
-            if (has_in && t_cur != j - 1) {  // first step of the launch
-                deltas_for(j - 1, dcur);
-                t_cur = j - 1;
-            }
+            if (has_in && !have) deltas_for(j - 1, dcur);  // first step of the launch
 #pragma unroll
             for (unsigned u = 0; u < kColUnroll; ++u) din[u] = dcur[u];
-            if (has_out) {
-                if (t_cur == ~0u || !same_table(j, t_cur)) deltas_for(j, dcur);
-                t_cur = j;
-            }
+            if (has_out && (!(has_in || have) || changed[j])) deltas_for(j, dcur);
+            have = true;
 #pragma unroll
             for (unsigned u = 0; u < kColUnroll; ++u) dout[u] = dcur[u];
-            for (uint32_t rv = wave; rv < a.R; rv += n_waves) {
-                const uint32_t r = __builtin_amdgcn_readfirstlane(rv);
-                const uint32_t peer = (r + a.R - 1) % a.R;
-                const uint64_t local_addr = local_of(r, j);
-                const uint64_t in_base = slab_stage + ((uint64_t)((j + 1) & 1) * a.R + peer) * per_rank;
-                const uint64_t out_base = slab_stage + ((uint64_t)(j & 1) * a.R + r) * per_rank;
-                uint64_t ain[kColUnroll], aout[kColUnroll], aloc[kColUnroll];
-#pragma unroll
-                for (unsigned u = 0; u < kColUnroll; ++u) {
-                    ain[u] = in_base + din[u];
-                    aout[u] = out_base + dout[u];
-                    aloc[u] = local_addr + bu[u];
-                }
-                if (!has_in) {
-                    column_step<0, true, BF16>(ain, aout, aloc);
-                } else if (summing) {
-                    if (has_out) column_step<1, true, BF16>(ain, aout, aloc);
-                    else column_step<1, false, BF16>(ain, aout, aloc);
-                } else {
-                    if (has_out) column_step<2, true, BF16>(ain, aout, aloc);
-                    else column_step<2, false, BF16>(ain, aout, aloc);
+            if (one_rank) {
+                rank_step(has_in, has_out, summing, my_slab + (uint64_t)my_chunk * a.chunk_bytes,
+                          my_in0 + ((j + 1) & 1 ? parity_stride : 0), my_out0 + (j & 1 ? parity_stride : 0), din, dout);
+                my_chunk = my_chunk ? my_chunk - 1 : a.R - 1;
+            } else {
+                for (uint32_t rv = wave; rv < a.R; rv += n_waves) {
+                    const uint32_t r = __builtin_amdgcn_readfirstlane(rv);
+                    const uint32_t peer = (r + a.R - 1) % a.R;
+                    rank_step(has_in, has_out, summing, local_of(r, j),
+                              slab_stage + ((uint64_t)((j + 1) & 1) * a.R + peer) * per_rank,
+                              slab_stage + ((uint64_t)(j & 1) * a.R + r) * per_rank, din, dout);
                 }
             }
             __syncthreads();  // the next step reads what other waves of this workgroup just staged
