@@ -1,0 +1,58 @@
+"""The entry points only enqueue kernels on the caller's stream (no allocation, no copy, no wait), so a
+whole ring run can be captured in a HIP graph and replayed.  Every replay is checked against the
+oracle, with ordinary eager work and synchronisations in between."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import codes, say, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def r2():
+    import paper_2512_25059_amd as pkg
+
+    pkg.load_library()
+    assert torch.cuda.is_available()
+    return pkg
+
+
+@pytest.mark.parametrize("schedule", [1, 2])
+def test_ring_run_in_a_graph(r2, oracle, schedule):
+    w = wl.scaled(wl.cfg2(), 8 * 8192 * 4)
+    dt, ph, odt, oph = codes(r2, oracle, w)
+    xs = wl.make_inputs(w)
+    want = oracle.expected(xs, odt, w.S, oph)
+    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, dt, ph, 0, schedule)
+    pristine = [to_device(x) for x in xs]
+    bufs = [p.clone() for p in pristine]
+    ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    log = torch.zeros((r2.r2_sim_num_transmissions(desc), w.C + 1), dtype=torch.int64, device="cuda")
+
+    say(f"graph capture, schedule={schedule}")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        r2.r2_ring_allreduce_sim(desc, bufs, w.epochs, ws, log)  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        r2.r2_ring_allreduce_sim(desc, bufs, w.epochs, ws, log)
+    for replay in range(4):
+        say(f"graph replay {replay}")
+        for b, p in zip(bufs, pristine):
+            b.copy_(p)                                   # eager work between replays
+        log.zero_()
+        junk = torch.randn(1 << 16, device="cuda").sum()  # library kernels in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for r in range(w.R):
+            got = bufs[r].cpu().numpy().view(xs[r].dtype)
+            assert np.array_equal(got, want[r]), f"replay {replay}, rank {r}"
+        assert log.cpu().numpy().any()
