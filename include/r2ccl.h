@@ -305,6 +305,98 @@ int r2_split_allreduce_sim(const r2_split_desc *desc, void *const *rank_bufs, co
                            void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Recursive R2CCL-AllReduce and the strategy selector -- Sec. 6 "Recursive R2CCL-AllReduce", built
+ * on the two-ring analysis of Sec. 5.2.
+ *
+ * With several failures the servers form a spectrum of bandwidths.  A global ring runs at the
+ * slowest server's rate; that server is then left out and a faster sub-ring formed from the rest,
+ * and so on; each ring reduces a share of the data that matches the bandwidth it adds; all
+ * reductions run in parallel and the broadcasts follow (Sec. 6).  The paper gives no pseudo-code:
+ * the rules below are this library's reading, chosen so that one degraded server gives back the
+ * two-ring schedule of Sec. 5.2 exactly.
+ *
+ * Plan (HOST, integer and double arithmetic): rank r's own bandwidth is the weight of the channels it
+ * still has.  Level 0 holds all ranks.  The next level drops every rank whose own bandwidth is the
+ * smallest among the current members, as long as two ranks remain; a level's ring runs on the
+ * channels that are up at ALL its members (fail_mask = union of the members' failed channels), its
+ * bandwidth is their weight, its increment the gain over the previous level; a peel that gains
+ * nothing makes no level and the peeling goes on.  share_k is proportional to
+ * increment_k / (2(p_k-1)/p_k), p_k = members_k * gpus_per_rank, so that all rings finish together
+ * when latency is ignored (for two levels: T1 = T2 of Sec. 5.2).
+ * R2_ERR_NO_HEALTHY_CHANNEL if no channel is up at every rank. */
+#define R2_MAX_LEVELS 16
+
+typedef struct {
+    uint64_t members;   /* bit r: rank r takes part in this level's ring           */
+    uint64_t fail_mask; /* channel state of the level's ring                       */
+    uint64_t bandwidth; /* weight of the channels healthy under fail_mask          */
+    uint64_t increment; /* bandwidth minus the previous level's (level 0: itself)  */
+    double share;       /* fraction of the data this level reduces                 */
+} r2_level;
+
+/* weights: HOST [n_channels]; fail_masks: HOST [n_ranks]; levels: HOST, room for max_levels
+ * (1..R2_MAX_LEVELS; the peeling stops there); *n_levels receives the count. */
+int r2_recursive_plan(uint32_t n_ranks, uint32_t gpus_per_rank, uint32_t n_channels, const uint32_t *weights,
+                      const uint64_t *fail_masks, uint32_t max_levels, r2_level *levels, uint32_t *n_levels);
+
+/* alpha-beta completion time of a plan (Sec. 6, last paragraph; Sec. 8 "AllReduce performance"):
+ *   max_k [ 2(p_k-1) alpha + 2(p_k-1)/p_k * share_k * bytes / (increment_k * beta) ]
+ * + max_{k>=1} [ hops_k * alpha + share_k * bytes / (increment_k * beta) ],
+ * hops_k = members_k + 2 * (n_ranks - members_k) - 1 (the broadcast chain), beta = bytes per second
+ * per unit of weight.  With alpha = 0 and two levels this is T(Y) = max(T1, T2) + T3 of Sec. 5.2;
+ * one level is the plain ring at the slowest server's balanced rate (R2CCL-Balance).
+ * Negative if an argument is invalid. */
+double r2_recursive_time(uint32_t n_ranks, uint32_t gpus_per_rank, const r2_level *levels, uint32_t n_levels,
+                         double bytes, double alpha, double beta);
+
+/* The selector: plans every depth 0..D (depth = levels - 1; D = the full peel, at most
+ * R2_MAX_LEVELS - 1) and returns in *depth the one with the smallest modelled time, the shallower on a
+ * tie.  Depth 0 is R2CCL-Balance, depth 1 with one degraded server is R2CCL-AllReduce.  times
+ * (optional, HOST, R2_MAX_LEVELS doubles) receives the modelled time of every depth, *n_depths
+ * (optional) their count. */
+int r2_select_strategy(uint32_t n_ranks, uint32_t gpus_per_rank, uint32_t n_channels, const uint32_t *weights,
+                       const uint64_t *fail_masks, double bytes, double alpha, double beta,
+                       uint32_t *depth, double *times, uint32_t *n_depths);
+
+/* The schedule on simulated ranks (a rank stands for a server).  Every rank buffer is cut into
+ * n_levels consecutive segments of level_elems[k] elements.  Segment k goes through
+ *   1. a ring all-reduce over level k's members under the level's channel state, the members taken
+ *      in ring order starting after the highest-numbered excluded rank (level 0: ranks 0..R-1), and,
+ *   2. if the level excludes ranks, the broadcast chain: the excluded ranks, in ascending order,
+ *      add their segments up hop by hop; each member in the order above adds that sum to its ring
+ *      result and relays it unchanged (R2_OP_SUM_FORWARD); the last member sends its finished result
+ *      on, and the excluded ranks copy it and pass it along in ascending order.  The transfer between
+ *      two ranks is cut by the union of their failed channels.
+ * Afterwards every rank holds, in segment k, fold(members in that order) + (running sum of the
+ * excluded ranks), rounded to the buffer type after every addition.  The levels are issued one
+ * after the other on `stream` (the paper runs the reductions concurrently on disjoint channel
+ * groups; the result is the same).  Every segment's byte size must be a multiple of 16 and divide
+ * into n_slabs * members_k chunks; level_elems sums to n_elems; a level may be empty. */
+typedef struct {
+    uint32_t n_ranks;    /* R, 2..R2_MAX_RANKS                      */
+    uint32_t n_channels; /* C                                       */
+    uint32_t align;      /* partition alignment, a multiple of 16   */
+    int32_t dtype;       /* r2_dtype                                */
+    int32_t schedule;    /* R2_SCHED_* for the ring runs            */
+    uint32_t n_slabs;    /* slabs of every ring run, >= 1           */
+    uint32_t n_levels;   /* 1..R2_MAX_LEVELS                        */
+    uint32_t reserved;   /* 0                                       */
+    uint64_t n_elems;    /* elements per rank                       */
+} r2_recursive_desc;
+
+/* Workspace (device, 256-byte aligned): the largest ring workspace of any level, the broadcast's
+ * offsets tables and its double-buffered stage.  0 if an argument is invalid. */
+uint64_t r2_recursive_workspace_bytes(const r2_recursive_desc *desc, const r2_level *levels,
+                                      const uint64_t *level_elems);
+
+/* levels, level_elems, weights, fail_masks: HOST arrays (n_levels, n_levels, n_channels, n_ranks).
+ * Only `members` and `fail_mask` of a level are read; members must be nested and hold >= 2 ranks.
+ * Asynchronous on `stream`; allocates nothing. */
+int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *const *rank_bufs, const uint32_t *weights,
+                               const uint64_t *fail_masks, const r2_level *levels, const uint64_t *level_elems,
+                               void *workspace, uint64_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Bridge-based logical re-ranking -- Sec. 6 "Topology-Aware Logical Re-ranking", Appendix D Alg. 1.
  *
  * HOST integer work, no device involved.  `ring` is a permutation of 0..n-1 (the logical ring order);

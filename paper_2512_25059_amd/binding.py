@@ -47,6 +47,17 @@ class _SplitDesc(C.Structure):
                 ("n_slabs_partial", C.c_uint32)]
 
 
+class _Level(C.Structure):
+    _fields_ = [("members", C.c_uint64), ("fail_mask", C.c_uint64), ("bandwidth", C.c_uint64),
+                ("increment", C.c_uint64), ("share", C.c_double)]
+
+
+class _RecursiveDesc(C.Structure):
+    _fields_ = [("n_ranks", C.c_uint32), ("n_channels", C.c_uint32), ("align", C.c_uint32),
+                ("dtype", C.c_int32), ("schedule", C.c_int32), ("n_slabs", C.c_uint32),
+                ("n_levels", C.c_uint32), ("reserved", C.c_uint32), ("n_elems", C.c_uint64)]
+
+
 class _SimDesc(C.Structure):
     _fields_ = [("n_ranks", C.c_uint32), ("n_slabs", C.c_uint32), ("n_channels", C.c_uint32),
                 ("align", C.c_uint32), ("n_elems", C.c_uint64), ("dtype", C.c_int32),
@@ -90,6 +101,38 @@ class SplitDesc:
                           self.n_slabs_partial)
 
 
+MAX_LEVELS = 16
+
+
+@dataclass(frozen=True)
+class Level:
+    """One ring of the recursive decomposition (mirror of r2_level)."""
+    members: int
+    fail_mask: int
+    bandwidth: int = 0
+    increment: int = 0
+    share: float = 0.0
+
+    def ranks(self) -> List[int]:
+        return [r for r in range(64) if (self.members >> r) & 1]
+
+
+@dataclass(frozen=True)
+class RecursiveDesc:
+    n_ranks: int
+    n_channels: int
+    align: int
+    n_elems: int
+    dtype: int
+    n_levels: int
+    n_slabs: int = 1
+    schedule: int = 0
+
+    def c(self) -> _RecursiveDesc:
+        return _RecursiveDesc(self.n_ranks, self.n_channels, self.align, self.dtype, self.schedule,
+                              self.n_slabs, self.n_levels, 0, self.n_elems)
+
+
 _lib = None
 
 
@@ -124,6 +167,16 @@ def load_library():
     lib.r2_split_workspace_bytes.argtypes = [C.POINTER(_SplitDesc)]
     lib.r2_split_allreduce_sim.restype = i32
     lib.r2_split_allreduce_sim.argtypes = [C.POINTER(_SplitDesc), vp, vp, u64, vp, u64, vp]
+    lib.r2_recursive_plan.restype = i32
+    lib.r2_recursive_plan.argtypes = [u32, u32, u32, vp, vp, u32, vp, vp]
+    lib.r2_recursive_time.restype = C.c_double
+    lib.r2_recursive_time.argtypes = [u32, u32, vp, u32, C.c_double, C.c_double, C.c_double]
+    lib.r2_select_strategy.restype = i32
+    lib.r2_select_strategy.argtypes = [u32, u32, u32, vp, vp, C.c_double, C.c_double, C.c_double, vp, vp, vp]
+    lib.r2_recursive_workspace_bytes.restype = u64
+    lib.r2_recursive_workspace_bytes.argtypes = [C.POINTER(_RecursiveDesc), vp, vp]
+    lib.r2_recursive_allreduce_sim.restype = i32
+    lib.r2_recursive_allreduce_sim.argtypes = [C.POINTER(_RecursiveDesc), vp, vp, vp, vp, vp, vp, u64, vp]
     lib.r2_bridge_rerank.restype = i32
     lib.r2_bridge_rerank.argtypes = [vp, vp, u32, vp, vp]
     lib.r2_reduce_copy.restype = i32
@@ -242,6 +295,75 @@ def r2_split_allreduce_sim(desc: SplitDesc, rank_bufs: Sequence, weights: Sequen
                                                int(degraded_fail_mask), wp, wb, _stream(stream))
     del arr
     _check(rc, "r2_split_allreduce_sim")
+
+
+def _u32s(xs: Sequence[int]):
+    return (C.c_uint32 * max(len(xs), 1))(*[int(x) for x in xs])
+
+
+def _u64s(xs: Sequence[int]):
+    return (C.c_uint64 * max(len(xs), 1))(*[int(x) for x in xs])
+
+
+def _levels(levels: Sequence[Level]):
+    arr = (_Level * max(len(levels), 1))()
+    for i, lv in enumerate(levels):
+        arr[i] = _Level(int(lv.members), int(lv.fail_mask), int(lv.bandwidth), int(lv.increment), float(lv.share))
+    return arr
+
+
+def r2_recursive_plan(weights: Sequence[int], fail_masks: Sequence[int], gpus_per_rank: int = 1,
+                      max_levels: int = MAX_LEVELS) -> List[Level]:
+    """Host call: the peel plan for per-rank failed-channel masks."""
+    w, m = _u32s(weights), _u64s(fail_masks)
+    out = (_Level * MAX_LEVELS)()
+    n = C.c_uint32(0)
+    rc = load_library().r2_recursive_plan(len(fail_masks), int(gpus_per_rank), len(weights), C.cast(w, C.c_void_p),
+                                          C.cast(m, C.c_void_p), int(max_levels), C.cast(out, C.c_void_p),
+                                          C.cast(C.pointer(n), C.c_void_p))
+    _check(rc, "r2_recursive_plan")
+    return [Level(int(l.members), int(l.fail_mask), int(l.bandwidth), int(l.increment), float(l.share))
+            for l in out[:n.value]]
+
+
+def r2_recursive_time(n_ranks: int, gpus_per_rank: int, levels: Sequence[Level], nbytes: float, alpha: float,
+                      beta: float) -> float:
+    arr = _levels(levels)
+    return float(load_library().r2_recursive_time(int(n_ranks), int(gpus_per_rank), C.cast(arr, C.c_void_p),
+                                                  len(levels), float(nbytes), float(alpha), float(beta)))
+
+
+def r2_select_strategy(weights: Sequence[int], fail_masks: Sequence[int], gpus_per_rank: int, nbytes: float,
+                       alpha: float, beta: float) -> Tuple[int, List[float]]:
+    """Host call: returns (chosen depth, modelled time of every depth)."""
+    w, m = _u32s(weights), _u64s(fail_masks)
+    depth, nd = C.c_uint32(0), C.c_uint32(0)
+    times = (C.c_double * MAX_LEVELS)()
+    rc = load_library().r2_select_strategy(len(fail_masks), int(gpus_per_rank), len(weights), C.cast(w, C.c_void_p),
+                                           C.cast(m, C.c_void_p), float(nbytes), float(alpha), float(beta),
+                                           C.cast(C.pointer(depth), C.c_void_p), C.cast(times, C.c_void_p),
+                                           C.cast(C.pointer(nd), C.c_void_p))
+    _check(rc, "r2_select_strategy")
+    return int(depth.value), [float(t) for t in times[:nd.value]]
+
+
+def r2_recursive_workspace_bytes(desc: RecursiveDesc, levels: Sequence[Level], level_elems: Sequence[int]) -> int:
+    arr, e = _levels(levels), _u64s(level_elems)
+    return int(load_library().r2_recursive_workspace_bytes(C.byref(desc.c()), C.cast(arr, C.c_void_p),
+                                                           C.cast(e, C.c_void_p)))
+
+
+def r2_recursive_allreduce_sim(desc: RecursiveDesc, rank_bufs: Sequence, weights: Sequence[int],
+                               fail_masks: Sequence[int], levels: Sequence[Level], level_elems: Sequence[int],
+                               workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    keep, p = _ptr_array(rank_bufs)
+    w, m, arr, e = _u32s(weights), _u64s(fail_masks), _levels(levels), _u64s(level_elems)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_recursive_allreduce_sim(C.byref(desc.c()), p, C.cast(w, C.c_void_p), C.cast(m, C.c_void_p),
+                                                   C.cast(arr, C.c_void_p), C.cast(e, C.c_void_p), wp, wb,
+                                                   _stream(stream))
+    del keep
+    _check(rc, "r2_recursive_allreduce_sim")
 
 
 def r2_bridge_rerank(ring: Sequence[int], rails: Sequence[int]) -> Tuple[List[int], int]:

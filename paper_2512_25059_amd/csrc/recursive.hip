@@ -1,0 +1,297 @@
+// Recursive R2CCL-AllReduce (R2CCL paper, Sec. 6, on top of Sec. 5.2): with several failures the
+// servers form a spectrum of bandwidths; a global ring runs at the slowest server's rate, the
+// slowest is left out and a faster sub-ring formed from the rest, and so on.  This file holds the
+// host planner (the peel, the shares, the alpha-beta time, the choice of depth) and the schedule on
+// simulated ranks, which is built from the ring simulation and the fused reduce-copy of ring.hip.
+#include "r2_internal.h"
+
+namespace {
+
+constexpr uint64_t kAlign256 = 256;
+
+uint64_t round_up(uint64_t x, uint64_t m) { return (x + m - 1) / m * m; }
+
+uint64_t weight_of(const uint32_t *weights, uint64_t fail_mask, uint32_t C)
+{
+    uint64_t w = 0;
+    for (uint32_t c = 0; c < C; ++c)
+        if (!((fail_mask >> c) & 1u)) w += weights[c];
+    return w;
+}
+
+uint64_t union_mask(const uint64_t *fail_masks, uint64_t members, uint32_t R, uint64_t full)
+{
+    uint64_t u = 0;
+    for (uint32_t r = 0; r < R; ++r)
+        if ((members >> r) & 1u) u |= fail_masks[r] & full;
+    return u;
+}
+
+double ring_factor(double p) { return 2.0 * (p - 1.0) / p; }
+
+unsigned popcount64(uint64_t x) { return (unsigned)__builtin_popcountll(x); }
+
+// The order in which a level's data visits the ranks: excluded ranks ascending, then the members in
+// ring order starting after the highest excluded rank (all ranks ascending if none is excluded).
+void chain_order(uint32_t R, uint64_t members, uint32_t *excl, uint32_t &m, uint32_t *order, uint32_t &p)
+{
+    m = p = 0;
+    for (uint32_t r = 0; r < R; ++r)
+        if (!((members >> r) & 1u)) excl[m++] = r;
+    const uint32_t start = m ? excl[m - 1] + 1 : 0;
+    for (uint32_t i = 0; i < R; ++i) {
+        const uint32_t r = (start + i) % R;
+        if ((members >> r) & 1u) order[p++] = r;
+    }
+}
+
+struct LevelShape {
+    r2_sim_desc ring;
+    uint64_t bytes, cap, ws_ring;
+    uint32_t m, p, hops;
+};
+
+struct RecShape {
+    LevelShape lv[R2_MAX_LEVELS];
+    uint64_t elem, ws_ring, tables_off, stage_off, total;
+};
+
+int rec_shape(const r2_recursive_desc *d, const r2_level *levels, const uint64_t *level_elems, RecShape &s)
+{
+    if (!d || !levels || !level_elems) return R2_ERR_INVALID;
+    if (d->n_ranks < 2 || d->n_ranks > R2_MAX_RANKS) return R2_ERR_INVALID;
+    if (d->n_channels == 0 || d->n_channels > R2_MAX_CHANNELS) return R2_ERR_INVALID;
+    if (d->align == 0 || d->align % 16 != 0) return R2_ERR_INVALID;
+    if (d->dtype != R2_F32 && d->dtype != R2_BF16) return R2_ERR_INVALID;
+    if (d->n_levels == 0 || d->n_levels > R2_MAX_LEVELS || d->n_slabs == 0 || d->reserved != 0) return R2_ERR_INVALID;
+    const uint32_t R = d->n_ranks;
+    const uint64_t all = R == 64 ? ~0ull : ((1ull << R) - 1);
+    s.elem = d->dtype == R2_F32 ? 4 : 2;
+    s.ws_ring = 0;
+    uint64_t sum = 0, max_cap = 0, max_hops = 0, prev = all;
+    for (uint32_t k = 0; k < d->n_levels; ++k) {
+        LevelShape &l = s.lv[k];
+        const uint64_t mem = levels[k].members;
+        if (k == 0 ? mem != all : ((mem & ~prev) != 0 || mem == prev)) return R2_ERR_INVALID;  // nested, shrinking
+        prev = mem;
+        l.p = popcount64(mem);
+        l.m = R - l.p;
+        if (l.p < 2) return R2_ERR_INVALID;
+        l.hops = l.m ? l.p + 2 * l.m - 1 : 0;
+        const uint64_t n = level_elems[k];
+        if (n > d->n_elems - sum) return R2_ERR_INVALID;
+        sum += n;
+        l.bytes = n * s.elem;
+        if (l.bytes % 16 != 0) return R2_ERR_INVALID;
+        l.cap = round_up(l.bytes ? l.bytes : 1, kAlign256);
+        l.ring = r2_sim_desc{l.p, d->n_slabs, d->n_channels, d->align, n, d->dtype, R2_PHASE_RS | R2_PHASE_AG, 0,
+                             d->schedule, 0};
+        l.ws_ring = 0;
+        if (n) {
+            if (r2_sim_num_steps(&l.ring) == 0) return R2_ERR_INVALID;
+            l.ws_ring = round_up(r2_sim_workspace_bytes(&l.ring), kAlign256);
+            if (l.ws_ring == 0) return R2_ERR_INVALID;
+            if (l.ws_ring > s.ws_ring) s.ws_ring = l.ws_ring;
+            if (l.m && l.cap > max_cap) max_cap = l.cap;
+            if (l.hops > max_hops) max_hops = l.hops;
+        }
+    }
+    if (sum != d->n_elems) return R2_ERR_INVALID;
+    s.tables_off = s.ws_ring;
+    s.stage_off = s.tables_off + round_up(max_hops * (uint64_t)(d->n_channels + 1) * 8, kAlign256);
+    s.total = s.stage_off + 2 * (uint64_t)d->n_channels * max_cap;
+    if (s.total == 0) s.total = kAlign256;
+    return R2_OK;
+}
+
+}  // namespace
+
+extern "C" int r2_recursive_plan(uint32_t n_ranks, uint32_t gpus_per_rank, uint32_t n_channels,
+                                 const uint32_t *weights, const uint64_t *fail_masks, uint32_t max_levels,
+                                 r2_level *levels, uint32_t *n_levels)
+{
+    if (n_ranks < 2 || n_ranks > R2_MAX_RANKS || gpus_per_rank == 0) return R2_ERR_INVALID;
+    if (n_channels == 0 || n_channels > R2_MAX_CHANNELS) return R2_ERR_INVALID;
+    if (max_levels == 0 || max_levels > R2_MAX_LEVELS) return R2_ERR_INVALID;
+    if (!weights || !fail_masks || !levels || !n_levels) return R2_ERR_INVALID;
+    const uint32_t R = n_ranks, C = n_channels;
+    const uint64_t full = C == 64 ? ~0ull : ((1ull << C) - 1);
+    uint64_t own[R2_MAX_RANKS];
+    for (uint32_t r = 0; r < R; ++r) own[r] = weight_of(weights, fail_masks[r] & full, C);
+
+    uint64_t members = R == 64 ? ~0ull : ((1ull << R) - 1);
+    uint64_t mask = union_mask(fail_masks, members, R, full);
+    uint64_t bw = weight_of(weights, mask, C);
+    if (bw == 0) return R2_ERR_NO_HEALTHY_CHANNEL;
+    uint32_t L = 0;
+    levels[L++] = r2_level{members, mask, bw, bw, 0.0};
+    while (L < max_levels) {
+        uint64_t lo = ~0ull;
+        for (uint32_t r = 0; r < R; ++r)
+            if (((members >> r) & 1u) && own[r] < lo) lo = own[r];
+        uint64_t rest = 0;
+        for (uint32_t r = 0; r < R; ++r)
+            if (((members >> r) & 1u) && own[r] > lo) rest |= 1ull << r;
+        if (popcount64(rest) < 2) break;
+        members = rest;
+        mask = union_mask(fail_masks, members, R, full);
+        bw = weight_of(weights, mask, C);
+        if (bw > levels[L - 1].bandwidth) {
+            levels[L] = r2_level{members, mask, bw, bw - levels[L - 1].bandwidth, 0.0};
+            ++L;
+        }
+    }
+    // shares: all rings finish together when latency is ignored
+    double raw[R2_MAX_LEVELS], sum = 0.0;
+    for (uint32_t k = 0; k < L; ++k) {
+        const double p = (double)popcount64(levels[k].members) * gpus_per_rank;
+        raw[k] = (double)levels[k].increment / ring_factor(p);
+        sum += raw[k];
+    }
+    for (uint32_t k = 0; k < L; ++k) levels[k].share = raw[k] / sum;
+    *n_levels = L;
+    return R2_OK;
+}
+
+extern "C" double r2_recursive_time(uint32_t n_ranks, uint32_t gpus_per_rank, const r2_level *levels,
+                                    uint32_t n_levels, double bytes, double alpha, double beta)
+{
+    if (!levels || n_levels == 0 || n_levels > R2_MAX_LEVELS || gpus_per_rank == 0 || n_ranks < 2) return -1.0;
+    if (!(beta > 0.0) || !(bytes >= 0.0) || !(alpha >= 0.0)) return -1.0;
+    double red = 0.0, bc = 0.0;
+    for (uint32_t k = 0; k < n_levels; ++k) {
+        const unsigned mem = popcount64(levels[k].members);
+        if (mem < 2 || mem > n_ranks || levels[k].increment == 0) return -1.0;
+        const double p = (double)mem * gpus_per_rank;
+        const double t = levels[k].share * bytes / ((double)levels[k].increment * beta);
+        const double tr = 2.0 * (p - 1.0) * alpha + ring_factor(p) * t;
+        if (tr > red) red = tr;
+        if (k) {
+            const double hops = (double)mem + 2.0 * (double)(n_ranks - mem) - 1.0;
+            const double tb = hops * alpha + t;
+            if (tb > bc) bc = tb;
+        }
+    }
+    return red + bc;
+}
+
+extern "C" int r2_select_strategy(uint32_t n_ranks, uint32_t gpus_per_rank, uint32_t n_channels,
+                                  const uint32_t *weights, const uint64_t *fail_masks, double bytes,
+                                  double alpha, double beta, uint32_t *depth, double *times, uint32_t *n_depths)
+{
+    if (!depth || !(beta > 0.0) || !(bytes >= 0.0) || !(alpha >= 0.0)) return R2_ERR_INVALID;
+    r2_level lv[R2_MAX_LEVELS];
+    uint32_t full = 0;
+    int rc = r2_recursive_plan(n_ranks, gpus_per_rank, n_channels, weights, fail_masks, R2_MAX_LEVELS, lv, &full);
+    if (rc) return rc;
+    uint32_t best = 0;
+    double best_t = 0.0;
+    for (uint32_t d = 0; d < full; ++d) {
+        uint32_t L = 0;
+        rc = r2_recursive_plan(n_ranks, gpus_per_rank, n_channels, weights, fail_masks, d + 1, lv, &L);
+        if (rc) return rc;
+        const double t = r2_recursive_time(n_ranks, gpus_per_rank, lv, L, bytes, alpha, beta);
+        if (t < 0.0) return R2_ERR_INVALID;
+        if (times) times[d] = t;
+        if (d == 0 || t < best_t) {
+            best = d;
+            best_t = t;
+        }
+    }
+    *depth = best;
+    if (n_depths) *n_depths = full;
+    return R2_OK;
+}
+
+extern "C" uint64_t r2_recursive_workspace_bytes(const r2_recursive_desc *desc, const r2_level *levels,
+                                                 const uint64_t *level_elems)
+{
+    RecShape s;
+    return rec_shape(desc, levels, level_elems, s) == R2_OK ? s.total : 0;
+}
+
+extern "C" int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *const *rank_bufs,
+                                          const uint32_t *weights, const uint64_t *fail_masks,
+                                          const r2_level *levels, const uint64_t *level_elems, void *workspace,
+                                          uint64_t workspace_bytes, void *stream)
+{
+    RecShape s;
+    int rc = rec_shape(desc, levels, level_elems, s);
+    if (rc) return rc;
+    if (!rank_bufs || !weights || !fail_masks) return R2_ERR_INVALID;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return R2_ERR_INVALID;
+    if (workspace_bytes < s.total) return R2_ERR_CAPACITY;
+    const uint32_t R = desc->n_ranks, C = desc->n_channels;
+    const uint64_t full = C == 64 ? ~0ull : ((1ull << C) - 1);
+    for (uint32_t r = 0; r < R; ++r) {
+        const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
+        if (desc->n_elems && (!p || (p & 15u))) return R2_ERR_INVALID;
+    }
+
+    // Every table this run needs must leave a channel: the levels' rings and every link of the chains.
+    uint32_t excl[R2_MAX_RANKS], order[R2_MAX_RANKS], chain[3 * R2_MAX_RANKS];
+    for (uint32_t k = 0; k < desc->n_levels; ++k) {
+        if (level_elems[k] == 0) continue;
+        if (!r2::any_healthy(weights, levels[k].fail_mask & full, C)) return R2_ERR_NO_HEALTHY_CHANNEL;
+        uint32_t m, p;
+        chain_order(R, levels[k].members, excl, m, order, p);
+        if (!m) continue;
+        uint32_t n = 0;
+        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
+        for (uint32_t i = 0; i < p; ++i) chain[n++] = order[i];
+        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
+        for (uint32_t i = 0; i + 1 < n; ++i)
+            if (!r2::any_healthy(weights, (fail_masks[chain[i]] | fail_masks[chain[i + 1]]) & full, C))
+                return R2_ERR_NO_HEALTHY_CHANNEL;
+    }
+
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    uint64_t *tables = reinterpret_cast<uint64_t *>(ws + s.tables_off);
+    const r2_dtype dt = (r2_dtype)desc->dtype;
+    uint64_t lo = 0;  // first element of the level's segment
+    r2_epoch links[3 * R2_MAX_RANKS];
+    for (uint32_t k = 0; k < desc->n_levels; ++k) {
+        const LevelShape &l = s.lv[k];
+        const uint64_t seg_off = lo * s.elem;
+        lo += level_elems[k];
+        if (level_elems[k] == 0) continue;
+        uint32_t m, p;
+        chain_order(R, levels[k].members, excl, m, order, p);
+
+        // 1. the level's ring over its members, under the channels that are up at all of them
+        void *seg[R2_MAX_RANKS];
+        for (uint32_t i = 0; i < p; ++i) seg[i] = static_cast<uint8_t *>(rank_bufs[order[i]]) + seg_off;
+        const r2_epoch state = {0, levels[k].fail_mask & full, weights};
+        rc = r2_ring_allreduce_sim(&l.ring, seg, &state, 1, ws, l.ws_ring, nullptr, stream);
+        if (rc) return rc;
+        if (!m) continue;
+
+        // 2. the broadcast chain; link i joins chain[i] and chain[i+1] and has table i
+        uint32_t n = 0;
+        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
+        for (uint32_t i = 0; i < p; ++i) chain[n++] = order[i];
+        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
+        for (uint32_t i = 0; i + 1 < n; ++i)
+            links[i] = r2_epoch{i, (fail_masks[chain[i]] | fail_masks[chain[i + 1]]) & full, weights};
+        rc = r2::launch_partition_epochs(links, n - 1, C, desc->align, l.bytes, n - 1, tables, nullptr,
+                                         (hipStream_t)stream);
+        if (rc) return rc;
+        void *stage[2][R2_MAX_CHANNELS];
+        for (uint32_t par = 0; par < 2; ++par)
+            for (uint32_t c = 0; c < C; ++c) stage[par][c] = ws + s.stage_off + ((uint64_t)par * C + c) * l.cap;
+        for (uint32_t i = 0; i < n; ++i) {
+            const bool first = i == 0, last = i + 1 == n;
+            int op;
+            if (i < m) op = R2_OP_SUM;                    // excluded ranks add themselves up
+            else if (i < m + p - 1) op = R2_OP_SUM_FORWARD;  // members take the sum, relay it unchanged
+            else if (i == m + p - 1) op = R2_OP_SUM;      // the last member sends its finished result on
+            else op = R2_OP_COPY;                         // excluded ranks take the result, pass it on
+            void *local = static_cast<uint8_t *>(rank_bufs[chain[i]]) + seg_off;
+            rc = r2_reduce_copy(local, l.bytes, dt, op, first ? nullptr : stage[(i + 1) & 1],
+                                first ? nullptr : tables + (uint64_t)(i - 1) * (C + 1), last ? nullptr : stage[i & 1],
+                                last ? nullptr : tables + (uint64_t)i * (C + 1), C, l.cap, nullptr, stream);
+            if (rc) return rc;
+        }
+    }
+    return R2_OK;
+}

@@ -1,0 +1,174 @@
+"""GPU parity: the recursive R2CCL-AllReduce schedule (Sec. 6) through the C ABI vs the oracle, bit for
+bit: against the oracle's step-by-step schedule and against the definition of the result."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import FILL, say
+from oracle import recursive as rec
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def r2():
+    import paper_2512_25059_amd as pkg
+
+    pkg.load_library()
+    assert torch.cuda.is_available()
+    return pkg
+
+
+def _inputs(rng, R, N, dtype, sigma=1.0):
+    xs = []
+    for _ in range(R):
+        x = (rng.standard_normal(N) * sigma).astype(np.float32)
+        if dtype == "bf16":
+            x = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+        xs.append(x)
+    return xs
+
+
+def _dev(a):
+    return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+
+def _levels(r2, plan):
+    return [r2.Level(sum(1 << r for r in l.members), l.fail_mask, l.bandwidth, l.increment, float(l.share))
+            for l in plan]
+
+
+def _run(r2, oracle, xs, dtype, plan, elems, S, C, align, weights, masks, schedule=0, step_by_step=True):
+    R, N = len(xs), xs[0].size
+    gdt = r2.F32 if dtype == "f32" else r2.BF16
+    odt = oracle.F32 if dtype == "f32" else oracle.BF16
+    levels = _levels(r2, plan)
+    desc = r2.RecursiveDesc(R, C, align, N, gdt, len(levels), S, schedule)
+    need = r2.r2_recursive_workspace_bytes(desc, levels, elems)
+    assert need > 0
+    ws = torch.full((need,), FILL, dtype=torch.uint8, device="cuda")
+    bufs = [_dev(x) for x in xs]
+    r2.r2_recursive_allreduce_sim(desc, bufs, weights, masks, levels, elems, ws)
+    torch.cuda.synchronize()
+    outs = [b.cpu().numpy().view(x.dtype) for b, x in zip(bufs, xs)]
+    want = rec.recursive_expected(xs, odt, plan, elems, S)
+    for r in range(R):
+        assert outs[r].tobytes() == want[r].tobytes(), f"rank {r} vs definition"
+    if step_by_step:
+        o_bufs = [x.copy() for x in xs]
+        rec.recursive_sim(o_bufs, odt, plan, elems, S, C, align, weights, masks)
+        for r in range(R):
+            assert outs[r].tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
+    return outs
+
+
+CASES = [
+    # weights, per-rank failed-channel masks
+    ([3, 5, 7, 11], [0b0001, 0b0011, 0, 0b0001, 0]),
+    ([50000] * 8, [0b1111, 0b0011, 0, 0]),
+    ([50000] * 8, [0, 0, 0b00111100, 0, 0, 0, 0, 0]),               # one degraded rank: Sec. 5.2
+    ([5] * 6, [0b000110, 0b000010, 0b000100, 0, 0, 0]),            # two equally slow ranks leave together
+    ([50000] * 8, [0] * 6),                                           # no failure: one ring
+    ([9, 9, 9], [0b001, 0b011, 0, 0b001, 0, 0, 0b011, 0, 0]),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("schedule", [1, 2])
+def test_recursive_small(r2, oracle, dtype, schedule):
+    rng = np.random.default_rng(500 + schedule)
+    per16 = 4 if dtype == "f32" else 8
+    for weights, masks in CASES:
+        plan = rec.plan(weights, masks)
+        R, C = len(masks), len(weights)
+        for S, unit in ((1, 37), (2, 5), (1, 1)):
+            elems = [S * len(l.members) * per16 * unit * (1 + (k + 1) % 3) for k, l in enumerate(plan)]
+            say(f"recursive {dtype} sched={schedule} R={R} C={C} levels={len(plan)} S={S} elems={elems}")
+            xs = _inputs(rng, R, sum(elems), dtype)
+            _run(r2, oracle, xs, dtype, plan, elems, S, C, 16, weights, masks, schedule)
+
+
+def test_recursive_empty_levels_and_truncated_plans(r2, oracle):
+    rng = np.random.default_rng(51)
+    weights, masks = [50000] * 8, [0b1111, 0b0011, 0, 0, 0b0001]
+    full = rec.plan(weights, masks)
+    assert len(full) == 4
+    for depth in (1, 2, 3, 4):
+        plan = rec.plan(weights, masks, 1, depth)
+        for empty in range(len(plan)):
+            elems = [0 if k == empty else len(l.members) * 4 * 11 for k, l in enumerate(plan)]
+            if sum(elems) == 0:
+                continue
+            say(f"recursive truncated depth={depth} empty level {empty} elems={elems}")
+            xs = _inputs(rng, 5, sum(elems), "f32")
+            _run(r2, oracle, xs, "f32", plan, elems, 1, 8, 256, weights, masks)
+
+
+def test_recursive_equals_split_for_one_degraded_rank(r2, oracle):
+    """Two levels with one rank left out is R2CCL-AllReduce: same bits as the split entry point."""
+    rng = np.random.default_rng(52)
+    R, d, C = 6, 4, 8
+    weights = [50000] * C
+    masks = [0] * R
+    masks[d] = 0b00100100
+    plan = rec.plan(weights, masks)
+    ng, npart = R * 8 * 300, (R - 1) * 8 * 123
+    xs = _inputs(rng, R, ng + npart, "bf16", 0.02)
+    say(f"recursive vs split R={R} d={d} global={ng} partial={npart}")
+    outs = _run(r2, oracle, xs, "bf16", plan, [ng, npart], 1, C, 256, weights, masks)
+    desc = r2.SplitDesc(R, d, C, 256, ng + npart, npart, r2.BF16, 0, 1, 1)
+    ws = torch.empty(r2.r2_split_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    bufs = [_dev(x) for x in xs]
+    r2.r2_split_allreduce_sim(desc, bufs, weights, masks[d], ws)
+    torch.cuda.synchronize()
+    for r in range(R):
+        assert bufs[r].cpu().numpy().view(np.uint16).tobytes() == outs[r].tobytes()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recursive_large(r2, oracle, dtype):
+    """Segments of several MiB (many tiles, the step schedule's launch shapes), shares from the plan."""
+    rng = np.random.default_rng(53)
+    R, C = 8, 8
+    weights = [50000] * C
+    masks = [0b00001111, 0, 0b00000011, 0, 0, 0b00000001, 0, 0]
+    plan = rec.plan(weights, masks)
+    assert len(plan) == 4
+    q = 8 * 7 * 6 * 5 * 8  # divides into every level's ring, 16-byte chunks
+    total = q * 300
+    elems = [int(float(l.share) * total) // q * q for l in plan[1:]]
+    elems = [total - sum(elems)] + elems
+    say(f"recursive large {dtype} elems={elems}")
+    xs = _inputs(rng, R, total, dtype, 0.02 if dtype == "bf16" else 1.0)
+    _run(r2, oracle, xs, dtype, plan, elems, 1, C, 256, weights, masks, schedule=1, step_by_step=False)
+
+
+def test_recursive_argument_errors(r2):
+    weights, masks = [50000] * 4, [0b0011, 0, 0, 0]
+    plan = rec.plan(weights, masks)
+    levels = _levels(r2, plan)
+    elems = [4 * 4 * 3, 3 * 4 * 3]
+    N = sum(elems)
+    desc = r2.RecursiveDesc(4, 4, 16, N, r2.F32, 2)
+    need = r2.r2_recursive_workspace_bytes(desc, levels, elems)
+    assert need > 0
+    bufs = [torch.zeros(N, dtype=torch.float32, device="cuda") for _ in range(4)]
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+    def fails(code, d=desc, lv=levels, el=elems, w=weights, m=masks, space=ws):
+        with pytest.raises(r2.R2Error) as e:
+            r2.r2_recursive_allreduce_sim(d, bufs, w, m, lv, el, space)
+        assert e.value.code == code
+
+    fails(-4, space=ws[:need - 256])                                          # workspace too small
+    fails(-1, el=[elems[0], elems[1] - 12])                             # sizes do not add up
+    fails(-1, el=[elems[0] + 4, elems[1] - 4])                          # a segment does not divide into its ring
+    fails(-1, lv=[levels[0], r2.Level(0b10011, 0)])                     # members not among the ranks
+    fails(-1, lv=[levels[0], r2.Level(0b1111, 0)])                      # not shrinking
+    fails(-1, lv=[levels[0], r2.Level(0b1000, 0)])                      # a ring of one
+    fails(-1, lv=[r2.Level(0b0111, 0), levels[1]])                      # level 0 must hold everybody
+    fails(-2, lv=[r2.Level(0b1111, 0b1111), levels[1]])                 # the level's ring has no channel
+    fails(-2, m=[0b0011, 0b1100, 0, 0])                                 # the link 0 -> 1 has no channel
+    assert r2.r2_recursive_workspace_bytes(r2.RecursiveDesc(4, 4, 16, N, r2.F32, 0), levels, elems) == 0
+    torch.cuda.synchronize()
+    assert all(float(b.abs().sum()) == 0.0 for b in bufs)               # nothing ran
