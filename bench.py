@@ -264,6 +264,73 @@ def split_line(r2, torch, np, wl, out=sys.stderr):
           f"({alg} algorithmic bytes)", file=out, flush=True)
 
 
+def _time_calls(torch, fn, n=20, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / n
+
+
+def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
+    """R2CCL-Balance on the collectives the paper measures besides all-reduce (Sec. 8, Appendix E):
+    reduce-scatter, all-gather and send/receive on the cfg2 shape (8 ranks, bf16, 128 MiB per rank),
+    one of eight channels down from the start."""
+    w = wl.cfg2()
+    R, N, C, e = w.R, w.N, w.C, 2
+    epochs = [(0, 0b00000100, [50000] * C)]
+    xs = wl.make_inputs(w)
+    bufs = [_to_device(torch, np, x) for x in xs]
+    recv = [torch.empty_like(b) for b in bufs]
+    for name, phases, S, units in (("reduce-scatter", r2.PHASE_RS, 1, (4 * R - 3) * N),
+                                   ("all-gather", r2.PHASE_AG, 1, (3 * R - 2) * N),
+                                   ("send/receive", r2.PHASE_SENDRECV, 8, 4 * R * N)):
+        desc = r2.SimDesc(R, S, C, w.align, N, r2.BF16, phases, 0, r2.SCHED_STEPS)
+        ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+        if phases == r2.PHASE_SENDRECV:
+            s = _time_calls(torch, lambda: r2.r2_sendrecv_sim(desc, bufs, recv, epochs, ws))
+        else:
+            s = _time_calls(torch, lambda: r2.r2_ring_allreduce_sim(desc, bufs, epochs, ws))
+        alg = units * e
+        print(f"{name:14s} cfg2 shape, channel 2 down: {s * 1e6:10.1f} us/op  {alg / s / 1e9:9.1f} GB/s  "
+              f"{100 * alg / s / 1e9 / HBM_PEAK_GBPS:6.2f} % of HBM peak ({alg} algorithmic bytes)", file=out, flush=True)
+        del ws
+
+
+def recursive_line(r2, torch, np, wl, out=sys.stderr):
+    """Recursive R2CCL-AllReduce (Sec. 6) on the cfg2 shape: rank 0 has lost four of eight NICs, rank 3
+    two, rank 5 one; shares from the planner."""
+    w = wl.cfg2()
+    R, C, e = w.R, w.C, 2
+    weights = [50000] * C
+    masks = [0b00001111, 0, 0, 0b00000011, 0, 0b00000001, 0, 0]
+    levels = r2.r2_recursive_plan(weights, masks)
+    q = 8 * 7 * 6 * 5 * 8 * 8  # every level's ring gets whole 16-byte vectors
+    total = w.N // q * q
+    elems = [int(l.share * total) // q * q for l in levels[1:]]
+    elems = [total - sum(elems)] + elems
+    desc = r2.RecursiveDesc(R, C, w.align, total, r2.BF16, len(levels))
+    xs = wl.make_inputs(w)
+    bufs = [_to_device(torch, np, x[:total].copy()) for x in xs]
+    ws = torch.empty(r2.r2_recursive_workspace_bytes(desc, levels, elems), dtype=torch.uint8, device="cuda")
+    s = _time_calls(torch, lambda: r2.r2_recursive_allreduce_sim(desc, bufs, weights, masks, levels, elems, ws))
+    alg = 0
+    for l, n in zip(levels, elems):
+        p = len(l.ranks())
+        m = R - p
+        # ring over the p members: 7p-6 units; chain: the m excluded ranks add up (2, then 4 each), the p
+        # members add and relay (4 each), the excluded ranks copy and pass on (3 each, the last 2)
+        chain = (2 + 4 * (m - 1) + 4 * p + 3 * (m - 1) + 2) if m else 0
+        alg += ((7 * p - 6) + chain) * n * e
+    depth, times = r2.r2_select_strategy(weights, masks, 1, total * e, 5e-6, 1e3)
+    print(f"recursive    {len(levels)} levels, elements {elems}: {s * 1e6:10.1f} us/op  {alg / s / 1e9:9.1f} GB/s  "
+          f"{100 * alg / s / 1e9 / HBM_PEAK_GBPS:6.2f} % of HBM peak ({alg} algorithmic bytes); "
+          f"selector (alpha 5 us, 50 MB/s per unit of weight) picks depth {depth}", file=out, flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -403,6 +470,8 @@ def main() -> int:
             del rk
             torch.cuda.empty_cache()
         split_line(r2, torch, np, wl)
+        recursive_line(r2, torch, np, wl)
+        other_collectives_lines(r2, torch, np, wl)
     if args.sweep:
         reduce_copy_sweep(r2, torch)
     return 0

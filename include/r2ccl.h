@@ -50,7 +50,8 @@ enum {
 
 typedef enum { R2_F32 = 0, R2_BF16 = 1 } r2_dtype;
 enum { R2_OP_SUM = 0, R2_OP_COPY = 1, R2_OP_SUM_FORWARD = 2 };
-enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2 }; /* both = all-reduce */
+enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2, /* both = all-reduce */
+       R2_PHASE_SENDRECV = 4 /* point-to-point to the ring successor; on its own only */ };
 enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2 };
 
 /* Static, human-readable text for a return code. */
@@ -162,6 +163,14 @@ int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int op,
  * uses the writer's table.  A failure "at step k" is an epoch with t_start = k; a recovery is a
  * later epoch with the bit cleared.  The result in the rank buffers does not depend on the epochs.
  *
+ * R2_PHASE_SENDRECV is the point-to-point case of R2CCL-Balance (Sec. 5.1 applies the redistribution
+ * to every collective; Sec. 8 and Appendix E measure it on SendRecv): rank r sends its whole buffer
+ * to rank r+1 and receives rank r-1's into a second buffer.  A slab is then one message chunk of
+ * n_elems/n_slabs elements, there are J = 2 steps (j = 0: stage <- send buffer; j = 1: receive
+ * buffer <- incoming) and one transmission per slab, t = l, so that a channel failing after chunk k
+ * re-partitions chunks k, k+1, ...  `rank_bufs` then holds 2R pointers: R send buffers, then R
+ * receive buffers (r2_sendrecv_sim takes them apart).  Only the step schedule runs it.
+ *
  * Slabs are independent of each other, and so are the bytes of a chunk.  The run is therefore cut
  * into passes -- groups of whole slabs, or, when one slab is too large, byte ranges of its chunks --
  * such that the stage bytes one step writes (over all ranks) stay within stage_window_bytes and can
@@ -181,9 +190,10 @@ typedef struct {
     uint32_t n_slabs;    /* S >= 1, R*S <= 65535                                                 */
     uint32_t n_channels; /* C, 1..R2_MAX_CHANNELS                                                */
     uint32_t align;      /* partition alignment in bytes, a multiple of 16                       */
-    uint64_t n_elems;    /* elements per rank, a multiple of R*S (0 is allowed: nothing to do)   */
+    uint64_t n_elems;    /* elements per rank, a multiple of R*S (of S for R2_PHASE_SENDRECV);
+                            0 is allowed: nothing to do                                          */
     int32_t dtype;       /* r2_dtype                                                             */
-    int32_t phases;      /* R2_PHASE_RS, R2_PHASE_AG or both                                     */
+    int32_t phases;      /* R2_PHASE_RS, R2_PHASE_AG, both, or R2_PHASE_SENDRECV                 */
     uint64_t stage_window_bytes; /* stage bytes one launch may write, summed over ranks; 0 = the
                                     library's default (128 MiB, half the Infinity Cache).  Only
                                     changes how the run is cut into passes, never the result.   */
@@ -247,6 +257,16 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           const r2_epoch *epochs, uint32_t n_epochs,
                           void *workspace, uint64_t workspace_bytes,
                           uint64_t *offsets_log, void *stream);
+
+/* Point-to-point under R2CCL-Balance (Sec. 5.1; measured in Sec. 8 "More results on other
+ * collectives" and Appendix E): desc->phases must be R2_PHASE_SENDRECV.  Rank r's send buffer
+ * (n_elems elements) goes, chunk by chunk through the partitioned stage buffers, into rank r+1's
+ * receive buffer; afterwards recv_bufs[r] equals send_bufs[(r-1) mod R] byte for byte whatever the
+ * epochs.  Same workspace, epochs, log and passes as r2_ring_allreduce_sim, which this calls with the
+ * two pointer lists joined.  Send buffers are only read. */
+int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
+                    const r2_epoch *epochs, uint32_t n_epochs, void *workspace, uint64_t workspace_bytes,
+                    uint64_t *offsets_log, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * R2CCL-AllReduce -- Sec. 5.2 ("Partial AllReduce", "R2CCL-AllReduce", "Data Partition Analysis") and

@@ -20,6 +20,7 @@ F32, BF16 = 0, 1
 OP_SUM, OP_COPY, OP_SUM_FORWARD = 0, 1, 2
 PHASE_RS, PHASE_AG = 1, 2
 PHASE_AR = PHASE_RS | PHASE_AG
+PHASE_SENDRECV = 4
 SCHED_AUTO, SCHED_STEPS, SCHED_FUSED = 0, 1, 2
 
 R2_OK = 0
@@ -198,6 +199,8 @@ def load_library():
     lib.r2_sim_fused_steps.argtypes = [pd, vp, u32, u32, vp, u64, vp]
     lib.r2_ring_allreduce_sim.restype = i32
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
+    lib.r2_sendrecv_sim.restype = i32
+    lib.r2_sendrecv_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
     _lib = lib
     return lib
 
@@ -531,3 +534,16 @@ def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
                                               wp, wb, _ptr(offsets_log), _stream(stream))
     del arr, keep
     _check(rc, "r2_ring_allreduce_sim")
+
+
+def r2_sendrecv_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epochs, workspace,
+                    offsets_log: Optional[torch.Tensor] = None, stream=None,
+                    workspace_bytes: Optional[int] = None) -> None:
+    sa, sp = _ptr_array(send_bufs)
+    ra, rp = _ptr_array(recv_bufs)
+    ep, keep = _epoch_array(epochs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_sendrecv_sim(C.byref(desc.c()), sp, rp, C.cast(ep, C.c_void_p), len(epochs),
+                                        wp, wb, _ptr(offsets_log), _stream(stream))
+    del sa, ra, keep
+    _check(rc, "r2_sendrecv_sim")

@@ -332,7 +332,7 @@ __global__ __launch_bounds__(kThreads) void reduce_copy_kernel(ChunkJob job, con
 // ---------------------------------------------------------------- front end 2: a ring step
 
 struct StepArgs {
-    uint64_t rank_buf[R2_MAX_RANKS];
+    uint64_t rank_buf[R2_MAX_RANKS];  // point-to-point: the send buffers at step 0, the receive buffers at step 1
     const uint64_t *tables;  // [S*T_slab][C+1]
     uint64_t stage;          // [2][R][S][C][cap]
     uint64_t chunk_bytes, cap;
@@ -340,6 +340,7 @@ struct StepArgs {
     uint32_t step;         // fused step j
     uint32_t T_slab;       // transmissions per slab
     uint32_t chunk_start;  // 1 when the run is an all-gather alone, else 0
+    uint32_t per_slab;     // ring chunks per slab: R, or 1 for point-to-point (every rank moves chunk 0)
     uint32_t slab_begin, slab_count;  // the slabs this launch covers
     uint64_t lo, hi;                  // and the byte range of every ring chunk it moves
 };
@@ -351,13 +352,13 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
     __shared__ ChannelTable tin, tout;
     const uint32_t r = blockIdx.y / a.slab_count, l = a.slab_begin + (blockIdx.y - r * a.slab_count);
     const uint32_t j = a.step;
-    const uint32_t chunk = (r + a.chunk_start + 2 * a.R - j) % a.R;  // j <= 2R-2
+    const uint32_t chunk = a.per_slab == 1 ? 0 : (r + a.chunk_start + 2 * a.R - j) % a.R;  // j <= 2R-2
     const uint32_t peer = (r + a.R - 1) % a.R;
     const uint64_t row = (uint64_t)a.C + 1;
     const uint64_t t_out = (uint64_t)l * a.T_slab + j;
 
     ChunkJob job;
-    job.local = reinterpret_cast<uint8_t *>(a.rank_buf[r]) + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
+    job.local = reinterpret_cast<uint8_t *>(a.rank_buf[r]) + ((uint64_t)l * a.per_slab + chunk) * a.chunk_bytes;
     job.bytes = a.chunk_bytes;
     job.lo = a.lo;
     job.hi = a.hi;
@@ -784,6 +785,7 @@ struct SimShape {
     // passes: the run is cut into groups of slabs, or one slab's chunks into byte ranges
     uint32_t slabs_per_pass, n_sub;
     uint64_t sub_bytes, n_passes;
+    bool p2p;  // point-to-point: two steps, one chunk per slab, separate receive buffers
 };
 
 uint64_t round_up(uint64_t x, uint64_t m) { return (x + m - 1) / m * m; }
@@ -797,17 +799,21 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     if (d->n_slabs == 0 || (uint64_t)d->n_slabs * d->n_ranks > 65535) return R2_ERR_INVALID;
     if (d->align == 0 || d->align % 16 != 0) return R2_ERR_INVALID;
     if (!valid_dtype(d->dtype)) return R2_ERR_INVALID;
-    if (d->phases != R2_PHASE_RS && d->phases != R2_PHASE_AG && d->phases != (R2_PHASE_RS | R2_PHASE_AG))
+    if (d->phases != R2_PHASE_RS && d->phases != R2_PHASE_AG && d->phases != (R2_PHASE_RS | R2_PHASE_AG) &&
+        d->phases != R2_PHASE_SENDRECV)
         return R2_ERR_INVALID;
     if (d->schedule != R2_SCHED_AUTO && d->schedule != R2_SCHED_STEPS && d->schedule != R2_SCHED_FUSED)
         return R2_ERR_INVALID;
-    const uint64_t per = (uint64_t)d->n_slabs * d->n_ranks;
+    const bool p2p = d->phases == R2_PHASE_SENDRECV;
+    if (p2p && d->schedule == R2_SCHED_FUSED) return R2_ERR_INVALID;
+    const uint64_t per = p2p ? d->n_slabs : (uint64_t)d->n_slabs * d->n_ranks;
     if (d->n_elems % per != 0) return R2_ERR_INVALID;
     if (d->n_elems > (1ull << 60)) return R2_ERR_OVERFLOW;
+    s.p2p = p2p;
     s.R = d->n_ranks;
     s.S = d->n_slabs;
     s.C = d->n_channels;
-    s.J = d->phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
+    s.J = p2p ? 2 : d->phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
     s.T_slab = s.J - 1;
     s.chunk_bytes = d->n_elems / per * elem_bytes(d->dtype);
     s.cap = round_up(s.chunk_bytes ? s.chunk_bytes : 1, 256);
@@ -867,6 +873,7 @@ void launch_step(const StepArgs &a, dim3 grid, hipStream_t st)
 // The fused-column schedule needs whole 16-byte vectors everywhere and a grid that fits.
 bool fused_eligible(const SimShape &s)
 {
+    if (s.p2p) return false;
     if (s.chunk_bytes == 0 || s.chunk_bytes % 16 != 0) return false;
     const uint64_t cols = (s.chunk_bytes + kColBytes - 1) / kColBytes;
     return cols * s.S <= 0x7fffffffull;
@@ -1025,8 +1032,9 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     if (!rank_bufs || step >= s.J || pass >= s.n_passes) return R2_ERR_INVALID;
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
     StepArgs a{};
+    const uint32_t first_buf = s.p2p && step == 1 ? s.R : 0;  // point-to-point receives into the second list
     for (uint32_t r = 0; r < s.R; ++r) {
-        a.rank_buf[r] = reinterpret_cast<uint64_t>(rank_bufs[r]);
+        a.rank_buf[r] = reinterpret_cast<uint64_t>(rank_bufs[first_buf + r]);
         if (s.chunk_bytes && (!a.rank_buf[r] || (a.rank_buf[r] & 15u))) return R2_ERR_INVALID;
     }
     if (s.chunk_bytes == 0) return R2_OK;
@@ -1040,6 +1048,7 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     a.step = step;
     a.T_slab = s.T_slab;
     a.chunk_start = desc->phases == R2_PHASE_AG ? 1 : 0;
+    a.per_slab = s.p2p ? 1 : s.R;
     if (s.n_sub > 1) {  // one slab, one byte range of its chunks
         a.slab_begin = (uint32_t)(pass / s.n_sub);
         a.slab_count = 1;
@@ -1054,7 +1063,7 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
 
     const bool has_in = step > 0, has_out = step < s.J - 1;
     int op;
-    if (desc->phases == R2_PHASE_AG) op = R2_OP_COPY;
+    if (desc->phases == R2_PHASE_AG || s.p2p) op = R2_OP_COPY;
     else if (desc->phases == R2_PHASE_RS) op = R2_OP_SUM;
     else op = step <= s.R - 1 ? R2_OP_SUM : R2_OP_COPY;
     const Mode m = mode_of(has_in, op, desc->dtype);
@@ -1173,7 +1182,7 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
     int rc = shape_of(desc, s);
     if (rc) return rc;
     if (!rank_bufs) return R2_ERR_INVALID;
-    for (uint32_t r = 0; r < s.R; ++r) {
+    for (uint32_t r = 0; r < (s.p2p ? 2 * s.R : s.R); ++r) {
         const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
         if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
     }
@@ -1215,6 +1224,22 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
     return R2_OK;
+}
+
+extern "C" int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
+                               const r2_epoch *epochs, uint32_t n_epochs, void *workspace,
+                               uint64_t workspace_bytes, uint64_t *offsets_log, void *stream)
+{
+    if (!desc || desc->phases != R2_PHASE_SENDRECV || !send_bufs || !recv_bufs) return R2_ERR_INVALID;
+    if (desc->n_ranks < 2 || desc->n_ranks > R2_MAX_RANKS) return R2_ERR_INVALID;
+    void *both[2 * R2_MAX_RANKS];
+    for (uint32_t r = 0; r < desc->n_ranks; ++r) {
+        both[r] = const_cast<void *>(send_bufs[r]);  // step 0 only reads them
+        both[desc->n_ranks + r] = recv_bufs[r];
+        for (uint32_t q = 0; q < desc->n_ranks; ++q)
+            if (send_bufs[q] == recv_bufs[r] && desc->n_elems) return R2_ERR_INVALID;  // no in-place exchange
+    }
+    return r2_ring_allreduce_sim(desc, both, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream);
 }
 
 extern "C" const char *r2_strerror(int code)

@@ -79,7 +79,7 @@ def test_pass_planning(r2):
 @pytest.mark.parametrize("bad", [
     dict(n_ranks=1), dict(n_ranks=65), dict(n_channels=0), dict(n_channels=65), dict(n_slabs=0),
     dict(align=0), dict(align=8), dict(align=24), dict(n_elems=(1 << 20) + 1), dict(dtype=7),
-    dict(phases=0), dict(phases=4), dict(n_slabs=8192, n_elems=8192 * 8 * 4), dict(schedule=3),
+    dict(phases=0), dict(phases=5), dict(phases=7), dict(phases=8), dict(n_slabs=8192, n_elems=8192 * 8 * 4), dict(schedule=3),
 ])
 def test_invalid_descriptors(r2, bad):
     base = dict(n_ranks=8, n_slabs=1, n_channels=8, align=256, n_elems=1 << 20, dtype=r2.BF16,
@@ -92,6 +92,17 @@ def test_invalid_descriptors(r2, bad):
         r2.r2_ring_allreduce_sim(d, [256] * base["n_ranks"], [(0, 0, [1] * max(base["n_channels"], 1))],
                                  4096, workspace_bytes=1 << 40)
     assert e.value.code == -1
+
+
+def test_sendrecv_descriptor_arithmetic(r2):
+    """Point-to-point: two steps, one transmission per message chunk, chunks of n_elems / n_slabs."""
+    d = r2.SimDesc(8, 6, 8, 256, 6 * 1000, r2.BF16, r2.PHASE_SENDRECV)
+    assert r2.r2_sim_num_steps(d) == 2
+    assert r2.r2_sim_num_transmissions(d) == 6
+    assert r2.r2_sim_stage_capacity(d) == 2048  # 2000 bytes per chunk, rounded up to 256
+    assert r2.r2_sim_resolve_schedule(d, [(0, 0, [1] * 8)]) == r2.SCHED_STEPS
+    assert r2.r2_sim_num_steps(r2.SimDesc(8, 6, 8, 256, 6 * 1000 + 1, r2.BF16, r2.PHASE_SENDRECV)) == 0
+    assert r2.r2_sim_num_steps(r2.SimDesc(8, 6, 8, 256, 6000, r2.BF16, r2.PHASE_SENDRECV, 0, r2.SCHED_FUSED)) == 0
 
 
 def test_sim_rejects_bad_epochs_and_buffers_before_any_device_work(r2):
