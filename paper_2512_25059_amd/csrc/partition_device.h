@@ -45,10 +45,12 @@ __device__ inline uint64_t partition_lane(uint32_t weight, bool failed, uint32_t
     uint64_t incl = e;
 #pragma unroll
     for (unsigned d = 1; d < kWave; d <<= 1) {
-        const uint64_t up = __shfl_up(incl, d, kWave);
-        if (lane >= d) incl += up;
+        if (d < C) {  // lanes from C on carry nothing: log2(C) rounds reach every channel
+            const uint64_t up = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += up;
+        }
     }
-    const uint64_t W = __shfl(incl, kWave - 1, kWave);
+    const uint64_t W = __shfl(incl, C - 1, kWave);
     const uint64_t P = incl - e;  // bandwidth of the channels before this one
 
     *total_weight = W;

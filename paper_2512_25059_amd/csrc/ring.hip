@@ -482,80 +482,119 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
     const uint32_t t_first = a.j0 ? a.j0 - 1 : 0;
     const uint32_t t_end = a.j1 < a.T_slab ? a.j1 : a.T_slab;
     const uint64_t *rows = slab_tables;  // rows + t * row = table of transmission t
-    if constexpr (PARTITION) {  // always with the rows in LDS
-        const uint32_t w_id = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane_id = threadIdx.x % kWave;
-        for (uint32_t t = t_first + w_id; t < t_end; t += blockDim.x / kWave) {
-            const uint64_t tg = (uint64_t)l * a.T_slab + t;  // transmission index of the whole run
-            const uint32_t e = epoch_at(*eb, tg);
-            const uint32_t weight = lane_id < C ? eb->weights[e * C + lane_id] : 0;
-            uint64_t W;
-            const uint64_t o = partition_lane(weight, (eb->fail_mask[e] >> lane_id) & 1u, C, a.chunk_bytes, a.align, &W);
-            uint64_t *lds_row = s_rows + (uint64_t)(t - t_first) * row;
-            if (lane_id < C) lds_row[lane_id] = o;
-            if (lane_id == 0) lds_row[C] = a.chunk_bytes;
-            if (k == 0) {
-                if (lane_id < C) a.tables_out[tg * row + lane_id] = o;
-                if (lane_id == 0) a.tables_out[tg * row + C] = a.chunk_bytes;
-                if (a.log_out) {
-                    if (lane_id < C) a.log_out[tg * row + lane_id] = o;
-                    if (lane_id == 0) a.log_out[tg * row + C] = a.chunk_bytes;
-                }
-            }
-        }
-        __syncthreads();
-        rows = s_rows - (uint64_t)t_first * row;
-    } else if (a.rows_in_lds) {
-        const uint32_t n = (t_end - t_first) * (uint32_t)row;
-        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_rows[i] = slab_tables[(uint64_t)t_first * row + i];
-        __syncthreads();
-        rows = s_rows - (uint64_t)t_first * row;
-    }
-
-    // Which slice holds the column's first byte, for every such transmission.
-    const bool ragged_width = b0 + kColBytes > a.chunk_bytes;  // the chunk's last, narrower column
-    for (uint32_t t = t_first + threadIdx.x; t < t_end; t += blockDim.x) {
-        const uint64_t *off = rows + t * row;
-        const uint32_t c = find_channel(off, C, b0);
-        info[t].lo = off[c];
-        info[t].hi = off[c + 1];
-        info[t].c = c;
-    }
-    __syncthreads();
-    R2_STAMP(1);
-
     // The wave index is made visibly wave-uniform: everything indexed by rank (the kernel-argument
     // array of rank buffers above all) then goes through scalar loads and the scalar cache instead
     // of a vector load from the argument block, which lives in host memory.
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint32_t lane = threadIdx.x % kWave, n_waves = blockDim.x / kWave;
+    const bool one_rank = a.R <= n_waves;                       // a wave plays one rank
+    const bool ragged_width = b0 + kColBytes > a.chunk_bytes;  // the chunk's last, narrower column
+
+    // A launch that starts at step 0 begins with every rank staging a chunk of its own buffer.
+    // Where that chunk lies depends on nothing computed below, so its loads are issued first and
+    // their latency passes while the tables are made.
+    const bool preload = a.j0 == 0 && one_rank && !ragged_width;
+    u32x4 pre[kColUnroll] = {};
+    if (preload) {
+        const uint64_t src = a.rank_buf[wave] + ((uint64_t)l * a.R + (wave + a.chunk_start) % a.R) * a.chunk_bytes + b0;
+#pragma unroll
+        for (unsigned u = 0; u < kColUnroll; ++u) pre[u] = load16<kNtLocalLoad>(src + (uint64_t)(u * kWave + lane) * 16);
+    }
+
+    // changed[t]: the table of transmission t may differ from that of t-1.  Tables mostly repeat,
+    // and then the stage offsets of a step can be carried over.
+    __shared__ uint32_t changed[2 * R2_MAX_RANKS];
+    const R2_LDS uint64_t *lds_rows = (const R2_LDS uint64_t *)s_rows;
+    bool slow;
+    if constexpr (PARTITION) {  // always with the rows in LDS
+        // One wave per channel state in force within [t_first, t_end): it cuts the chunk once, into
+        // the row of the first transmission the state governs here.  Then one thread per
+        // transmission copies its state's row and notes the slice that holds the column.
+        const uint64_t tg0 = (uint64_t)l * a.T_slab;  // transmission index (of the whole run) of the slab's first
+        const uint32_t e_lo = epoch_at(*eb, tg0 + t_first), e_hi = epoch_at(*eb, tg0 + t_end - 1);
+        auto first_tx = [&](uint32_t e) { return e == e_lo ? t_first : (uint32_t)(eb->t_start[e] - tg0); };
+        for (uint32_t ev = e_lo + wave; ev <= e_hi; ev += n_waves) {
+            const uint32_t e = __builtin_amdgcn_readfirstlane(ev);
+            const uint32_t weight = lane < C ? eb->weights[e * C + lane] : 0;
+            uint64_t W;
+            const uint64_t o = partition_lane(weight, (eb->fail_mask[e] >> lane) & 1u, C, a.chunk_bytes, a.align, &W);
+            uint64_t *lds_row = s_rows + (uint64_t)(first_tx(e) - t_first) * row;
+            if (lane < C) lds_row[lane] = o;
+            if (lane == 0) lds_row[C] = a.chunk_bytes;
+        }
+        __syncthreads();
+        R2_STAMP(40);
+        for (uint32_t tv = t_first + wave; tv < t_end; tv += n_waves) {  // lane c handles entry c of the row
+            const uint32_t t = __builtin_amdgcn_readfirstlane(tv);
+            const uint32_t ts = first_tx(epoch_at(*eb, tg0 + t));
+            const R2_LDS uint64_t *src = lds_rows + (uint64_t)(ts - t_first) * row;
+            const uint64_t lo = lane <= C ? src[lane] : 0, hi = lane < C ? src[lane + 1] : 0;
+            if (t != ts && lane <= C) s_rows[(uint64_t)(t - t_first) * row + lane] = lo;
+            if (lane < C && lo <= b0 && b0 < hi) {  // the one slice that holds the column's first byte
+                info[t].lo = lo;
+                info[t].hi = hi;
+                info[t].c = lane;
+            }
+            if (lane == 0) changed[t] = t == ts;  // the first transmission of a state, or of this launch
+        }
+        __syncthreads();
+        R2_STAMP(1);
+        rows = s_rows - (uint64_t)t_first * row;
+        slow = ragged_width;
+    } else {
+        if (a.rows_in_lds) {
+            const uint32_t n = (t_end - t_first) * (uint32_t)row;
+            for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_rows[i] = slab_tables[(uint64_t)t_first * row + i];
+            __syncthreads();
+            rows = s_rows - (uint64_t)t_first * row;
+        }
+        // Which slice holds the column's first byte, for every such transmission.
+        for (uint32_t t = t_first + threadIdx.x; t < t_end; t += blockDim.x) {
+            const uint64_t *off = rows + t * row;
+            const uint32_t c = find_channel(off, C, b0);
+            info[t].lo = off[c];
+            info[t].hi = off[c + 1];
+            info[t].c = c;
+        }
+        __syncthreads();
+        R2_STAMP(1);
+        // (lane c compares entry c of the two rows)
+        for (uint32_t t = t_first + wave; t < t_end; t += n_waves) {
+            bool eq = false;
+            if (a.rows_in_lds && t > t_first) {
+                eq = true;
+                if (lane < C)
+                    eq = lds_rows[(uint64_t)(t - t_first) * row + lane] == lds_rows[(uint64_t)(t - 1 - t_first) * row + lane];
+                eq = __all(eq);
+            }
+            if (lane == 0) changed[t] = !eq;
+        }
+        // Straddling columns need the rows in LDS for the fast loop; otherwise they take the slow one.
+        int straddles = 0;
+        if (!a.rows_in_lds)
+            for (uint32_t t = t_first + threadIdx.x; t < t_end; t += blockDim.x)
+                if (b1 > info[t].hi) straddles = 1;
+        slow = ragged_width || __syncthreads_or(straddles);
+    }
+    // The first column of a slab records the rows it computed for the caller: last of all, so that
+    // no step waits for these stores.
+    auto record_rows = [&]() {
+        if (!PARTITION || k != 0) return;
+        const uint32_t n = (t_end - t_first) * (uint32_t)row;
+        const uint64_t at = ((uint64_t)l * a.T_slab + t_first) * row;
+        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
+            const uint64_t v = lds_rows[i];
+            a.tables_out[at + i] = v;
+            if (a.log_out) a.log_out[at + i] = v;
+        }
+    };
     const uint64_t per_rank = (uint64_t)a.S * C * a.cap;  // stage bytes of one (parity, rank)
     const uint64_t slab_stage = a.stage + (uint64_t)l * C * a.cap;
     auto local_of = [&](uint32_t r, uint32_t j) {
         const uint32_t chunk = (r + a.chunk_start + 2 * a.R - j) % a.R;
         return a.rank_buf[r] + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
     };
-
-    // changed[t]: the table of transmission t differs from that of t-1 (lane c compares entry c).
-    // Tables mostly repeat, and then the stage offsets of a step can be carried over.
-    __shared__ uint32_t changed[2 * R2_MAX_RANKS];
-    const R2_LDS uint64_t *lds_rows = (const R2_LDS uint64_t *)s_rows;
-    for (uint32_t t = t_first + wave; t < t_end; t += n_waves) {
-        bool eq = false;
-        if (a.rows_in_lds && t > t_first) {
-            eq = true;
-            if (lane < C)
-                eq = lds_rows[(uint64_t)(t - t_first) * row + lane] == lds_rows[(uint64_t)(t - 1 - t_first) * row + lane];
-            eq = __all(eq);
-        }
-        if (lane == 0) changed[t] = !eq;
-    }
-
-    // Straddling columns need the rows in LDS for the fast loop; otherwise they take the slow one.
-    int straddles = 0;
-    if (!a.rows_in_lds)
-        for (uint32_t t = t_first + threadIdx.x; t < t_end; t += blockDim.x)
-            if (b1 > info[t].hi) straddles = 1;
-    const bool slow = ragged_width || __syncthreads_or(straddles);
+    R2_STAMP(41);
 
     if (!slow) {
         // Full-width column: straight-line steps and barriers only.  Where the column lies inside
@@ -608,7 +647,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         // When a wave plays one rank, what it needs per step is hoisted out of the step loop: the
         // slab of its buffer, its own stage and its predecessor's (parity 0; parity 1 is R ranks
         // further), and the ring chunk it is at, which goes one down per step.
-        const bool one_rank = a.R <= n_waves;
         const uint32_t my_peer = (wave + a.R - 1) % a.R;
         const uint64_t my_slab = a.rank_buf[wave] + (uint64_t)l * a.R * a.chunk_bytes;
         const uint64_t my_in0 = slab_stage + (uint64_t)my_peer * per_rank;
@@ -632,8 +670,13 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
 #pragma unroll
             for (unsigned u = 0; u < kColUnroll; ++u) dout[u] = dcur[u];
             if (one_rank) {
-                rank_step(has_in, has_out, summing, my_slab + (uint64_t)my_chunk * a.chunk_bytes,
-                          my_in0 + ((j + 1) & 1 ? parity_stride : 0), my_out0 + (j & 1 ? parity_stride : 0), din, dout);
+                if (j == 0 && preload) {  // the chunk is already in registers
+#pragma unroll
+                    for (unsigned u = 0; u < kColUnroll; ++u) store16<false>(my_out0 + dout[u], pre[u]);
+                } else {
+                    rank_step(has_in, has_out, summing, my_slab + (uint64_t)my_chunk * a.chunk_bytes,
+                              my_in0 + ((j + 1) & 1 ? parity_stride : 0), my_out0 + (j & 1 ? parity_stride : 0), din, dout);
+                }
                 my_chunk = my_chunk ? my_chunk - 1 : a.R - 1;
             } else {
                 for (uint32_t rv = wave; rv < a.R; rv += n_waves) {
@@ -647,6 +690,7 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             __syncthreads();  // the next step reads what other waves of this workgroup just staged
             R2_STAMP(2 + j);
         }
+        record_rows();
         return;
     }
 
@@ -720,6 +764,7 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         }
         __syncthreads();
     }
+    record_rows();
 }
 template <bool BF16>
 __global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_kernel(const FusedArgs a)
