@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure (8 TB/s)
 # (FETCH_SIZE reads half the copied bytes there, WRITE_SIZE all of them).  The figures and the
 # commands are in profiles/ring_step_sum_bf16_cfg2_pmc.md.  Not measured for other workloads.
 MEASURED_TRAFFIC = {
-    ("cfg2", "sum"): int((131117.2 * (131072.0 / 65550.7) + 262158.5 * (131072.0 / 131072.0)) * 1024),
+    ("cfg2", "sum"): int((131117.5 * (131072.0 / 65550.8) + 262164.2 * (131072.0 / 131072.0)) * 1024),
 }
 
 
@@ -66,21 +66,23 @@ class Runner:
         self.call = r2.SimCall(self.desc, self.bufs, w.epochs, self.ws)  # arguments marshalled once
 
     def _fused_times(self, reps: int):
-        """Fused-column schedule: all launches of a run between one pair of events."""
-        torch, r2 = self.torch, self.r2
+        """Fused-column schedule: a run is one launch per stretch of steps between channel-state
+        changes, a few microseconds each, so a pair of events round a single launch would mostly time
+        the host.  Whole runs are issued back to back between one pair of events instead (in place,
+        as in time_steps); the figure is the average per launch, dispatch gaps included."""
+        torch = self.torch
         segs = _fused_segments(self.w)
-        total = 0.0
-        for _ in range(reps):
-            self.restore()
-            r2.r2_sim_prepare(self.desc, self.w.epochs, self.ws)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for j0, j1 in segs:
-                r2.r2_sim_fused_steps(self.desc, self.bufs, j0, j1, self.ws)
-            e1.record()
-            torch.cuda.synchronize()
-            total += e0.elapsed_time(e1)
-        return {"fused": (total / (reps * len(segs)), reps * len(segs))}
+        n = max(20 * reps, 100)
+        self.restore()
+        for _ in range(3):
+            self.step()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            self.step()
+        e1.record()
+        torch.cuda.synchronize()
+        return {"fused": (e0.elapsed_time(e1) / (n * len(segs)), n * len(segs))}
 
     def restore(self):
         for b, p in zip(self.bufs, self.pristine):
@@ -381,7 +383,7 @@ def main() -> int:
         dom = "fused"
         dom_avg_ms, dom_launches = ktimes[dom]
         launch_bytes = w.algorithmic_bytes / len(_fused_segments(w))
-        kernel_name = "ring_fused_kernel<%s> (stage round trip served by L2: not an HBM figure)" % w.dtype
+        kernel_name = "ring_fused_partition_kernel<%s> (ring_fused_kernel when the tables are prepared up front; stage round trip served by L2: not an HBM figure)" % w.dtype
     else:
         dom = "sum" if "sum" in ktimes else "copy"
         dom_units = 4 if dom == "sum" else 3
