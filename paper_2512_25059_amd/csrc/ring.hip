@@ -528,8 +528,11 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             const uint32_t t = __builtin_amdgcn_readfirstlane(tv);
             const uint32_t ts = first_tx(epoch_at(*eb, tg0 + t));
             const R2_LDS uint64_t *src = lds_rows + (uint64_t)(ts - t_first) * row;
-            const uint64_t lo = lane <= C ? src[lane] : 0, hi = lane < C ? src[lane + 1] : 0;
-            if (t != ts && lane <= C) s_rows[(uint64_t)(t - t_first) * row + lane] = lo;
+            const uint64_t lo = lane < C ? src[lane] : 0, hi = lane < C ? src[lane + 1] : 0;
+            if (t != ts) {  // C may be the whole wavefront: lane 0 also writes the row's last entry
+                if (lane < C) s_rows[(uint64_t)(t - t_first) * row + lane] = lo;
+                if (lane == 0) s_rows[(uint64_t)(t - t_first) * row + C] = a.chunk_bytes;
+            }
             if (lane < C && lo <= b0 && b0 < hi) {  // the one slice that holds the column's first byte
                 info[t].lo = lo;
                 info[t].hi = hi;

@@ -192,6 +192,30 @@ def test_sim_many_channels_and_single_channel(r2, oracle):
     _full_compare_small(r2, oracle, w1)
 
 
+@pytest.mark.parametrize("schedule", [1, 2])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sim_maximum_ranks_and_channels(r2, oracle, dtype, schedule):
+    """The limits of the interface: 64 ranks (127 fused steps, 126 transmissions per slab; in the fused
+    schedule four ranks share a wave) and 64 channels, where the table rows of a fused launch no longer
+    fit its LDS block and the prepared tables are read from memory instead."""
+    from dataclasses import replace
+
+    R, S, E = 64, 2, 776  # 776 elements: 3104 or 1552 bytes, whole 16-byte vectors
+    T = S * (2 * R - 2)
+    base = replace(wl.cfg1(), R=R, dtype=dtype, N=R * S * E, S=S, align=16, phases="ar", sigma=1.0, seed=64)
+    w8 = replace(base, name=f"R64_C8_{dtype}", C=8,
+                 epochs=((0, 0b1, tuple([50000] * 8)), (T // 3, 0b10100000, tuple(range(1, 9))), (T - 5, 0, tuple([1] * 8))))
+    _full_compare_small(r2, oracle, w8, schedule=schedule)
+    w64 = replace(base, name=f"R64_C64_{dtype}", C=64,
+                  epochs=((0, 0xFF00FF00FF00FF00, tuple(range(1, 65))), (130, 1 << 63, tuple([7] * 64)),
+                          (200, (1 << 64) - 2, tuple([3] * 64))))
+    _full_compare_small(r2, oracle, w64, schedule=schedule)
+    # one channel state for the whole run: a single fused launch whose 126 rows of 65 entries exceed the
+    # LDS block, so the tables are prepared up front and the columns that straddle cuts look them up in memory
+    w64b = replace(base, name=f"R64_C64_one_state_{dtype}", C=64, epochs=((0, 0x00FF00FF00FF00FE, tuple(range(1, 65))),))
+    _full_compare_small(r2, oracle, w64b, schedule=schedule)
+
+
 def test_sim_result_independent_of_schedule(r2, oracle):
     """Lossless whatever the failure timing: different schedules, same bits."""
     from dataclasses import replace
