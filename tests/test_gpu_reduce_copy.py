@@ -200,3 +200,47 @@ def test_reduce_copy_bad_tables_move_nothing(r2, oracle):
 def test_reduce_copy_zero_bytes(r2):
     say("reduce_copy bytes=0")
     r2.r2_reduce_copy(None, r2.F32, r2.OP_SUM, [256], 256, None, None, 1, 16, nbytes=0)
+
+
+def test_reduce_copy_chunk_beyond_4GiB(r2, oracle):
+    """A chunk of 4 GiB + 1 MiB + 6 bytes of bf16 (2^31 + 2^19 + 3 elements): slice offsets, stage
+    addresses and the ragged tail all lie beyond 32 bits.  Too large for the host oracle in a test, so the
+    expected values are built on the GPU with library operations from the definition: per element
+    bf16(float(incoming) + float(local)), incoming and outgoing slices cut at the oracle's tables."""
+    n_el = (1 << 31) + (1 << 19) + 3
+    nbytes = n_el * 2
+    C = 3
+    in_off = oracle.partition([2, 1, 3], 0b000, nbytes, 256)
+    out_off = oracle.partition([2, 1, 3], 0b010, nbytes, 256)
+    cap = int(max(np.diff(in_off.astype(np.int64)).max(), np.diff(out_off.astype(np.int64)).max()))
+    cap = (cap + 255) // 256 * 256
+    say(f"reduce_copy beyond 4 GiB: bytes={nbytes} in_off={in_off.tolist()} out_off={out_off.tolist()} cap={cap}")
+    g = torch.Generator(device="cuda").manual_seed(99)
+    local = torch.randn(n_el, generator=g, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    incoming = torch.randn(n_el, generator=g, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    want = torch.empty_like(local)
+    step = 1 << 28  # in pieces: the fp32 temporaries of the whole chunk would be 16 GiB
+    for a in range(0, n_el, step):
+        b = min(a + step, n_el)
+        want[a:b] = (incoming[a:b].float() + local[a:b].float()).to(torch.bfloat16)
+    raw_in = incoming.view(torch.uint8)
+    d_in = []
+    for k in range(C):
+        buf = torch.full((cap,), FILL, dtype=torch.uint8, device="cuda")
+        a, b = int(in_off[k]), int(in_off[k + 1])
+        buf[:b - a] = raw_in[a:b]
+        d_in.append(buf)
+    d_out = [torch.full((cap,), FILL, dtype=torch.uint8, device="cuda") for _ in range(C)]
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    r2.r2_reduce_copy(local.view(torch.int16), r2.BF16, r2.OP_SUM, d_in, _dev(in_off), d_out, _dev(out_off), C, cap,
+                      status, nbytes=nbytes)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert torch.equal(local.view(torch.int16), want.view(torch.int16))
+    raw_want = want.view(torch.uint8)
+    for k in range(C):
+        a, b = int(out_off[k]), int(out_off[k + 1])
+        assert torch.equal(d_out[k][:b - a], raw_want[a:b]), f"out stage {k}"
+        assert bool((d_out[k][b - a:] == FILL).all()), f"out stage {k}: bytes beyond the slice"
+    del local, incoming, want, d_in, d_out
+    torch.cuda.empty_cache()

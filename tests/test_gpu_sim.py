@@ -216,6 +216,50 @@ def test_sim_maximum_ranks_and_channels(r2, oracle, dtype, schedule):
     _full_compare_small(r2, oracle, w64b, schedule=schedule)
 
 
+@pytest.mark.parametrize("schedule", [1, 2])
+def test_sim_maximum_slabs(r2, oracle, schedule):
+    """R * S just under the 65535 limit of the launch grid: 8191 slabs of 8 ranks with one 16-byte
+    vector per ring chunk, the channel state changing every 1000 transmissions."""
+    from dataclasses import replace
+
+    R, S, C = 8, 8191, 4
+    T = S * (2 * R - 2)
+    eps = tuple((t0, (1 << ((t0 // 1000) % C)), (5, 6, 7, 8)) for t0 in range(0, T, 1000))
+    w = replace(wl.cfg1(), name="S8191", R=R, dtype="f32", N=R * S * 4, S=S, C=C, align=16, phases="ar",
+                sigma=1.0, seed=8191, epochs=eps)
+    _full_compare_small(r2, oracle, w, schedule=schedule)
+
+
+def test_sim_chunks_beyond_4GiB(r2, oracle):
+    """Byte offsets that do not fit 32 bits: two ranks of 8 GiB + 8 MiB each, i.e. ring chunks of
+    4 GiB + 4 MiB, moved in byte-range passes.  Too large for the oracle's step-by-step ring on the host, so
+    the result is checked by what it must be for two ranks -- one fp32 addition per element, the same bits in
+    either order -- and the tables against the oracle's partition."""
+    R, C = 2, 3
+    N = (1 << 31) + (1 << 21)
+    weights = (3, 1, 2)
+    epochs = [(0, 0, weights), (1, 0b010, weights)]
+    desc = r2.SimDesc(R, 1, C, 256, N, r2.F32, r2.PHASE_AR, 0, r2.SCHED_STEPS)
+    chunk_bytes = N // R * 4
+    assert chunk_bytes > 1 << 32 and r2.r2_sim_num_passes(desc) > 1
+    say(f"sim beyond 4 GiB: R={R} N={N} chunk={chunk_bytes} B passes={r2.r2_sim_num_passes(desc)}")
+    g = torch.Generator(device="cuda").manual_seed(4096)
+    xs = [torch.randn(N, generator=g, dtype=torch.float32, device="cuda") for _ in range(R)]
+    want = xs[0] + xs[1]
+    ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    log = torch.full((2, C + 1), -1, dtype=torch.int64, device="cuda")
+    r2.r2_ring_allreduce_sim(desc, xs, epochs, ws, log)
+    torch.cuda.synchronize()
+    for r in range(R):
+        assert torch.equal(xs[r].view(torch.int32), want.view(torch.int32)), f"rank {r}"
+    got = log.cpu().numpy().view(np.uint64)
+    for t, (_, mask, w) in enumerate(epochs):
+        assert got[t].tolist() == oracle.partition(w, mask, chunk_bytes, 256).tolist()
+    assert int(got[0][-1]) == chunk_bytes and int(got[0][1]) > 1 << 31  # cuts beyond 2 GiB and 4 GiB
+    del xs, want, ws
+    torch.cuda.empty_cache()
+
+
 def test_sim_result_independent_of_schedule(r2, oracle):
     """Lossless whatever the failure timing: different schedules, same bits."""
     from dataclasses import replace
