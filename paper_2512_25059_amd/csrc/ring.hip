@@ -655,33 +655,99 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         const uint64_t my_in0 = slab_stage + (uint64_t)my_peer * per_rank;
         const uint64_t my_out0 = slab_stage + (uint64_t)wave * per_rank;
         const uint64_t parity_stride = (uint64_t)a.R * per_rank;
-        uint32_t my_chunk = (wave + a.chunk_start + 2 * a.R - a.j0) % a.R;
+        const uint32_t my_chunk = (wave + a.chunk_start + 2 * a.R - a.j0) % a.R;
 
         // The table a step reads with is the one the step before wrote with, and tables mostly
         // repeat from step to step, so the offsets are carried along and looked up only on change.
         uint64_t dcur[kColUnroll];
-        bool have = false;  // dcur holds the offsets of the previous transmission
-        for (uint32_t j = a.j0; j < a.j1; ++j) {
-            const bool has_in = j > 0, has_out = j + 1 < a.J;
-            const bool summing = has_in && j <= a.sum_last;
-            uint64_t din[kColUnroll], dout[kColUnroll];
-            if (has_in && !have) deltas_for(j - 1, dcur);  // first step of the launch
-#pragma unroll
-            for (unsigned u = 0; u < kColUnroll; ++u) din[u] = dcur[u];
-            if (has_out && (!(has_in || have) || changed[j])) deltas_for(j, dcur);
-            have = true;
-#pragma unroll
-            for (unsigned u = 0; u < kColUnroll; ++u) dout[u] = dcur[u];
-            if (one_rank) {
-                if (j == 0 && preload) {  // the chunk is already in registers
-#pragma unroll
-                    for (unsigned u = 0; u < kColUnroll; ++u) store16<false>(my_out0 + dout[u], pre[u]);
+        if (one_rank) {
+            // A wave that plays one rank runs the steps as up to five stretches of one kind each --
+            // copy-send, sums that stage onward, a last sum, copies that stage onward, a last copy --
+            // so that the body of each stretch is a handful of loads and stores between two
+            // barriers, with wave-uniform address updates and no per-step decisions beyond "did the
+            // table change", which is one bit of a mask held in scalar registers.
+            const uint32_t ti = t_first + lane;
+            const uint64_t chg_lo = __ballot(ti < t_end && changed[ti] != 0);
+            const uint64_t chg_hi = __ballot(ti + kWave < t_end && changed[ti + kWave] != 0);
+            auto table_changes_at = [&](uint32_t j) {  // j within [t_first, t_end)
+                const uint32_t i = j - t_first;
+                return ((i < kWave ? chg_lo >> i : chg_hi >> (i - kWave)) & 1u) != 0;
+            };
+            uint32_t chunk = my_chunk;
+            uint64_t loc = my_slab + (uint64_t)chunk * a.chunk_bytes;  // the ring chunk of the step
+            auto next_chunk = [&]() {
+                if (chunk) {
+                    --chunk;
+                    loc -= a.chunk_bytes;
                 } else {
-                    rank_step(has_in, has_out, summing, my_slab + (uint64_t)my_chunk * a.chunk_bytes,
-                              my_in0 + ((j + 1) & 1 ? parity_stride : 0), my_out0 + (j & 1 ? parity_stride : 0), din, dout);
+                    chunk = a.R - 1;
+                    loc += (uint64_t)(a.R - 1) * a.chunk_bytes;
                 }
-                my_chunk = my_chunk ? my_chunk - 1 : a.R - 1;
+            };
+            // Steps [j, j_end) of one KIND (1 sum, 2 copy), all of them staging onward or none.
+            auto stretch = [&](auto kind_tag, auto out_tag, uint32_t &j, uint32_t j_end) {
+                constexpr int KIND = decltype(kind_tag)::value;
+                constexpr bool HAS_OUT = decltype(out_tag)::value;
+                for (; j < j_end; ++j) {
+                    const uint64_t in_base = my_in0 + ((j + 1) & 1 ? parity_stride : 0);
+                    const uint64_t out_base = my_out0 + (j & 1 ? parity_stride : 0);
+                    uint64_t ain[kColUnroll], aout[kColUnroll], aloc[kColUnroll];
+#pragma unroll
+                    for (unsigned u = 0; u < kColUnroll; ++u) {
+                        ain[u] = in_base + dcur[u];
+                        aloc[u] = loc + bu[u];
+                    }
+                    if (HAS_OUT && table_changes_at(j)) deltas_for(j, dcur);
+#pragma unroll
+                    for (unsigned u = 0; u < kColUnroll; ++u) aout[u] = out_base + dcur[u];
+                    column_step<KIND, HAS_OUT, BF16>(ain, aout, aloc);
+                    next_chunk();
+                    __syncthreads();  // the next step reads what other waves of this workgroup just staged
+                    R2_STAMP(2 + j);
+                }
+            };
+            using std::integral_constant;
+            uint32_t j = a.j0;
+            const uint32_t last = a.J - 1;  // the one step that stages nothing
+            if (j == 0) {  // copy-send: nothing comes in, the chunk goes out under table 0
+                deltas_for(0, dcur);
+                uint64_t aout[kColUnroll], aloc[kColUnroll];
+#pragma unroll
+                for (unsigned u = 0; u < kColUnroll; ++u) {
+                    aout[u] = my_out0 + dcur[u];
+                    aloc[u] = loc + bu[u];
+                }
+                if (preload) {  // the chunk is already in registers
+#pragma unroll
+                    for (unsigned u = 0; u < kColUnroll; ++u) store16<false>(aout[u], pre[u]);
+                } else {
+                    column_step<0, true, BF16>(aout, aout, aloc);
+                }
+                next_chunk();
+                __syncthreads();
+                R2_STAMP(2);
+                j = 1;
             } else {
+                deltas_for(j - 1, dcur);  // the table the launch's first step reads with
+            }
+            const uint32_t sum_end = a.sum_last + 1 < a.j1 ? a.sum_last + 1 : a.j1;  // sums are steps 1..sum_last
+            stretch(integral_constant<int, 1>{}, integral_constant<bool, true>{}, j, sum_end < last ? sum_end : last);
+            if (j < sum_end) stretch(integral_constant<int, 1>{}, integral_constant<bool, false>{}, j, sum_end);
+            stretch(integral_constant<int, 2>{}, integral_constant<bool, true>{}, j, a.j1 < last ? a.j1 : last);
+            if (j < a.j1) stretch(integral_constant<int, 2>{}, integral_constant<bool, false>{}, j, a.j1);
+        } else {
+            bool have = false;  // dcur holds the offsets of the previous transmission
+            for (uint32_t j = a.j0; j < a.j1; ++j) {
+                const bool has_in = j > 0, has_out = j + 1 < a.J;
+                const bool summing = has_in && j <= a.sum_last;
+                uint64_t din[kColUnroll], dout[kColUnroll];
+                if (has_in && !have) deltas_for(j - 1, dcur);  // first step of the launch
+#pragma unroll
+                for (unsigned u = 0; u < kColUnroll; ++u) din[u] = dcur[u];
+                if (has_out && (!(has_in || have) || changed[j])) deltas_for(j, dcur);
+                have = true;
+#pragma unroll
+                for (unsigned u = 0; u < kColUnroll; ++u) dout[u] = dcur[u];
                 for (uint32_t rv = wave; rv < a.R; rv += n_waves) {
                     const uint32_t r = __builtin_amdgcn_readfirstlane(rv);
                     const uint32_t peer = (r + a.R - 1) % a.R;
@@ -689,9 +755,9 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                               slab_stage + ((uint64_t)((j + 1) & 1) * a.R + peer) * per_rank,
                               slab_stage + ((uint64_t)(j & 1) * a.R + r) * per_rank, din, dout);
                 }
+                __syncthreads();  // the next step reads what other waves of this workgroup just staged
+                R2_STAMP(2 + j);
             }
-            __syncthreads();  // the next step reads what other waves of this workgroup just staged
-            R2_STAMP(2 + j);
         }
         record_rows();
         return;
