@@ -688,6 +688,91 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             auto stretch = [&](auto kind_tag, auto out_tag, uint32_t &j, uint32_t j_end) {
                 constexpr int KIND = decltype(kind_tag)::value;
                 constexpr bool HAS_OUT = decltype(out_tag)::value;
+                if constexpr (KIND == 1 && HAS_OUT) {
+                    // Sums: the local chunk of step j+1 is untouched until then, so it is loaded
+                    // during step j, behind step j's own loads, and is in registers when its turn
+                    // comes.  Two register sets alternate; the barrier does not wait for loads.
+                    u32x4 set_a[kColUnroll], set_b[kColUnroll];
+                    // AHEAD is a compile-time choice so that each variant is straight-line code and
+                    // the waits the compiler places count exactly the loads that variant issued.
+                    auto sum_step = [&](auto ahead_tag, u32x4(&cur)[kColUnroll], u32x4(&nxt)[kColUnroll]) {
+                        constexpr bool AHEAD = decltype(ahead_tag)::value;
+                        const uint64_t in_base = my_in0 + ((j + 1) & 1 ? parity_stride : 0);
+                        const uint64_t out_base = my_out0 + (j & 1 ? parity_stride : 0);
+                        u32x4 inc[kColUnroll];
+                        uint64_t aloc[kColUnroll];
+#pragma unroll
+                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                            inc[u] = load16<false>(in_base + dcur[u]);
+                            aloc[u] = loc + bu[u];
+                        }
+                        next_chunk();
+                        if constexpr (AHEAD) {
+#pragma unroll
+                            for (unsigned u = 0; u < kColUnroll; ++u) nxt[u] = load16<kNtLocalLoad>(loc + bu[u]);
+                        }
+                        if (table_changes_at(j)) deltas_for(j, dcur);
+#pragma unroll
+                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                            const u32x4 v = combine<BF16 ? kSumBF16 : kSumF32>(inc[u], cur[u]);
+                            store16<kNtLocalStore>(aloc[u], v);
+                            store16<false>(out_base + dcur[u], v);
+                        }
+                        __syncthreads();  // the next step reads what other waves of this workgroup just staged
+                        R2_STAMP(2 + j);
+                        ++j;
+                    };
+                    using Yes = std::integral_constant<bool, true>;
+                    using No = std::integral_constant<bool, false>;
+                    if (j < j_end) {
+#pragma unroll
+                        for (unsigned u = 0; u < kColUnroll; ++u) set_a[u] = load16<kNtLocalLoad>(loc + bu[u]);
+                        for (;;) {
+                            if (j + 1 >= j_end) {
+                                sum_step(No{}, set_a, set_b);
+                                break;
+                            }
+                            sum_step(Yes{}, set_a, set_b);
+                            if (j + 1 >= j_end) {
+                                sum_step(No{}, set_b, set_a);
+                                break;
+                            }
+                            sum_step(Yes{}, set_b, set_a);
+                        }
+                    }
+                    return;
+                }
+                if constexpr (KIND == 2) {
+                    // Copies: two register sets alternate here too, so that a step's loads never
+                    // have to wait until the previous step's stores have read their data.
+                    u32x4 set_a[kColUnroll], set_b[kColUnroll];
+                    auto copy_step = [&](u32x4(&buf)[kColUnroll]) {
+                        const uint64_t in_base = my_in0 + ((j + 1) & 1 ? parity_stride : 0);
+                        const uint64_t out_base = my_out0 + (j & 1 ? parity_stride : 0);
+                        uint64_t aloc[kColUnroll];
+#pragma unroll
+                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                            buf[u] = load16<false>(in_base + dcur[u]);
+                            aloc[u] = loc + bu[u];
+                        }
+                        if (HAS_OUT && table_changes_at(j)) deltas_for(j, dcur);
+#pragma unroll
+                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                            store16<kNtLocalStore>(aloc[u], buf[u]);
+                            if constexpr (HAS_OUT) store16<false>(out_base + dcur[u], buf[u]);
+                        }
+                        next_chunk();
+                        __syncthreads();  // the next step reads what other waves of this workgroup just staged
+                        R2_STAMP(2 + j);
+                        ++j;
+                    };
+                    while (j < j_end) {
+                        copy_step(set_a);
+                        if (j >= j_end) break;
+                        copy_step(set_b);
+                    }
+                    return;
+                }
                 for (; j < j_end; ++j) {
                     const uint64_t in_base = my_in0 + ((j + 1) & 1 ? parity_stride : 0);
                     const uint64_t out_base = my_out0 + (j & 1 ? parity_stride : 0);
