@@ -192,7 +192,9 @@ struct ChunkJob {
 };
 
 // FWD (sums only): the outgoing stage gets the incoming data unchanged instead of the sum.
-template <Mode M, bool HAS_OUT, bool FWD = false, typename InPtr, typename OutPtr>
+// NT_OUT: the outgoing stage is written with non-temporal stores (a chunk too large for the next
+// reader to find it in cache).
+template <Mode M, bool HAS_OUT, bool FWD = false, bool NT_OUT = kNtStageStore, typename InPtr, typename OutPtr>
 __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_ptr, int32_t *status,
                                  ChannelTable &tin, ChannelTable &tout)
 {
@@ -253,7 +255,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
             for (unsigned u = 0; u < kUnroll; ++u) {
                 const u32x4 r = combine<M>(inc[u], loc[u]);
                 if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b + u * (kThreads * 16), r);
-                if constexpr (HAS_OUT) store16<kNtStageStore>(sout.delta + b + u * (kThreads * 16), FWD ? inc[u] : r);
+                if constexpr (HAS_OUT) store16<NT_OUT>(sout.delta + b + u * (kThreads * 16), FWD ? inc[u] : r);
             }
             continue;
         }
@@ -280,7 +282,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
                 if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b, r);
                 if constexpr (HAS_OUT) {
                     const uint64_t d = out_one ? sout.delta : tout.delta[find_channel(tout.off, C, b)];
-                    store16<kNtStageStore>(d + b, FWD ? inc[u] : r);
+                    store16<NT_OUT>(d + b, FWD ? inc[u] : r);
                 }
             }
         }
@@ -319,12 +321,12 @@ struct PtrList {
     uint64_t p[R2_MAX_CHANNELS];
 };
 
-template <Mode M, bool HAS_OUT, bool FWD = false>
+template <Mode M, bool HAS_OUT, bool FWD = false, bool NT_OUT = false>
 __global__ __launch_bounds__(kThreads) void reduce_copy_kernel(ChunkJob job, const PtrList in_stage,
                                                                const PtrList out_stage, int32_t *status)
 {
     __shared__ ChannelTable tin, tout;
-    run_chunk<M, HAS_OUT, FWD>(
+    run_chunk<M, HAS_OUT, FWD, NT_OUT>(
         job, [&](unsigned c) { return in_stage.p[c]; }, [&](unsigned c) { return out_stage.p[c]; },
         status, tin, tout);
 }
@@ -1107,12 +1109,19 @@ int plan_schedule(const r2_sim_desc *desc, const SimShape &s, const r2_epoch *ep
     return step_bytes <= kFusedAutoBytes && fewer ? R2_SCHED_FUSED : R2_SCHED_STEPS;
 }
 
+// A stage this large is gone from the caches before anybody reads it back: written around them.
+constexpr uint64_t kNtStageBytes = 128ull << 20;
+
 template <Mode M, bool HAS_OUT, bool FWD = false>
 void launch_single(const ChunkJob &job, const PtrList &in, const PtrList &out, int32_t *status,
                    unsigned blocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD>), dim3(blocks), dim3(kThreads), 0, st, job, in,
-                       out, status);
+    if (HAS_OUT && job.bytes > kNtStageBytes)
+        hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD, HAS_OUT>), dim3(blocks), dim3(kThreads), 0, st, job,
+                           in, out, status);
+    else
+        hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD, false>), dim3(blocks), dim3(kThreads), 0, st, job, in,
+                           out, status);
 }
 
 }  // namespace
