@@ -525,7 +525,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             if (lane == 0) lds_row[C] = a.chunk_bytes;
         }
         __syncthreads();
-        R2_STAMP(40);
         for (uint32_t tv = t_first + wave; tv < t_end; tv += n_waves) {  // lane c handles entry c of the row
             const uint32_t t = __builtin_amdgcn_readfirstlane(tv);
             const uint32_t ts = first_tx(epoch_at(*eb, tg0 + t));
@@ -599,7 +598,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         const uint32_t chunk = (r + a.chunk_start + 2 * a.R - j) % a.R;
         return a.rank_buf[r] + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
     };
-    R2_STAMP(41);
 
     if (!slow) {
         // Full-width column: straight-line steps and barriers only.  Where the column lies inside
