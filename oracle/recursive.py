@@ -156,15 +156,21 @@ def recursive_expected(inputs: Sequence[np.ndarray], dtype: int, levels: Sequenc
 
 def recursive_sim(bufs: Sequence[np.ndarray], dtype: int, levels: Sequence[Level],
                   level_elems: Sequence[int], n_slabs: int, n_channels: int, align: int,
-                  weights: Sequence[int], fail_masks: Sequence[int]) -> None:
+                  weights: Sequence[int], fail_masks: Sequence[int]):
     """The schedule step by step, in place on ``bufs``: for every level the ring over its members
     on its segment under the level's channel state, then, for the levels above 0, the broadcast
-    chain.  A link between two ranks is cut by the union of their failed channels."""
+    chain.  A link between two ranks is cut by the union of their failed channels.
+
+    Returns, per level, ``None`` (no chain) or ``(chain, tables[len(chain)-1, C+1], stage)`` with
+    the ranks in the order the data visits them, the table of every link and the two stage
+    parities (C buffers each) as the chain left them."""
     R = len(bufs)
     es = bufs[0].itemsize
     lo = 0
+    trace = []
     for lv, n in zip(levels, level_elems):
         hi = lo + n
+        trace.append(None)
         if n == 0:
             continue
         excl, order = chain_order(R, lv.members)
@@ -181,9 +187,11 @@ def recursive_sim(bufs: Sequence[np.ndarray], dtype: int, levels: Sequence[Level
             def table(u, v):
                 return o.partition(weights, fail_masks[u] | fail_masks[v], nbytes, align)
 
+            tables = np.stack([table(chain[i], chain[i + 1]) for i in range(len(chain) - 1)])
+            trace[-1] = (chain, tables, stage)
             for i, r in enumerate(chain):
-                t_in = table(chain[i - 1], r) if i else None
-                t_out = table(r, chain[i + 1]) if i + 1 < len(chain) else None
+                t_in = tables[i - 1] if i else None
+                t_out = tables[i] if i + 1 < len(chain) else None
                 s_in = stage[(i + 1) & 1] if i else None
                 s_out = stage[i & 1] if i + 1 < len(chain) else None
                 if i < m:                     # excluded ranks add themselves up
@@ -199,3 +207,4 @@ def recursive_sim(bufs: Sequence[np.ndarray], dtype: int, levels: Sequence[Level
             bufs[r][lo:hi] = segs[r]
         lo = hi
     assert lo == bufs[0].size
+    return trace

@@ -154,6 +154,12 @@ def test_selector_prefers_balance_for_small_messages():
     assert (small, large) == (0, 1)
 
 
+def test_selector_ties_go_to_the_shallower_plan():
+    """Nothing to move and no latency: every depth takes time 0; the plain balanced ring is chosen."""
+    depth, times = rec.select_depth(EQ8, [0b1111, 0b11, 0, 0], 1, 0, 0, 1)
+    assert times == [0, 0, 0] and depth == 0
+
+
 def test_time_is_monotone_in_alpha_and_bytes():
     lv = rec.plan(EQ8, [0b1111, 0b11, 0, 0])
     t = lambda b, a: rec.completion_time(lv, 4, 1, b, a, F(1, 1000))
@@ -219,11 +225,44 @@ def test_one_degraded_rank_reproduces_the_split_schedule(dtype):
     ng, npart = R * 2 * per16 * 5, (R - 1) * 3 * per16 * 3
     xs = _inputs(rng, R, ng + npart, dtype)
     a = [x.copy() for x in xs]
-    rec.recursive_sim(a, dtype, lv, [ng, npart], 1, C, 32, w, masks)
+    trace = rec.recursive_sim(a, dtype, lv, [ng, npart], 1, C, 32, w, masks)
     b = [x.copy() for x in xs]
-    sp.split_sim(b, dtype, d, npart, 1, 1, C, 32, w, masks[d])
+    t_two, stage = sp.split_sim(b, dtype, d, npart, 1, 1, C, 32, w, masks[d])
     for r in range(R):
         assert a[r].tobytes() == b[r].tobytes()
+    # the broadcast's links and stage buffers too: links that touch d are cut by d's channel state
+    assert trace[0] is None
+    chain, tables, st = trace[1]
+    assert chain == [d] + [(d + 1 + i) % R for i in range(R - 1)] + [d]
+    for i in range(len(chain) - 1):
+        touches_d = d in (chain[i], chain[i + 1])
+        assert tables[i].tolist() == t_two[0 if touches_d else 1].tolist()
+    for par in range(2):
+        for c in range(C):
+            assert st[par][c].tobytes() == stage[par][c].tobytes()
+
+
+def test_links_are_cut_by_both_ends():
+    """A link's table is the partition under the failed channels of BOTH its ends: a channel that either
+    end has lost carries nothing; by hand for one link of a chain with two excluded ranks."""
+    w = [1, 1, 1, 1]
+    masks = [0b0011, 0b0100, 0, 0]           # own bandwidth 2, 3, 4, 4
+    lv = rec.plan(w, masks)
+    assert [l.members for l in lv] == [[0, 1, 2, 3], [1, 2, 3], [2, 3]]
+    elems = [4 * 16, 3 * 16, 2 * 32]
+    xs = _inputs(np.random.default_rng(3), 4, sum(elems), o.F32)
+    trace = rec.recursive_sim([x.copy() for x in xs], o.F32, lv, elems, 1, 4, 16, w, masks)
+    chain, tables, _ = trace[2]
+    assert chain == [0, 1, 2, 3, 0, 1]
+    nbytes = elems[2] * 4                     # 256 bytes
+    # link 0 -> 1: channels 0, 1 (rank 0) and 2 (rank 1) are down: everything rides on channel 3
+    assert tables[0].tolist() == [0, 0, 0, 0, nbytes]
+    # link 1 -> 2: only channel 2 is down: thirds of 256 in units of 16 bytes: 5, 5 and 6 units
+    assert tables[1].tolist() == [0, 80, 160, 160, nbytes]
+    # link 2 -> 3: nothing down: quarters
+    assert tables[2].tolist() == [0, 64, 128, 192, nbytes]
+    # link 3 -> 0: rank 0's state
+    assert tables[3].tolist() == [0, 0, 0, 128, nbytes]
 
 
 def test_chain_order():
@@ -267,6 +306,11 @@ def test_host_planner_matches_oracle(r2):
         # the choice may differ only where two depths tie to rounding
         assert depth == odepth or abs(times[depth] - times[odepth]) <= 1e-12 * times[odepth]
     assert n_multi > 100
+
+
+def test_host_selector_ties_go_to_the_shallower_plan(r2):
+    depth, times = r2.r2_select_strategy(EQ8, [0b1111, 0b11, 0, 0], 1, 0.0, 0.0, 1.0)
+    assert times == [0.0, 0.0, 0.0] and depth == 0
 
 
 def test_host_planner_rejects_bad_arguments(r2):
