@@ -300,7 +300,10 @@ double r2_split_time(uint32_t n_servers, uint32_t gpus_per_server, double lost_f
  * buffer type after every addition, and in the head the plain ring all-reduce.
  * n_partial = 0 is the plain all-reduce.  (n_elems - n_partial) * element size must be a multiple
  * of 16; the head must divide into n_slabs_global * R chunks and the tail into
- * n_slabs_partial * (R-1) chunks.  The two stage-1 runs are issued one after the other on `stream`. */
+ * n_slabs_partial * (R-1) chunks.  Head and tail run side by side: the global ring on `stream`, the
+ * partial ring and its broadcast on a library-owned stream (default priority, created once per
+ * device) that is forked off `stream` and joined to it again with events at the end of the call, so
+ * the call stays in order on `stream`. */
 typedef struct {
     uint32_t n_ranks;         /* R, 3..R2_MAX_RANKS                          */
     uint32_t degraded_rank;   /* d < R                                       */
@@ -388,10 +391,12 @@ int r2_select_strategy(uint32_t n_ranks, uint32_t gpus_per_rank, uint32_t n_chan
  *      on, and the excluded ranks copy it and pass it along in ascending order.  The transfer between
  *      two ranks is cut by the union of their failed channels.
  * Afterwards every rank holds, in segment k, fold(members in that order) + (running sum of the
- * excluded ranks), rounded to the buffer type after every addition.  The levels are issued one
- * after the other on `stream` (the paper runs the reductions concurrently on disjoint channel
- * groups; the result is the same).  Every segment's byte size must be a multiple of 16 and divide
- * into n_slabs * members_k chunks; level_elems sums to n_elems; a level may be empty. */
+ * excluded ranks), rounded to the buffer type after every addition.  The levels touch disjoint
+ * segments and have workspaces of their own, so they run side by side, as the paper's reductions
+ * do: level k on one of a few library-owned streams (default priority, created once per device),
+ * forked off `stream` and joined to it again with events before the call returns to the caller's
+ * order.  Every segment's byte size must be a multiple of 16 and divide into n_slabs * members_k
+ * chunks; level_elems sums to n_elems; a level may be empty. */
 typedef struct {
     uint32_t n_ranks;    /* R, 2..R2_MAX_RANKS                      */
     uint32_t n_channels; /* C                                       */
@@ -404,8 +409,8 @@ typedef struct {
     uint64_t n_elems;    /* elements per rank                       */
 } r2_recursive_desc;
 
-/* Workspace (device, 256-byte aligned): the largest ring workspace of any level, the broadcast's
- * offsets tables and its double-buffered stage.  0 if an argument is invalid. */
+/* Workspace (device, 256-byte aligned): per level, its ring workspace, its broadcast's offsets
+ * tables and double-buffered stage.  0 if an argument is invalid. */
 uint64_t r2_recursive_workspace_bytes(const r2_recursive_desc *desc, const r2_level *levels,
                                       const uint64_t *level_elems);
 

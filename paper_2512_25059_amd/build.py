@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", f) for f in ("partition.hip", "ring.hip", "split.hip", "recursive.hip", "rerank.cpp")]
+SOURCES = [os.path.join(HERE, "csrc", f) for f in ("partition.hip", "ring.hip", "split.hip", "recursive.hip", "streams.hip", "rerank.cpp")]
 HEADERS = [os.path.join(HERE, "csrc", "r2_internal.h"), os.path.join(HERE, "csrc", "partition_device.h"),
            os.path.join(ROOT, "include", "r2ccl.h")]
 LIB = os.path.join(HERE, "libr2ccl.so")

@@ -27,4 +27,30 @@ int launch_partition_epochs(const r2_epoch *epochs, uint32_t n_epochs, uint32_t 
                             uint64_t chunk_bytes, uint64_t n_tx, uint64_t *tables, uint64_t *log,
                             hipStream_t stream);
 
+// Independent pieces of one call (the rings of a split or recursive all-reduce) run side by side:
+// the caller's stream forks into a few library-owned streams of default priority and joins them
+// again before the call's dependent work, all with events, so the call stays asynchronous and in
+// order on the caller's stream (and can be captured into a graph).  The streams are created once
+// per device and live until the process ends.
+constexpr unsigned kSideStreams = 3;
+
+class ForkJoin {
+public:
+    // Lane 0 is the caller's stream, lanes 1..kSideStreams the library's.  rc() is R2_OK unless a
+    // runtime call failed; after a failure the remaining calls do nothing.
+    explicit ForkJoin(hipStream_t user);
+    ~ForkJoin();
+    ForkJoin(const ForkJoin &) = delete;
+    ForkJoin &operator=(const ForkJoin &) = delete;
+    hipStream_t lane(unsigned i);  // lane i, forked off the caller's stream where this object was made
+    int join();                    // the caller's stream waits for every lane that was used
+    int rc() const { return rc_; }
+
+private:
+    hipStream_t user_;
+    struct Pool *pool_;
+    bool used_[kSideStreams] = {};
+    int rc_ = R2_OK;
+};
+
 }  // namespace r2

@@ -48,12 +48,13 @@ void chain_order(uint32_t R, uint64_t members, uint32_t *excl, uint32_t &m, uint
 struct LevelShape {
     r2_sim_desc ring;
     uint64_t bytes, cap, ws_ring;
+    uint64_t ring_off, tables_off, stage_off;  // the level's own part of the workspace
     uint32_t m, p, hops;
 };
 
 struct RecShape {
     LevelShape lv[R2_MAX_LEVELS];
-    uint64_t elem, ws_ring, tables_off, stage_off, total;
+    uint64_t elem, total;
 };
 
 int rec_shape(const r2_recursive_desc *d, const r2_level *levels, const uint64_t *level_elems, RecShape &s)
@@ -67,8 +68,8 @@ int rec_shape(const r2_recursive_desc *d, const r2_level *levels, const uint64_t
     const uint32_t R = d->n_ranks;
     const uint64_t all = R == 64 ? ~0ull : ((1ull << R) - 1);
     s.elem = d->dtype == R2_F32 ? 4 : 2;
-    s.ws_ring = 0;
-    uint64_t sum = 0, max_cap = 0, max_hops = 0, prev = all;
+    s.total = 0;
+    uint64_t sum = 0, prev = all;
     for (uint32_t k = 0; k < d->n_levels; ++k) {
         LevelShape &l = s.lv[k];
         const uint64_t mem = levels[k].members;
@@ -87,19 +88,17 @@ int rec_shape(const r2_recursive_desc *d, const r2_level *levels, const uint64_t
         l.ring = r2_sim_desc{l.p, d->n_slabs, d->n_channels, d->align, n, d->dtype, R2_PHASE_RS | R2_PHASE_AG, 0,
                              d->schedule, 0};
         l.ws_ring = 0;
+        l.ring_off = l.tables_off = l.stage_off = s.total;
         if (n) {
             if (r2_sim_num_steps(&l.ring) == 0) return R2_ERR_INVALID;
             l.ws_ring = round_up(r2_sim_workspace_bytes(&l.ring), kAlign256);
             if (l.ws_ring == 0) return R2_ERR_INVALID;
-            if (l.ws_ring > s.ws_ring) s.ws_ring = l.ws_ring;
-            if (l.m && l.cap > max_cap) max_cap = l.cap;
-            if (l.hops > max_hops) max_hops = l.hops;
+            l.tables_off = l.ring_off + l.ws_ring;
+            l.stage_off = l.tables_off + round_up(l.hops * (uint64_t)(d->n_channels + 1) * 8, kAlign256);
+            s.total = l.stage_off + (l.m ? 2 * (uint64_t)d->n_channels * l.cap : 0);
         }
     }
     if (sum != d->n_elems) return R2_ERR_INVALID;
-    s.tables_off = s.ws_ring;
-    s.stage_off = s.tables_off + round_up(max_hops * (uint64_t)(d->n_channels + 1) * 8, kAlign256);
-    s.total = s.stage_off + 2 * (uint64_t)d->n_channels * max_cap;
     if (s.total == 0) s.total = kAlign256;
     return R2_OK;
 }
@@ -246,15 +245,21 @@ extern "C" int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *c
     }
 
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    uint64_t *tables = reinterpret_cast<uint64_t *>(ws + s.tables_off);
     const r2_dtype dt = (r2_dtype)desc->dtype;
     uint64_t lo = 0;  // first element of the level's segment
     r2_epoch links[3 * R2_MAX_RANKS];
+    // The levels work on disjoint segments with workspaces of their own: each runs, ring and
+    // broadcast chain, on a lane of its own, side by side with the others.
+    r2::ForkJoin lanes((hipStream_t)stream);
+    if (lanes.rc()) return lanes.rc();
+    uint32_t n_busy = 0;
     for (uint32_t k = 0; k < desc->n_levels; ++k) {
         const LevelShape &l = s.lv[k];
         const uint64_t seg_off = lo * s.elem;
         lo += level_elems[k];
         if (level_elems[k] == 0) continue;
+        void *const lane = lanes.lane(n_busy++ % (r2::kSideStreams + 1));
+        uint64_t *tables = reinterpret_cast<uint64_t *>(ws + l.tables_off);
         uint32_t m, p;
         chain_order(R, levels[k].members, excl, m, order, p);
 
@@ -262,7 +267,7 @@ extern "C" int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *c
         void *seg[R2_MAX_RANKS];
         for (uint32_t i = 0; i < p; ++i) seg[i] = static_cast<uint8_t *>(rank_bufs[order[i]]) + seg_off;
         const r2_epoch state = {0, levels[k].fail_mask & full, weights};
-        rc = r2_ring_allreduce_sim(&l.ring, seg, &state, 1, ws, l.ws_ring, nullptr, stream);
+        rc = r2_ring_allreduce_sim(&l.ring, seg, &state, 1, ws + l.ring_off, l.ws_ring, nullptr, lane);
         if (rc) return rc;
         if (!m) continue;
 
@@ -274,11 +279,11 @@ extern "C" int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *c
         for (uint32_t i = 0; i + 1 < n; ++i)
             links[i] = r2_epoch{i, (fail_masks[chain[i]] | fail_masks[chain[i + 1]]) & full, weights};
         rc = r2::launch_partition_epochs(links, n - 1, C, desc->align, l.bytes, n - 1, tables, nullptr,
-                                         (hipStream_t)stream);
+                                         (hipStream_t)lane);
         if (rc) return rc;
         void *stage[2][R2_MAX_CHANNELS];
         for (uint32_t par = 0; par < 2; ++par)
-            for (uint32_t c = 0; c < C; ++c) stage[par][c] = ws + s.stage_off + ((uint64_t)par * C + c) * l.cap;
+            for (uint32_t c = 0; c < C; ++c) stage[par][c] = ws + l.stage_off + ((uint64_t)par * C + c) * l.cap;
         for (uint32_t i = 0; i < n; ++i) {
             const bool first = i == 0, last = i + 1 == n;
             int op;
@@ -289,9 +294,9 @@ extern "C" int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *c
             void *local = static_cast<uint8_t *>(rank_bufs[chain[i]]) + seg_off;
             rc = r2_reduce_copy(local, l.bytes, dt, op, first ? nullptr : stage[(i + 1) & 1],
                                 first ? nullptr : tables + (uint64_t)(i - 1) * (C + 1), last ? nullptr : stage[i & 1],
-                                last ? nullptr : tables + (uint64_t)i * (C + 1), C, l.cap, nullptr, stream);
+                                last ? nullptr : tables + (uint64_t)i * (C + 1), C, l.cap, nullptr, lane);
             if (rc) return rc;
         }
     }
-    return R2_OK;
+    return lanes.join();
 }

@@ -105,6 +105,13 @@ extern "C" int r2_split_allreduce_sim(const r2_split_desc *desc, void *const *ra
     const r2_epoch degraded = {0, degraded_fail_mask, weights};
     const r2_epoch healthy = {0, 0, weights};
 
+    // The head and the tail of the buffers are disjoint and have workspaces of their own, so the two
+    // run side by side, as the paper's stage-1 rings do: the global ring on the caller's stream, the
+    // partial ring and, behind it, its broadcast on a stream forked off the caller's.
+    r2::ForkJoin lanes((hipStream_t)stream);
+    if (lanes.rc()) return lanes.rc();
+    void *const tail = s.n_global ? (void *)lanes.lane(1) : stream;
+
     // Stage 1a: global all-reduce of the head of every buffer, over all ranks; the ring passes
     // through the degraded server, so its channel state governs.
     if (s.n_global) {
@@ -120,7 +127,8 @@ extern "C" int r2_split_allreduce_sim(const r2_split_desc *desc, void *const *ra
         order[i] = (d + 1 + i) % R;
         part[i] = static_cast<uint8_t *>(rank_bufs[order[i]]) + s.n_global * s.elem;
     }
-    rc = r2_ring_allreduce_sim(&s.partial, part, &healthy, 1, ws + s.ws_global, s.ws_partial, nullptr, stream);
+    rc = r2_ring_allreduce_sim(&s.partial, part, &healthy, 1, ws + s.ws_global, s.ws_partial, nullptr,
+                               tail);
     if (rc) return rc;
 
     // Stage 2: the tailored broadcast.  d sends its own tail into the healthy ring; every healthy
@@ -129,7 +137,7 @@ extern "C" int r2_split_allreduce_sim(const r2_split_desc *desc, void *const *ra
     // between healthy ranks by the full state (table 1).
     uint64_t *tables = reinterpret_cast<uint64_t *>(ws + s.tables_off);
     const r2_epoch two[2] = {{0, degraded_fail_mask, weights}, {1, 0, weights}};
-    rc = r2::launch_partition_epochs(two, 2, C, desc->align, s.part_bytes, 2, tables, nullptr, (hipStream_t)stream);
+    rc = r2::launch_partition_epochs(two, 2, C, desc->align, s.part_bytes, 2, tables, nullptr, (hipStream_t)tail);
     if (rc) return rc;
     const uint64_t *t_deg = tables, *t_ok = tables + (C + 1);
     void *stage[2][R2_MAX_CHANNELS];
@@ -139,17 +147,19 @@ extern "C" int r2_split_allreduce_sim(const r2_split_desc *desc, void *const *ra
     const r2_dtype dt = (r2_dtype)desc->dtype;
 
     // step 0: d stages its tail
-    rc = r2_reduce_copy(d_tail, s.part_bytes, dt, R2_OP_SUM, nullptr, nullptr, stage[0], t_deg, C, s.cap, nullptr, stream);
+    rc = r2_reduce_copy(d_tail, s.part_bytes, dt, R2_OP_SUM, nullptr, nullptr, stage[0], t_deg, C, s.cap, nullptr, tail);
     if (rc) return rc;
     for (uint32_t k = 1; k + 1 <= R; ++k) {  // k = 1 .. R-1: the healthy ranks in ring order
         const bool last = k == R - 1;
         const uint64_t *t_in = k == 1 ? t_deg : t_ok;
         const uint64_t *t_out = last ? t_deg : t_ok;
         rc = r2_reduce_copy(part[k - 1], s.part_bytes, dt, last ? R2_OP_SUM : R2_OP_SUM_FORWARD,
-                            stage[(k + 1) & 1], t_in, stage[k & 1], t_out, C, s.cap, nullptr, stream);
+                            stage[(k + 1) & 1], t_in, stage[k & 1], t_out, C, s.cap, nullptr, tail);
         if (rc) return rc;
     }
     // step R: d takes the finished result
-    return r2_reduce_copy(d_tail, s.part_bytes, dt, R2_OP_COPY, stage[(R + 1) & 1], t_deg, nullptr, nullptr, C,
-                          s.cap, nullptr, stream);
+    rc = r2_reduce_copy(d_tail, s.part_bytes, dt, R2_OP_COPY, stage[(R + 1) & 1], t_deg, nullptr, nullptr, C, s.cap,
+                        nullptr, tail);
+    if (rc) return rc;
+    return lanes.join();
 }

@@ -59,24 +59,30 @@ def _run(r2, oracle, xs, dtype, plan, elems, S, C, align, weights, masks, schedu
         trace = rec.recursive_sim(o_bufs, odt, plan, elems, S, C, align, weights, masks)
         for r in range(R):
             assert outs[r].tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
-        # The broadcast's link tables and stage buffers sit at the end of the workspace, sized for the
-        # largest chain and re-used level after level: what is left is the last chain's.
-        chains = [t for t in trace if t is not None]
-        if chains:
-            es = xs[0].itemsize
-            caps = [(n * es + 255) // 256 * 256 for t, n in zip(trace, elems) if t is not None]
-            max_hops = max(len(t[0]) - 1 for t in chains)
-            stage_bytes = 2 * C * max(caps)
-            tab_bytes = (max_hops * (C + 1) * 8 + 255) // 256 * 256
-            chain, tables, stage = chains[-1]
-            cap = caps[-1]
-            got_tab = ws[need - stage_bytes - tab_bytes: need - stage_bytes - tab_bytes + tables.size * 8]
-            assert got_tab.cpu().numpy().view(np.uint64).reshape(tables.shape).tolist() == tables.tolist(), "link tables"
-            if len(chains) == 1:  # with several chains the buffers also hold what earlier chains left behind
-                got_stage = ws[need - stage_bytes: need - stage_bytes + 2 * C * cap].cpu().numpy().reshape(2, C, cap)
-                for par in range(2):
-                    for c in range(C):
-                        assert got_stage[par, c].tobytes() == stage[par][c].tobytes(), f"chain stage parity {par} channel {c}"
+        # Every level has its own part of the workspace: ring workspace, link tables, chain stage.
+        es = xs[0].itemsize
+        up = lambda x: (x + 255) // 256 * 256
+        at = 0
+        for lv, n, tr in zip(plan, elems, trace):
+            if n == 0:
+                continue
+            p = len(lv.members)
+            ring = r2.SimDesc(p, S, C, align, n, gdt, r2.PHASE_AR, 0, schedule)
+            at += up(r2.r2_sim_workspace_bytes(ring))
+            if tr is None:
+                continue
+            chain, tables, stage = tr
+            cap = up(n * es)
+            got_tab = ws[at: at + tables.size * 8].cpu().numpy().view(np.uint64).reshape(tables.shape)
+            assert got_tab.tolist() == tables.tolist(), f"link tables of the ring over {lv.members}"
+            at += up((len(chain) - 1) * (C + 1) * 8)
+            got_stage = ws[at: at + 2 * C * cap].cpu().numpy().reshape(2, C, cap)
+            for par in range(2):
+                for c in range(C):
+                    assert got_stage[par, c].tobytes() == stage[par][c].tobytes(), \
+                        f"chain stage of the ring over {lv.members}: parity {par} channel {c}"
+            at += 2 * C * cap
+        assert at == need
     return outs
 
 
