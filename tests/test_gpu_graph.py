@@ -56,3 +56,46 @@ def test_ring_run_in_a_graph(r2, oracle, schedule):
             got = bufs[r].cpu().numpy().view(xs[r].dtype)
             assert np.array_equal(got, want[r]), f"replay {replay}, rank {r}"
         assert log.cpu().numpy().any()
+
+
+def test_split_run_in_a_graph(r2, oracle):
+    """The split all-reduce forks the caller's stream into a library-owned one and joins it again with
+    events; captured, that becomes a fork and a join inside the graph."""
+    from oracle import split
+
+    rng = np.random.default_rng(77)
+    R, d, C = 5, 2, 8
+    ng, npart = R * 8 * 700, (R - 1) * 8 * 300
+    xs = []
+    for _ in range(R):
+        x = torch.from_numpy(rng.standard_normal(ng + npart).astype(np.float32) * 0.02)
+        xs.append(x.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy())
+    weights, mask = [50000] * C, 0b00110000
+    want = split.split_expected(xs, oracle.BF16, d, npart, 1, 1)
+    desc = r2.SplitDesc(R, d, C, 256, ng + npart, npart, r2.BF16, 0, 1, 1)
+    pristine = [to_device(x) for x in xs]
+    bufs = [p.clone() for p in pristine]
+    ws = torch.empty(r2.r2_split_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+
+    say("graph capture of the split all-reduce")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        r2.r2_split_allreduce_sim(desc, bufs, weights, mask, ws)  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        r2.r2_split_allreduce_sim(desc, bufs, weights, mask, ws)
+    for replay in range(3):
+        say(f"split graph replay {replay}")
+        for b, p in zip(bufs, pristine):
+            b.copy_(p)
+        junk = torch.randn(1 << 16, device="cuda").sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for r in range(R):
+            got = bufs[r].cpu().numpy().view(np.uint16)
+            assert np.array_equal(got, want[r]), f"replay {replay}, rank {r}"
