@@ -11,6 +11,8 @@ SOURCES = [os.path.join(HERE, "csrc", f) for f in ("partition.hip", "ring.hip", 
 HEADERS = [os.path.join(HERE, "csrc", "r2_internal.h"), os.path.join(HERE, "csrc", "partition_device.h"),
            os.path.join(ROOT, "include", "r2ccl.h")]
 LIB = os.path.join(HERE, "libr2ccl.so")
+EXAMPLE_SRC = os.path.join(HERE, "examples", "ring_allreduce.c")
+EXAMPLE = os.path.join(HERE, "examples", "ring_allreduce")
 
 # Packed-fp32 instructions are switched off for all device code.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -38,7 +40,23 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    build_example(verbose)
     return LIB
+
+
+def build_example(verbose: bool = False) -> str:
+    """The plain-C caller of the ABI: compiled with gcc against the header and the library just built."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-O2", "-std=c11", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(rocm, "include"),
+           "-I" + os.path.join(ROOT, "include"), EXAMPLE_SRC, "-L" + HERE, "-lr2ccl",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN/..",
+           "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", EXAMPLE]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed on the C example:\n" + res.stdout)
+    return EXAMPLE
 
 
 if __name__ == "__main__":
