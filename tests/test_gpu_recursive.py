@@ -112,6 +112,37 @@ def test_recursive_small(r2, oracle, dtype, schedule):
             _run(r2, oracle, xs, dtype, plan, elems, S, C, 16, weights, masks, schedule)
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_recursive_random_failure_patterns(r2, oracle, seed):
+    """Random failure patterns: ranks lose random channels (one channel is kept up everywhere so that the
+    global ring exists), random weights, types, schedules and segment sizes."""
+    rng = np.random.default_rng(600 + seed)
+    n_multi = 0
+    for case in range(15):
+        R, C = int(rng.integers(2, 10)), int(rng.integers(2, 9))
+        weights = [int(x) for x in rng.integers(1, 1000, C)]
+        keep = int(rng.integers(0, C))
+        masks = []
+        for _ in range(R):
+            m = 0
+            if rng.random() < 0.6:
+                m = int(rng.integers(0, 1 << C)) & ~(1 << keep)
+            masks.append(m)
+        plan = rec.plan(weights, masks)
+        n_multi += len(plan) > 2
+        dtype = "f32" if rng.random() < 0.5 else "bf16"
+        per16 = 4 if dtype == "f32" else 8
+        S = int(rng.integers(1, 3))
+        schedule = int(rng.integers(0, 3))
+        elems = [S * len(l.members) * per16 * int(rng.integers(0, 40)) for l in plan]
+        if sum(elems) == 0:
+            elems[0] = S * R * per16
+        say(f"recursive random {seed}.{case} {dtype} sched={schedule} R={R} C={C} masks={masks} levels={len(plan)} elems={elems}")
+        xs = _inputs(rng, R, sum(elems), dtype)
+        _run(r2, oracle, xs, dtype, plan, elems, S, C, (16, 256)[int(rng.integers(0, 2))], weights, masks, schedule)
+    assert n_multi >= 3
+
+
 def test_recursive_empty_levels_and_truncated_plans(r2, oracle):
     rng = np.random.default_rng(51)
     weights, masks = [50000] * 8, [0b1111, 0b0011, 0, 0, 0b0001]

@@ -260,6 +260,43 @@ def test_sim_chunks_beyond_4GiB(r2, oracle):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_sim_random_configurations(r2, oracle, seed):
+    """Random small configurations -- ring size, slabs, channels, chunk size (ragged included), alignment,
+    type, phases, schedule, pass window, channel states that change at random transmissions -- each compared
+    in full (buffers, offsets log, stage area where it is comparable) with the oracle."""
+    from dataclasses import replace
+
+    rng = np.random.default_rng(9000 + seed)
+    for case in range(25):
+        R = int(rng.integers(2, 21))
+        S = int(rng.integers(1, 6))
+        C = int(rng.integers(1, 13))
+        dtype = "f32" if rng.random() < 0.5 else "bf16"
+        phases = ("ar", "rs", "ag")[int(rng.integers(0, 3))]
+        schedule = int(rng.integers(1, 3))
+        es = 4 if dtype == "f32" else 2
+        if schedule == 2 or rng.random() < 0.5:
+            E = int(rng.integers(1, 400)) * (16 // es)       # whole 16-byte vectors (needed by the fused schedule)
+        else:
+            E = int(rng.integers(1, 3000))                    # anything, element path included
+        align = (16, 32, 256)[int(rng.integers(0, 3))]
+        J1 = (2 * R - 2) if phases == "ar" else (R - 1)
+        T = S * J1
+        eps, t0 = [], 0
+        while t0 < T:
+            mask = int(rng.integers(0, (1 << C) - 1)) if C > 1 else 0       # never every channel
+            weights = tuple(int(x) for x in rng.integers(1, 60000, C))
+            eps.append((t0, mask, weights))
+            t0 += int(rng.integers(1, max(2, T)))
+        window = 0 if rng.random() < 0.5 else int(rng.integers(1, 8)) * R * E * es // 2 + 256
+        w = replace(wl.cfg1(), name=f"random{seed}_{case}", R=R, dtype=dtype, N=R * S * E, S=S, C=C, align=align,
+                    phases=phases, sigma=1.0, seed=1000 * seed + case, epochs=tuple(eps))
+        # with several passes and several states the stage area's leftovers depend on the pass order
+        one_pass = window == 0
+        _full_compare_small(r2, oracle, w, window=window, check_stage=one_pass or len(eps) == 1, schedule=schedule)
+
+
 def test_sim_result_independent_of_schedule(r2, oracle):
     """Lossless whatever the failure timing: different schedules, same bits."""
     from dataclasses import replace
