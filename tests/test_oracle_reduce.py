@@ -91,6 +91,28 @@ def _rand_epochs(rng, C, T_total):
     return eps
 
 
+def test_three_ranks_by_hand(oracle):
+    """R = 3, one element per ring chunk, inputs 1 2 3 | 10 20 30 | 100 200 300, worked with pencil.
+    Reduce-scatter alone: chunk c starts at rank c and collects one more term per hop, so rank r holds at
+    chunk c the fold of ranks c .. r (cyclically); the all-gather then spreads the full sums; an all-gather
+    alone passes each rank's chunk (r + 1) round unchanged."""
+    xs = [np.array(v, dtype=np.float32) for v in ([1, 2, 3], [10, 20, 30], [100, 200, 300])]
+    eps = [(0, 0, (1, 1))]
+
+    def run(phases):
+        bufs = [x.copy() for x in xs]
+        oracle.ring_sim(bufs, F32, 1, 2, 4, eps, phases)
+        return [b.tolist() for b in bufs], [e.tolist() for e in oracle.expected(xs, F32, 1, phases)]
+
+    want_rs = [[1, 222, 303], [11, 20, 333], [111, 220, 300]]
+    want_ar = [[111, 222, 333]] * 3
+    want_ag = [[100, 2, 30]] * 3  # rank r contributes chunk r+1 of its own buffer: 2, 30 and (rank 2) chunk 0 = 100
+    for phases, want in ((1, want_rs), (3, want_ar), (2, want_ag)):
+        got, by_definition = run(phases)
+        assert got == want, phases
+        assert by_definition == want, phases
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("phases", [1, 2, 3])
 def test_ring_sim_vs_python_ring_and_definition(oracle, dtype, phases):
