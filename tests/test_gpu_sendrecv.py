@@ -101,3 +101,26 @@ def test_sendrecv_argument_errors(r2):
         r2.r2_sim_fused_steps(desc, sb + rb, 0, 2, ws)
     torch.cuda.synchronize()
     assert all(float(t.sum()) == 0.0 for t in rb)  # nothing ran
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_sendrecv_random_configurations(r2, oracle, seed):
+    """Random ring sizes, chunk counts and sizes (ragged included), channel counts, alignments, pass windows
+    and channel states that change between chunks."""
+    rng = np.random.default_rng(800 + seed)
+    for case in range(20):
+        R, S, C = int(rng.integers(2, 17)), int(rng.integers(1, 9)), int(rng.integers(1, 13))
+        dtype = "f32" if rng.random() < 0.5 else "bf16"
+        es = 4 if dtype == "f32" else 2
+        E = int(rng.integers(1, 5000))
+        align = (16, 64, 256)[int(rng.integers(0, 3))]
+        eps, t0 = [], 0
+        while t0 < S:
+            mask = int(rng.integers(0, (1 << C) - 1)) if C > 1 else 0
+            eps.append((t0, mask, [int(x) for x in rng.integers(1, 60000, C)]))
+            t0 += int(rng.integers(1, S + 1))
+        window = 0 if rng.random() < 0.5 else int(rng.integers(1, 6)) * R * E * es // 2 + 256
+        send = [rng.integers(0, 1 << 16, S * E).astype(np.uint16) if dtype == "bf16"
+                else rng.standard_normal(S * E).astype(np.float32) for _ in range(R)]
+        say(f"sendrecv random {seed}.{case} {dtype} R={R} S={S} C={C} E={E} align={align} window={window} epochs={len(eps)}")
+        _run(r2, oracle, send, dtype, S, C, align, eps, window=window, check_stage=window == 0 or len(eps) == 1)
