@@ -198,7 +198,7 @@ typedef struct {
                                     library's default (128 MiB, half the Infinity Cache).  Only
                                     changes how the run is cut into passes, never the result.   */
     int32_t schedule;    /* R2_SCHED_STEPS: one launch per fused step and pass.
-                            R2_SCHED_FUSED: one launch takes every column (2 KiB of each ring chunk)
+                            R2_SCHED_FUSED: one launch takes every column (1 or 2 KiB of each ring chunk)
                             through all steps between two channel-state changes; needs chunks that
                             are a multiple of 16 bytes.
                             R2_SCHED_AUTO (0): FUSED for launch-bound sizes, else STEPS.           */
@@ -235,7 +235,7 @@ int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint64_t pass, 
                 void *workspace, uint64_t workspace_bytes, void *stream);
 
 /* Fused-column schedule: the steps [step_begin, step_end) of every rank and slab in ONE launch.  A
- * workgroup takes a 2 KiB column of the ring chunks of one slab through all these steps, one wave
+ * workgroup takes a column (1 KiB, or 2 KiB once that fills the GPU) of the ring chunks of one slab through all these steps, one wave
  * per rank, with a workgroup barrier between steps; columns are independent of each other and
  * drift apart in time.  Only valid if, for every slab, the transmissions t of equal parity with
  * step_begin-1 <= t <= step_end-1 all use one channel state: otherwise a column that is ahead could

@@ -387,8 +387,12 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
 // the same over the steps of the launch: then a stage location belongs to one column, and columns
 // may drift apart in time without overwriting each other's unread data (see plan_schedule).
 
-constexpr unsigned kColUnroll = 2;                     // vectors per lane: a column is 2 KiB wide
-constexpr unsigned kColBytes = kWave * 16 * kColUnroll;
+// A column is 1 or 2 vectors per lane wide (1 or 2 KiB; template parameter U).  All ranks of a column
+// share one compute unit, so its steps are bound by that unit's instruction issue as much as by the
+// hand-off: while the narrow columns of a run do not fill the GPU they are the faster ones (half the
+// work per step and unit, twice the units busy); wide columns halve the per-column overhead once they do.
+constexpr unsigned kNarrowColBytes = kWave * 16;
+constexpr uint64_t kWideColumnsFrom = 256;  // wide columns from this many of them on (one per compute unit)
 constexpr unsigned kMaxFusedWaves = 16;
 
 struct ColInfo {  // the slice of one transmission's table that holds the column's first byte
@@ -418,19 +422,19 @@ constexpr uint32_t kFusedLdsRowBytes = 48 * 1024;  // at most this much LDS for 
 // that the code is straight-line: all loads of the step are issued before the first use, and
 // nothing waits for the stores.  KIND: 0 copy-send, 1 sum, 2 copy.  The caller supplies, per vector
 // of the lane, the addresses in the incoming stage, the outgoing stage and the local buffer.
-template <int KIND, bool HAS_OUT, bool BF16>
-__device__ inline void column_step(const uint64_t (&ain)[kColUnroll], const uint64_t (&aout)[kColUnroll],
-                                   const uint64_t (&aloc)[kColUnroll])
+template <unsigned U, int KIND, bool HAS_OUT, bool BF16>
+__device__ inline void column_step(const uint64_t (&ain)[U], const uint64_t (&aout)[U],
+                                   const uint64_t (&aloc)[U])
 {
     constexpr bool HAS_IN = KIND != 0, READS_LOCAL = KIND != 2;
-    u32x4 inc[kColUnroll], loc[kColUnroll];
+    u32x4 inc[U], loc[U];
 #pragma unroll
-    for (unsigned u = 0; u < kColUnroll; ++u) {
+    for (unsigned u = 0; u < U; ++u) {
         if constexpr (HAS_IN) inc[u] = load16<false>(ain[u]);
         if constexpr (READS_LOCAL) loc[u] = load16<kNtLocalLoad>(aloc[u]);
     }
 #pragma unroll
-    for (unsigned u = 0; u < kColUnroll; ++u) {
+    for (unsigned u = 0; u < U; ++u) {
         u32x4 v;
         if constexpr (KIND == 0) v = loc[u];
         else if constexpr (KIND == 2) v = inc[u];
@@ -465,15 +469,15 @@ __device__ uint64_t g_dbg[256];
 // PARTITION: the kernel computes the table rows it needs itself, from the channel states in `eb`
 // (every workgroup for its own use, in LDS; the first column of each slab also records them in
 // the workspace and the log), so that no partition launch has to run in front of it.
-template <bool BF16, bool PARTITION>
+template <bool BF16, bool PARTITION, unsigned U>
 __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
 {
     R2_STAMP(0);
     __shared__ ColInfo info[2 * R2_MAX_RANKS];  // by transmission within the slab
     const uint32_t l = (uint32_t)(blockIdx.x / a.cols_per_chunk);
     const uint64_t k = blockIdx.x - (uint64_t)l * a.cols_per_chunk;
-    const uint64_t b0 = k * kColBytes;
-    const uint64_t b1 = b0 + kColBytes < a.chunk_bytes ? b0 + kColBytes : a.chunk_bytes;
+    const uint64_t b0 = k * (kWave * 16 * U);
+    const uint64_t b1 = b0 + (kWave * 16 * U) < a.chunk_bytes ? b0 + (kWave * 16 * U) : a.chunk_bytes;
     const uint32_t C = a.C;
     const uint64_t row = (uint64_t)C + 1;
     const uint64_t *slab_tables = a.tables + (uint64_t)l * a.T_slab * row;
@@ -490,17 +494,17 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint32_t lane = threadIdx.x % kWave, n_waves = blockDim.x / kWave;
     const bool one_rank = a.R <= n_waves;                       // a wave plays one rank
-    const bool ragged_width = b0 + kColBytes > a.chunk_bytes;  // the chunk's last, narrower column
+    const bool ragged_width = b0 + (kWave * 16 * U) > a.chunk_bytes;  // the chunk's last, narrower column
 
     // A launch that starts at step 0 begins with every rank staging a chunk of its own buffer.
     // Where that chunk lies depends on nothing computed below, so its loads are issued first and
     // their latency passes while the tables are made.
     const bool preload = a.j0 == 0 && one_rank && !ragged_width;
-    u32x4 pre[kColUnroll] = {};
+    u32x4 pre[U] = {};
     if (preload) {
         const uint64_t src = a.rank_buf[wave] + ((uint64_t)l * a.R + (wave + a.chunk_start) % a.R) * a.chunk_bytes + b0;
 #pragma unroll
-        for (unsigned u = 0; u < kColUnroll; ++u) pre[u] = load16<kNtLocalLoad>(src + (uint64_t)(u * kWave + lane) * 16);
+        for (unsigned u = 0; u < U; ++u) pre[u] = load16<kNtLocalLoad>(src + (uint64_t)(u * kWave + lane) * 16);
     }
 
     // changed[t]: the table of transmission t may differ from that of t-1.  Tables mostly repeat,
@@ -605,21 +609,21 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         // looks its vectors up in the (LDS) row, without branching.
         uint32_t top = 0;
         while ((top ? top * 2 : 1) < C) top = top ? top * 2 : 1;
-        uint64_t bu[kColUnroll];
+        uint64_t bu[U];
 #pragma unroll
-        for (unsigned u = 0; u < kColUnroll; ++u) bu[u] = b0 + (uint64_t)(u * kWave + lane) * 16;
+        for (unsigned u = 0; u < U; ++u) bu[u] = b0 + (uint64_t)(u * kWave + lane) * 16;
 
         // Stage offset (within one rank's stage of one parity) of each of the lane's vectors under
         // the table of transmission t.
-        auto deltas_for = [&](uint32_t t, uint64_t(&d)[kColUnroll]) {
+        auto deltas_for = [&](uint32_t t, uint64_t(&d)[U]) {
             if (b1 <= info[t].hi) {
                 const uint64_t base = (uint64_t)info[t].c * a.cap - info[t].lo;
 #pragma unroll
-                for (unsigned u = 0; u < kColUnroll; ++u) d[u] = base + bu[u];
+                for (unsigned u = 0; u < U; ++u) d[u] = base + bu[u];
             } else {  // only reached with the rows in LDS
                 const R2_LDS uint64_t *off = lds_rows + (uint64_t)(t - t_first) * row;
 #pragma unroll
-                for (unsigned u = 0; u < kColUnroll; ++u) {
+                for (unsigned u = 0; u < U; ++u) {
                     const uint32_t c = find_channel_flat(off, C, top, bu[u]);
                     d[u] = (uint64_t)c * a.cap - off[c] + bu[u];
                 }
@@ -627,23 +631,23 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         };
         // One rank's share of step j, given where its chunk and its stages are.
         auto rank_step = [&](bool has_in, bool has_out, bool summing, uint64_t local_addr,
-                             uint64_t in_base, uint64_t out_base, const uint64_t(&din)[kColUnroll],
-                             const uint64_t(&dout)[kColUnroll]) {
-            uint64_t ain[kColUnroll], aout[kColUnroll], aloc[kColUnroll];
+                             uint64_t in_base, uint64_t out_base, const uint64_t(&din)[U],
+                             const uint64_t(&dout)[U]) {
+            uint64_t ain[U], aout[U], aloc[U];
 #pragma unroll
-            for (unsigned u = 0; u < kColUnroll; ++u) {
+            for (unsigned u = 0; u < U; ++u) {
                 ain[u] = in_base + din[u];
                 aout[u] = out_base + dout[u];
                 aloc[u] = local_addr + bu[u];
             }
             if (!has_in) {
-                column_step<0, true, BF16>(ain, aout, aloc);
+                column_step<U, 0, true, BF16>(ain, aout, aloc);
             } else if (summing) {
-                if (has_out) column_step<1, true, BF16>(ain, aout, aloc);
-                else column_step<1, false, BF16>(ain, aout, aloc);
+                if (has_out) column_step<U, 1, true, BF16>(ain, aout, aloc);
+                else column_step<U, 1, false, BF16>(ain, aout, aloc);
             } else {
-                if (has_out) column_step<2, true, BF16>(ain, aout, aloc);
-                else column_step<2, false, BF16>(ain, aout, aloc);
+                if (has_out) column_step<U, 2, true, BF16>(ain, aout, aloc);
+                else column_step<U, 2, false, BF16>(ain, aout, aloc);
             }
         };
 
@@ -659,7 +663,7 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
 
         // The table a step reads with is the one the step before wrote with, and tables mostly
         // repeat from step to step, so the offsets are carried along and looked up only on change.
-        uint64_t dcur[kColUnroll];
+        uint64_t dcur[U];
         if (one_rank) {
             // A wave that plays one rank runs the steps as up to five stretches of one kind each --
             // copy-send, sums that stage onward, a last sum, copies that stage onward, a last copy --
@@ -692,28 +696,28 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                     // Sums: the local chunk of step j+1 is untouched until then, so it is loaded
                     // during step j, behind step j's own loads, and is in registers when its turn
                     // comes.  Two register sets alternate; the barrier does not wait for loads.
-                    u32x4 set_a[kColUnroll], set_b[kColUnroll];
+                    u32x4 set_a[U], set_b[U];
                     // AHEAD is a compile-time choice so that each variant is straight-line code and
                     // the waits the compiler places count exactly the loads that variant issued.
-                    auto sum_step = [&](auto ahead_tag, u32x4(&cur)[kColUnroll], u32x4(&nxt)[kColUnroll]) {
+                    auto sum_step = [&](auto ahead_tag, u32x4(&cur)[U], u32x4(&nxt)[U]) {
                         constexpr bool AHEAD = decltype(ahead_tag)::value;
                         const uint64_t in_base = my_in0 + ((j + 1) & 1 ? parity_stride : 0);
                         const uint64_t out_base = my_out0 + (j & 1 ? parity_stride : 0);
-                        u32x4 inc[kColUnroll];
-                        uint64_t aloc[kColUnroll];
+                        u32x4 inc[U];
+                        uint64_t aloc[U];
 #pragma unroll
-                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                        for (unsigned u = 0; u < U; ++u) {
                             inc[u] = load16<false>(in_base + dcur[u]);
                             aloc[u] = loc + bu[u];
                         }
                         next_chunk();
                         if constexpr (AHEAD) {
 #pragma unroll
-                            for (unsigned u = 0; u < kColUnroll; ++u) nxt[u] = load16<kNtLocalLoad>(loc + bu[u]);
+                            for (unsigned u = 0; u < U; ++u) nxt[u] = load16<kNtLocalLoad>(loc + bu[u]);
                         }
                         if (table_changes_at(j)) deltas_for(j, dcur);
 #pragma unroll
-                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                        for (unsigned u = 0; u < U; ++u) {
                             const u32x4 v = combine<BF16 ? kSumBF16 : kSumF32>(inc[u], cur[u]);
                             store16<kNtLocalStore>(aloc[u], v);
                             store16<false>(out_base + dcur[u], v);
@@ -726,7 +730,7 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                     using No = std::integral_constant<bool, false>;
                     if (j < j_end) {
 #pragma unroll
-                        for (unsigned u = 0; u < kColUnroll; ++u) set_a[u] = load16<kNtLocalLoad>(loc + bu[u]);
+                        for (unsigned u = 0; u < U; ++u) set_a[u] = load16<kNtLocalLoad>(loc + bu[u]);
                         for (;;) {
                             if (j + 1 >= j_end) {
                                 sum_step(No{}, set_a, set_b);
@@ -745,19 +749,19 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                 if constexpr (KIND == 2) {
                     // Copies: two register sets alternate here too, so that a step's loads never
                     // have to wait until the previous step's stores have read their data.
-                    u32x4 set_a[kColUnroll], set_b[kColUnroll];
-                    auto copy_step = [&](u32x4(&buf)[kColUnroll]) {
+                    u32x4 set_a[U], set_b[U];
+                    auto copy_step = [&](u32x4(&buf)[U]) {
                         const uint64_t in_base = my_in0 + ((j + 1) & 1 ? parity_stride : 0);
                         const uint64_t out_base = my_out0 + (j & 1 ? parity_stride : 0);
-                        uint64_t aloc[kColUnroll];
+                        uint64_t aloc[U];
 #pragma unroll
-                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                        for (unsigned u = 0; u < U; ++u) {
                             buf[u] = load16<false>(in_base + dcur[u]);
                             aloc[u] = loc + bu[u];
                         }
                         if (HAS_OUT && table_changes_at(j)) deltas_for(j, dcur);
 #pragma unroll
-                        for (unsigned u = 0; u < kColUnroll; ++u) {
+                        for (unsigned u = 0; u < U; ++u) {
                             store16<kNtLocalStore>(aloc[u], buf[u]);
                             if constexpr (HAS_OUT) store16<false>(out_base + dcur[u], buf[u]);
                         }
@@ -776,16 +780,16 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                 for (; j < j_end; ++j) {
                     const uint64_t in_base = my_in0 + ((j + 1) & 1 ? parity_stride : 0);
                     const uint64_t out_base = my_out0 + (j & 1 ? parity_stride : 0);
-                    uint64_t ain[kColUnroll], aout[kColUnroll], aloc[kColUnroll];
+                    uint64_t ain[U], aout[U], aloc[U];
 #pragma unroll
-                    for (unsigned u = 0; u < kColUnroll; ++u) {
+                    for (unsigned u = 0; u < U; ++u) {
                         ain[u] = in_base + dcur[u];
                         aloc[u] = loc + bu[u];
                     }
                     if (HAS_OUT && table_changes_at(j)) deltas_for(j, dcur);
 #pragma unroll
-                    for (unsigned u = 0; u < kColUnroll; ++u) aout[u] = out_base + dcur[u];
-                    column_step<KIND, HAS_OUT, BF16>(ain, aout, aloc);
+                    for (unsigned u = 0; u < U; ++u) aout[u] = out_base + dcur[u];
+                    column_step<U, KIND, HAS_OUT, BF16>(ain, aout, aloc);
                     next_chunk();
                     __syncthreads();  // the next step reads what other waves of this workgroup just staged
                     R2_STAMP(2 + j);
@@ -796,17 +800,17 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             const uint32_t last = a.J - 1;  // the one step that stages nothing
             if (j == 0) {  // copy-send: nothing comes in, the chunk goes out under table 0
                 deltas_for(0, dcur);
-                uint64_t aout[kColUnroll], aloc[kColUnroll];
+                uint64_t aout[U], aloc[U];
 #pragma unroll
-                for (unsigned u = 0; u < kColUnroll; ++u) {
+                for (unsigned u = 0; u < U; ++u) {
                     aout[u] = my_out0 + dcur[u];
                     aloc[u] = loc + bu[u];
                 }
                 if (preload) {  // the chunk is already in registers
 #pragma unroll
-                    for (unsigned u = 0; u < kColUnroll; ++u) store16<false>(aout[u], pre[u]);
+                    for (unsigned u = 0; u < U; ++u) store16<false>(aout[u], pre[u]);
                 } else {
-                    column_step<0, true, BF16>(aout, aout, aloc);
+                    column_step<U, 0, true, BF16>(aout, aout, aloc);
                 }
                 next_chunk();
                 __syncthreads();
@@ -825,14 +829,14 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             for (uint32_t j = a.j0; j < a.j1; ++j) {
                 const bool has_in = j > 0, has_out = j + 1 < a.J;
                 const bool summing = has_in && j <= a.sum_last;
-                uint64_t din[kColUnroll], dout[kColUnroll];
+                uint64_t din[U], dout[U];
                 if (has_in && !have) deltas_for(j - 1, dcur);  // first step of the launch
 #pragma unroll
-                for (unsigned u = 0; u < kColUnroll; ++u) din[u] = dcur[u];
+                for (unsigned u = 0; u < U; ++u) din[u] = dcur[u];
                 if (has_out && (!(has_in || have) || changed[j])) deltas_for(j, dcur);
                 have = true;
 #pragma unroll
-                for (unsigned u = 0; u < kColUnroll; ++u) dout[u] = dcur[u];
+                for (unsigned u = 0; u < U; ++u) dout[u] = dcur[u];
                 for (uint32_t rv = wave; rv < a.R; rv += n_waves) {
                     const uint32_t r = __builtin_amdgcn_readfirstlane(rv);
                     const uint32_t peer = (r + a.R - 1) % a.R;
@@ -876,9 +880,9 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             const uint64_t in_base = slab_stage + ((uint64_t)((j + 1) & 1) * a.R + peer) * per_rank;
             const uint64_t out_base = slab_stage + ((uint64_t)(j & 1) * a.R + r) * per_rank;
 
-            u32x4 inc[kColUnroll], loc[kColUnroll];
+            u32x4 inc[U], loc[U];
 #pragma unroll
-            for (unsigned u = 0; u < kColUnroll; ++u) {
+            for (unsigned u = 0; u < U; ++u) {
                 const uint64_t b = b0 + (uint64_t)(u * kWave + lane) * 16;
                 if (b < b1) {
                     if (has_in) {
@@ -895,7 +899,7 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                 }
             }
 #pragma unroll
-            for (unsigned u = 0; u < kColUnroll; ++u) {
+            for (unsigned u = 0; u < U; ++u) {
                 const uint64_t b = b0 + (uint64_t)(u * kWave + lane) * 16;
                 if (b < b1) {
                     u32x4 v;
@@ -920,18 +924,18 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
     }
     record_rows();
 }
-template <bool BF16>
+template <bool BF16, unsigned U>
 __global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_kernel(const FusedArgs a)
 {
-    fused_body<BF16, false>(a, nullptr);
+    fused_body<BF16, false, U>(a, nullptr);
 }
 
 static_assert(sizeof(FusedArgs) + sizeof(EpochBatch) <= 4000, "kernel arguments must fit 4 KiB");
 
-template <bool BF16>
+template <bool BF16, unsigned U>
 __global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_partition_kernel(const FusedArgs a, const EpochBatch eb)
 {
-    fused_body<BF16, true>(a, &eb);
+    fused_body<BF16, true, U>(a, &eb);
 }
 
 #ifdef R2_FUSED_TIMING
@@ -1074,8 +1078,15 @@ bool fused_eligible(const SimShape &s)
 {
     if (s.p2p) return false;
     if (s.chunk_bytes == 0 || s.chunk_bytes % 16 != 0) return false;
-    const uint64_t cols = (s.chunk_bytes + kColBytes - 1) / kColBytes;
+    const uint64_t cols = (s.chunk_bytes + kNarrowColBytes - 1) / kNarrowColBytes;
     return cols * s.S <= 0x7fffffffull;
+}
+
+// Vectors per lane of a run's columns (see kWideColumnsFrom).
+unsigned fused_col_unroll(const SimShape &s)
+{
+    const uint64_t wide = (s.chunk_bytes + 2 * kNarrowColBytes - 1) / (2 * kNarrowColBytes);
+    return wide * s.S >= kWideColumnsFrom ? 2 : 1;
 }
 
 // Decides between one launch per step and fused columns, and marks the steps before which a fused
@@ -1330,7 +1341,9 @@ int launch_fused(const r2_sim_desc *desc, const SimShape &s, void *const *rank_b
     a.stage = reinterpret_cast<uint64_t>(workspace) + s.stage_off;
     a.chunk_bytes = s.chunk_bytes;
     a.cap = s.cap;
-    a.cols_per_chunk = (s.chunk_bytes + kColBytes - 1) / kColBytes;
+    const unsigned unroll = fused_col_unroll(s);
+    const uint64_t col_bytes = (uint64_t)kNarrowColBytes * unroll;
+    a.cols_per_chunk = (s.chunk_bytes + col_bytes - 1) / col_bytes;
     a.R = s.R;
     a.S = s.S;
     a.C = s.C;
@@ -1345,16 +1358,23 @@ int launch_fused(const r2_sim_desc *desc, const SimShape &s, void *const *rank_b
     if (eb && !lds) return R2_ERR_INVALID;
     const unsigned waves = s.R < kMaxFusedWaves ? s.R : kMaxFusedWaves;
     const dim3 grid((unsigned)(a.cols_per_chunk * s.S)), block(waves * kWave);
+    const bool bf16 = desc->dtype == R2_BF16;
     if (eb) {
-        if (desc->dtype == R2_BF16)
-            hipLaunchKernelGGL((ring_fused_partition_kernel<true>), grid, block, lds, stream, a, *eb);
-        else
-            hipLaunchKernelGGL((ring_fused_partition_kernel<false>), grid, block, lds, stream, a, *eb);
+        if (unroll == 2) {
+            if (bf16) hipLaunchKernelGGL((ring_fused_partition_kernel<true, 2>), grid, block, lds, stream, a, *eb);
+            else hipLaunchKernelGGL((ring_fused_partition_kernel<false, 2>), grid, block, lds, stream, a, *eb);
+        } else {
+            if (bf16) hipLaunchKernelGGL((ring_fused_partition_kernel<true, 1>), grid, block, lds, stream, a, *eb);
+            else hipLaunchKernelGGL((ring_fused_partition_kernel<false, 1>), grid, block, lds, stream, a, *eb);
+        }
     } else {
-        if (desc->dtype == R2_BF16)
-            hipLaunchKernelGGL((ring_fused_kernel<true>), grid, block, lds, stream, a);
-        else
-            hipLaunchKernelGGL((ring_fused_kernel<false>), grid, block, lds, stream, a);
+        if (unroll == 2) {
+            if (bf16) hipLaunchKernelGGL((ring_fused_kernel<true, 2>), grid, block, lds, stream, a);
+            else hipLaunchKernelGGL((ring_fused_kernel<false, 2>), grid, block, lds, stream, a);
+        } else {
+            if (bf16) hipLaunchKernelGGL((ring_fused_kernel<true, 1>), grid, block, lds, stream, a);
+            else hipLaunchKernelGGL((ring_fused_kernel<false, 1>), grid, block, lds, stream, a);
+        }
     }
     return hip_rc(hipGetLastError());
 }
