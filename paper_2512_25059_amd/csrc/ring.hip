@@ -392,7 +392,10 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
 // hand-off: while the narrow columns of a run do not fill the GPU they are the faster ones (half the
 // work per step and unit, twice the units busy); wide columns halve the per-column overhead once they do.
 constexpr unsigned kNarrowColBytes = kWave * 16;
-constexpr uint64_t kWideColumnsFrom = 256;  // wide columns from this many of them on (one per compute unit)
+#ifndef R2_WIDE_FROM
+#define R2_WIDE_FROM 256
+#endif
+constexpr uint64_t kWideColumnsFrom = R2_WIDE_FROM;  // wide columns from this many of them on (one per compute unit)
 constexpr unsigned kMaxFusedWaves = 16;
 
 struct ColInfo {  // the slice of one transmission's table that holds the column's first byte
