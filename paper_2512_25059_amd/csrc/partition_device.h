@@ -41,17 +41,28 @@ __device__ inline uint64_t partition_lane(uint32_t weight, bool failed, uint32_t
                                           uint32_t align, uint64_t *total_weight)
 {
     const unsigned lane = threadIdx.x & (kWave - 1);
-    const uint64_t e = (lane < C && !failed) ? weight : 0;
-    uint64_t incl = e;
-#pragma unroll
-    for (unsigned d = 1; d < kWave; d <<= 1) {
-        if (d < C) {  // lanes from C on carry nothing: log2(C) rounds reach every channel
-            const uint64_t up = __shfl_up(incl, d, kWave);
-            if (lane >= d) incl += up;
+    const uint32_t e = (lane < C && !failed) ? weight : 0;
+    uint64_t P = 0, W = 0;  // bandwidth of the channels before this one; total
+    if (C <= 16) {
+        // Few channels: a walk over them with the running sum in scalar registers beats the
+        // log-step scan, whose every round is a round trip through the cross-lane network.
+        for (uint32_t c = 0; c < C; ++c) {
+            const uint32_t wc = __builtin_amdgcn_readlane(e, c);
+            if (lane == c) P = W;
+            W += wc;
         }
+    } else {
+        uint64_t incl = e;
+#pragma unroll
+        for (unsigned d = 1; d < kWave; d <<= 1) {
+            if (d < C) {  // lanes from C on carry nothing: log2(C) rounds reach every channel
+                const uint64_t up = __shfl_up(incl, d, kWave);
+                if (lane >= d) incl += up;
+            }
+        }
+        W = __shfl(incl, C - 1, kWave);
+        P = incl - e;
     }
-    const uint64_t W = __shfl(incl, C - 1, kWave);
-    const uint64_t P = incl - e;  // bandwidth of the channels before this one
 
     *total_weight = W;
     if (W == 0) return 0;

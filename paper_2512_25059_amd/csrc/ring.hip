@@ -532,21 +532,28 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             if (lane == 0) lds_row[C] = a.chunk_bytes;
         }
         __syncthreads();
-        for (uint32_t tv = t_first + wave; tv < t_end; tv += n_waves) {  // lane c handles entry c of the row
-            const uint32_t t = __builtin_amdgcn_readfirstlane(tv);
-            const uint32_t ts = first_tx(epoch_at(*eb, tg0 + t));
-            const R2_LDS uint64_t *src = lds_rows + (uint64_t)(ts - t_first) * row;
-            const uint64_t lo = lane < C ? src[lane] : 0, hi = lane < C ? src[lane + 1] : 0;
-            if (t != ts) {  // C may be the whole wavefront: lane 0 also writes the row's last entry
-                if (lane < C) s_rows[(uint64_t)(t - t_first) * row + lane] = lo;
-                if (lane == 0) s_rows[(uint64_t)(t - t_first) * row + C] = a.chunk_bytes;
+        // A group of 16, 32 or 64 lanes (enough for a row) per transmission, lane c of the group for
+        // entry c of the row: with few channels one round serves every transmission of the launch.
+        const uint32_t width = row <= 16 ? 16 : row <= 32 ? 32 : kWave;
+        const uint32_t per = kWave / width, c = lane % width;
+        for (uint32_t t = t_first + wave * per + lane / width; t < t_end; t += n_waves * per) {
+            uint32_t ts = t_first;  // the first transmission (here) of the state in force at t
+            for (uint32_t k = e_lo + 1; k <= e_hi; ++k) {
+                const uint64_t begins = eb->t_start[k];
+                if (begins <= tg0 + t) ts = (uint32_t)(begins - tg0);
             }
-            if (lane < C && lo <= b0 && b0 < hi) {  // the one slice that holds the column's first byte
+            const R2_LDS uint64_t *src = lds_rows + (uint64_t)(ts - t_first) * row;
+            const uint64_t lo = c < C ? src[c] : 0, hi = c < C ? src[c + 1] : 0;
+            if (t != ts) {  // C may be the whole wavefront: lane 0 also writes the row's last entry
+                if (c < C) s_rows[(uint64_t)(t - t_first) * row + c] = lo;
+                if (c == 0) s_rows[(uint64_t)(t - t_first) * row + C] = a.chunk_bytes;
+            }
+            if (c < C && lo <= b0 && b0 < hi) {  // the one slice that holds the column's first byte
                 info[t].lo = lo;
                 info[t].hi = hi;
-                info[t].c = lane;
+                info[t].c = c;
             }
-            if (lane == 0) changed[t] = t == ts;  // the first transmission of a state, or of this launch
+            if (c == 0) changed[t] = t == ts;  // the first transmission of a state, or of this launch
         }
         __syncthreads();
         R2_STAMP(1);
