@@ -499,13 +499,28 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
     const bool one_rank = a.R <= n_waves;                       // a wave plays one rank
     const bool ragged_width = b0 + (kWave * 16 * U) > a.chunk_bytes;  // the chunk's last, narrower column
 
+    // What a wave that plays one rank needs per step depends on the launch arguments only, so it is
+    // worked out here, ahead of the prologue's barriers: the slab of its buffer, its own stage and its
+    // predecessor's (parity 0; parity 1 is R ranks further), and the ring chunk it starts at, which
+    // goes one down per step.  (With more ranks than waves these describe the wave's first rank and
+    // are not used.)
+    const uint64_t per_rank = (uint64_t)a.S * C * a.cap;  // stage bytes of one (parity, rank)
+    const uint64_t slab_stage = a.stage + (uint64_t)l * C * a.cap;
+    const uint32_t my_rank = wave < a.R ? wave : 0;
+    const uint32_t my_peer = (my_rank + a.R - 1) % a.R;
+    const uint64_t my_slab = a.rank_buf[my_rank] + (uint64_t)l * a.R * a.chunk_bytes;
+    const uint64_t my_in0 = slab_stage + (uint64_t)my_peer * per_rank;
+    const uint64_t my_out0 = slab_stage + (uint64_t)my_rank * per_rank;
+    const uint64_t parity_stride = (uint64_t)a.R * per_rank;
+    const uint32_t my_chunk = (my_rank + a.chunk_start + 2 * a.R - a.j0) % a.R;
+
     // A launch that starts at step 0 begins with every rank staging a chunk of its own buffer.
     // Where that chunk lies depends on nothing computed below, so its loads are issued first and
     // their latency passes while the tables are made.
     const bool preload = a.j0 == 0 && one_rank && !ragged_width;
     u32x4 pre[U] = {};
     if (preload) {
-        const uint64_t src = a.rank_buf[wave] + ((uint64_t)l * a.R + (wave + a.chunk_start) % a.R) * a.chunk_bytes + b0;
+        const uint64_t src = my_slab + (uint64_t)my_chunk * a.chunk_bytes + b0;  // j0 = 0: my_chunk is step 0's
 #pragma unroll
         for (unsigned u = 0; u < U; ++u) pre[u] = load16<kNtLocalLoad>(src + (uint64_t)(u * kWave + lane) * 16);
     }
@@ -606,8 +621,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             if (a.log_out) a.log_out[at + i] = v;
         }
     };
-    const uint64_t per_rank = (uint64_t)a.S * C * a.cap;  // stage bytes of one (parity, rank)
-    const uint64_t slab_stage = a.stage + (uint64_t)l * C * a.cap;
     auto local_of = [&](uint32_t r, uint32_t j) {
         const uint32_t chunk = (r + a.chunk_start + 2 * a.R - j) % a.R;
         return a.rank_buf[r] + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
@@ -661,15 +674,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             }
         };
 
-        // When a wave plays one rank, what it needs per step is hoisted out of the step loop: the
-        // slab of its buffer, its own stage and its predecessor's (parity 0; parity 1 is R ranks
-        // further), and the ring chunk it is at, which goes one down per step.
-        const uint32_t my_peer = (wave + a.R - 1) % a.R;
-        const uint64_t my_slab = a.rank_buf[wave] + (uint64_t)l * a.R * a.chunk_bytes;
-        const uint64_t my_in0 = slab_stage + (uint64_t)my_peer * per_rank;
-        const uint64_t my_out0 = slab_stage + (uint64_t)wave * per_rank;
-        const uint64_t parity_stride = (uint64_t)a.R * per_rank;
-        const uint32_t my_chunk = (wave + a.chunk_start + 2 * a.R - a.j0) % a.R;
 
         // The table a step reads with is the one the step before wrote with, and tables mostly
         // repeat from step to step, so the offsets are carried along and looked up only on change.
