@@ -6,7 +6,8 @@
 //
 // The data path is bandwidth-bound: per 16-byte vector two loads, one add, two stores.  Every lane
 // moves whole 16-byte vectors; a wavefront touches 1 KiB of consecutive addresses per access.  The
-// channel of a vector is found by a short binary search in an LDS copy of the offsets table.
+// slice that holds a tile is found by a wavefront-wide comparison against the offsets table, which
+// every wavefront holds in its lanes; only tiles that straddle a cut search an LDS copy per lane.
 #include <type_traits>
 
 #include "partition_device.h"
@@ -133,49 +134,52 @@ __device__ inline uint32_t find_channel(const uint64_t *off, uint32_t C, uint64_
     return lo;
 }
 
-__device__ inline uint64_t uniform64(uint64_t x)  // tell the compiler the value is wave-uniform
-{
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-
 // The slice that holds chunk byte b0, remembered from tile to tile: a workgroup walks the chunk
 // front to back and slices are long, so the table is searched only when a cut is crossed.
 struct Span {
     uint64_t lo = 0, hi = 0, delta = 0;
 };
-__device__ inline void locate(const ChannelTable &t, uint32_t C, uint64_t b0, Span &s)
+
+// One table as every wavefront holds it: lane c has slice c's bounds (lanes from C on hold nothing),
+// and whether the table is acceptable.  Read straight from memory by each wavefront for itself -- a
+// few cached loads -- so that the common path needs neither LDS nor a workgroup barrier.
+struct LaneRow {
+    uint64_t off = 0, next = 0;
+    int bad = 0;  // 0 or an R2_ERR code
+};
+__device__ inline LaneRow load_row(const uint64_t *__restrict__ g_off, uint32_t C, uint64_t bytes, uint64_t cap)
+{
+    const unsigned c = threadIdx.x % kWave;
+    LaneRow r;
+    if (c < C) {
+        r.off = g_off[c];
+        r.next = g_off[c + 1];
+        if (c == 0 && r.off != 0) r.bad = R2_ERR_INVALID;
+        if (c == C - 1 && r.next != bytes) r.bad = R2_ERR_INVALID;
+        if (r.next < r.off) r.bad = R2_ERR_INVALID;
+        else if (r.next - r.off > cap) r.bad = R2_ERR_CAPACITY;
+        if (r.next != r.off && (r.off & 15u)) r.bad = R2_ERR_INVALID;  // a non-empty slice starts on 16 B
+    }
+    return r;
+}
+__device__ inline uint64_t lane_value(uint64_t x, uint32_t lane)  // x of a wave-uniform lane
+{
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)x, lane);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(x >> 32), lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+// The slice that holds byte b0 (wave-uniform, below the chunk's size): one lane's bounds contain it.
+template <typename Ptr>
+__device__ inline void locate(const LaneRow &r, uint32_t C, uint64_t b0, Span &s, Ptr base_of)
 {
     if (b0 < s.lo || b0 >= s.hi) {
-        const uint32_t c = find_channel(t.off, C, b0);
-        s.lo = uniform64(t.off[c]);
-        s.hi = uniform64(t.off[c + 1]);
-        s.delta = uniform64(t.delta[c]);
+        const unsigned lane = threadIdx.x % kWave;
+        const uint64_t holds = __ballot(lane < C && r.off <= b0 && b0 < r.next);
+        const uint32_t c = __builtin_amdgcn_readfirstlane((uint32_t)__builtin_ctzll(holds));
+        s.lo = lane_value(r.off, c);
+        s.hi = lane_value(r.next, c);
+        s.delta = base_of(c) - s.lo;
     }
-}
-
-// Lanes 0..C of the workgroup copy one table to LDS and check it.  Returns 0 or an R2_ERR code
-// (per lane; the caller combines them).
-__device__ inline int load_table(ChannelTable &t, const uint64_t *__restrict__ g_off,
-                                 uint64_t base_c, uint32_t C, uint64_t bytes, uint64_t cap)
-{
-    const unsigned c = threadIdx.x;
-    int bad = 0;
-    if (c <= C) {
-        const uint64_t o = g_off[c];
-        t.off[c] = o;
-        if (c == 0 && o != 0) bad = R2_ERR_INVALID;
-        if (c == C && o != bytes) bad = R2_ERR_INVALID;
-        if (c < C) {
-            const uint64_t next = g_off[c + 1];
-            if (next < o) bad = R2_ERR_INVALID;
-            else if (next - o > cap) bad = R2_ERR_CAPACITY;
-            if (next != o && (o & 15u)) bad = R2_ERR_INVALID;  // a non-empty slice starts on 16 B
-            t.delta[c] = base_c - o;
-        }
-    }
-    return bad;
 }
 
 // ---------------------------------------------------------------- the chunk worker
@@ -202,21 +206,44 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
     constexpr bool NEED_LOCAL = M != kCopy;
     const uint32_t C = job.C;
 
-    // Tables to LDS, with a sanity check whose verdict is the same in every workgroup.
+    // Every wavefront reads the tables for itself and checks them; the verdict is the same in every
+    // wavefront of every workgroup, so a bad table moves nothing anywhere.
+    LaneRow rin, rout;
     int bad = 0;
     if constexpr (HAS_IN) {
-        const unsigned c = threadIdx.x;
-        bad = load_table(tin, job.in_off, c < C ? in_ptr(c) : 0, C, job.bytes, job.cap);
+        rin = load_row(job.in_off, C, job.bytes, job.cap);
+        bad = rin.bad;
     }
     if constexpr (HAS_OUT) {
-        const unsigned c = threadIdx.x;
-        const int b2 = load_table(tout, job.out_off, c < C ? out_ptr(c) : 0, C, job.bytes, job.cap);
-        if (!bad) bad = b2;
+        rout = load_row(job.out_off, C, job.bytes, job.cap);
+        if (!bad) bad = rout.bad;
     }
-    if (__syncthreads_or(bad)) {
+    if (__any(bad)) {
         if (bad && status) atomicMin(status, bad);
         return;
     }
+    // The rare paths (a tile that straddles a cut, a ragged tail, an unaligned chunk) look channels up
+    // per lane in an LDS copy of the tables, made when first needed; whether it is needed is the same
+    // for all threads of the workgroup, so the barrier inside is reached by all or none.
+    bool tables_in_lds = false;
+    auto tables_to_lds = [&]() {
+        if (tables_in_lds) return;
+        const unsigned c = threadIdx.x;
+        if (c < C) {
+            if constexpr (HAS_IN) {
+                tin.off[c] = rin.off;
+                tin.delta[c] = in_ptr(c) - rin.off;
+                if (c == C - 1) tin.off[C] = rin.next;
+            }
+            if constexpr (HAS_OUT) {
+                tout.off[c] = rout.off;
+                tout.delta[c] = out_ptr(c) - rout.off;
+                if (c == C - 1) tout.off[C] = rout.next;
+            }
+        }
+        __syncthreads();
+        tables_in_lds = true;
+    };
 
     uint8_t *const local = job.local;
     const bool aligned = (reinterpret_cast<uintptr_t>(local) & 15u) == 0;
@@ -234,11 +261,11 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
         const uint64_t b1 = (v0 + tile < nvec ? v0 + tile : nvec) * 16;
         bool in_one = true, out_one = true;
         if constexpr (HAS_IN) {
-            locate(tin, C, b0, sin);
+            locate(rin, C, b0, sin, in_ptr);
             in_one = b1 <= sin.hi;
         }
         if constexpr (HAS_OUT) {
-            locate(tout, C, b0, sout);
+            locate(rout, C, b0, sout, out_ptr);
             out_one = b1 <= sout.hi;
         }
         u32x4 inc[kUnroll], loc[kUnroll];
@@ -261,6 +288,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
         }
         // The chunk's last, partial tile, or a tile that straddles a cut: every lane checks its
         // bounds and, where needed, looks its channel up.
+        if (!in_one || !out_one) tables_to_lds();
 #pragma unroll
         for (unsigned u = 0; u < kUnroll; ++u) {
             const uint64_t v = v0 + u * kThreads + threadIdx.x;
@@ -293,6 +321,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
     using Elem = typename std::conditional<M == kSumF32, uint32_t, uint16_t>::type;
     const uint64_t first = nvec * 16;
     const uint64_t n_el = (job.hi - first) / sizeof(Elem);
+    if (n_el) tables_to_lds();
     for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < n_el;
          i += (uint64_t)gridDim.x * kThreads) {
         const uint64_t b = first + i * sizeof(Elem);
