@@ -29,9 +29,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure (8 TB/s)
 # commands are in profiles/ring_step_sum_bf16_cfg2_pmc.md (cfg3: ..._f32_cfg3_pmc.md).  Not measured for
 # other workloads.
 MEASURED_TRAFFIC = {
-    ("cfg2", "sum"): int((131117.5 * (131072.0 / 65550.8) + 262164.2 * (131072.0 / 131072.0)) * 1024),
+    ("cfg2", "sum"): int((131108.5 * (131072.0 / 65550.8) + 262168.1 * (131072.0 / 131072.0)) * 1024),
     # cfg3: the calibration copy is one 256 MiB rank buffer (profiles/ring_step_sum_f32_cfg3_pmc.md)
-    ("cfg3", "sum"): int((131115.3 * (262144.0 / 131089.1) + 262156.6 * (262144.0 / 262144.0)) * 1024),
+    ("cfg3", "sum"): int((131114.0 * (262144.0 / 131087.2) + 262158.7 * (262144.0 / 262144.0)) * 1024),
 }
 
 
