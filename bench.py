@@ -281,9 +281,13 @@ def _time_calls(torch, fn, n=20, warm=3):
 
 
 def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
-    """R2CCL-Balance on the collectives the paper measures besides all-reduce (Sec. 8, Appendix E):
-    reduce-scatter, all-gather and send/receive on the cfg2 shape (8 ranks, bf16, 128 MiB per rank),
-    one of eight channels down from the start."""
+    """R2CCL-Balance on the other collectives it serves (Sec. 5, table of strategies; Sec. 8 and
+    Appendix E measure some of them): reduce-scatter, all-gather, send/receive, broadcast, reduce and
+    all-to-all on the cfg2 shape (8 ranks, bf16, 128 MiB per rank), one of eight channels down from
+    the start.  Algorithmic bytes, in units of one rank buffer: a hop that only stages or only takes
+    data moves 2, one that takes and stages onward 3 (so does a reduce hop: two reads, one write), a
+    reduce-scatter step 4; all-to-all moves (R-1)/R of every buffer through the stage (4) and copies
+    the own block (2)."""
     w = wl.cfg2()
     R, N, C, e = w.R, w.N, w.C, 2
     epochs = [(0, 0b00000100, [50000] * C)]
@@ -292,11 +296,16 @@ def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
     recv = [torch.empty_like(b) for b in bufs]
     for name, phases, S, units in (("reduce-scatter", r2.PHASE_RS, 1, (4 * R - 3) * N),
                                    ("all-gather", r2.PHASE_AG, 1, (3 * R - 2) * N),
-                                   ("send/receive", r2.PHASE_SENDRECV, 8, 4 * R * N)):
+                                   ("send/receive", r2.PHASE_SENDRECV, 8, 4 * R * N),
+                                   ("broadcast", r2.PHASE_BROADCAST, 8, (3 * R - 2) * N),
+                                   ("reduce", r2.PHASE_REDUCE, 8, (3 * R - 1) * N),
+                                   ("all-to-all", r2.PHASE_ALLTOALL, 1, (4 * R - 2) * N)):
         desc = r2.SimDesc(R, S, C, w.align, N, r2.BF16, phases, 0, r2.SCHED_STEPS)
         ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
         if phases == r2.PHASE_SENDRECV:
             s = _time_calls(torch, lambda: r2.r2_sendrecv_sim(desc, bufs, recv, epochs, ws))
+        elif phases == r2.PHASE_ALLTOALL:
+            s = _time_calls(torch, lambda: r2.r2_alltoall_sim(desc, bufs, recv, epochs, ws))
         else:
             s = _time_calls(torch, lambda: r2.r2_ring_allreduce_sim(desc, bufs, epochs, ws))
         alg = units * e

@@ -49,9 +49,13 @@ enum {
 #define R2_MAX_RANKS 64
 
 typedef enum { R2_F32 = 0, R2_BF16 = 1 } r2_dtype;
-enum { R2_OP_SUM = 0, R2_OP_COPY = 1, R2_OP_SUM_FORWARD = 2 };
+enum { R2_OP_SUM = 0, R2_OP_COPY = 1, R2_OP_SUM_FORWARD = 2, R2_OP_SUM_SEND = 3 };
 enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2, /* both = all-reduce */
-       R2_PHASE_SENDRECV = 4 /* point-to-point to the ring successor; on its own only */ };
+       /* the other collectives R2CCL-Balance serves; each on its own only */
+       R2_PHASE_SENDRECV = 4,   /* point-to-point to the ring successor */
+       R2_PHASE_BROADCAST = 8,  /* ring broadcast from desc->root       */
+       R2_PHASE_REDUCE = 16,    /* ring reduce to desc->root            */
+       R2_PHASE_ALLTOALL = 32   /* pairwise exchange of R blocks        */ };
 enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2 };
 
 /* Static, human-readable text for a return code. */
@@ -128,6 +132,9 @@ int r2_rollback_plan_device(const uint64_t *offsets, const uint32_t *weights,
  *     op == R2_OP_SUM_FORWARD       : as R2_OP_SUM for local, but the outgoing stage gets `incoming`
  *                                     itself, not the sum (the relay step of the broadcast of
  *                                     Sec. 5.2); needs both stages
+ *     op == R2_OP_SUM_SEND          : v = incoming + local goes to the outgoing stage only and local
+ *                                     stays as it was (a hop of a Reduce towards its root: a rank
+ *                                     that passes the sum on does not keep it); needs both stages
  * in_stage and out_stage may not both be NULL.
  *   local       device, `bytes` bytes (a whole number of elements), 16-byte aligned for full speed;
  *               an address that is only element-aligned is handled one element at a time
@@ -171,6 +178,26 @@ int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int op,
  * re-partitions chunks k, k+1, ...  `rank_bufs` then holds 2R pointers: R send buffers, then R
  * receive buffers (r2_sendrecv_sim takes them apart).  Only the step schedule runs it.
  *
+ * The remaining collectives of the table of strategies in Sec. 5 keep their ring schedule as well
+ * (Sec. 5.1, "Overhead Analysis": the volume a server must send does not change, only its cut over
+ * the healthy NICs).  A slab is one message chunk of n_elems/n_slabs elements; the hop sent at step j
+ * of chunk l is transmission t = l*(R-1) + j; one rank is active per step:
+ *   R2_PHASE_BROADCAST  J = R steps; at step j rank root+j works: j = 0 stages its chunk, the ranks
+ *                       after it take the incoming chunk and stage it onward, the last one only takes
+ *                       it.  Afterwards every buffer equals the root's.
+ *   R2_PHASE_REDUCE     J = R steps; at step j rank root+1+j works: j = 0 stages its chunk, the ranks
+ *                       after it stage incoming + their own chunk onward and keep their own buffer as
+ *                       it was (R2_OP_SUM_SEND), at j = R-1 the root adds the incoming sum into its
+ *                       buffer: root <- x[root+1] + x[root+2] + ... + x[root], folded in that order,
+ *                       rounded to the buffer type after every addition.
+ *   R2_PHASE_ALLTOALL   (r2_alltoall_sim) a buffer is R blocks of n_slabs chunks; in round k = 1..R-1
+ *                       rank r sends its block r+k to rank r+k and receives rank r-k's block r into
+ *                       block r-k of its receive buffer, two steps per chunk as for SENDRECV; chunk l
+ *                       of round k is transmission (k-1)*n_slabs + l, for every rank alike.  A rank's
+ *                       own block is copied without touching a channel.  The run has (R-1)*n_slabs
+ *                       internal slabs: that many rows of tables and that many stage buffers per rank.
+ * Only the step schedule runs these.
+ *
  * Slabs are independent of each other, and so are the bytes of a chunk.  The run is therefore cut
  * into passes -- groups of whole slabs, or, when one slab is too large, byte ranges of its chunks --
  * such that the stage bytes one step writes (over all ranks) stay within stage_window_bytes and can
@@ -187,13 +214,13 @@ typedef struct {
 
 typedef struct {
     uint32_t n_ranks;    /* R, 2..R2_MAX_RANKS                                                   */
-    uint32_t n_slabs;    /* S >= 1, R*S <= 65535                                                 */
+    uint32_t n_slabs;    /* S >= 1, R*S <= 65535 (R2_PHASE_ALLTOALL: R*(R-1)*S <= 65535)         */
     uint32_t n_channels; /* C, 1..R2_MAX_CHANNELS                                                */
     uint32_t align;      /* partition alignment in bytes, a multiple of 16                       */
-    uint64_t n_elems;    /* elements per rank, a multiple of R*S (of S for R2_PHASE_SENDRECV);
-                            0 is allowed: nothing to do                                          */
+    uint64_t n_elems;    /* elements per rank, a multiple of R*S (of S for R2_PHASE_SENDRECV,
+                            _BROADCAST and _REDUCE); 0 is allowed: nothing to do                 */
     int32_t dtype;       /* r2_dtype                                                             */
-    int32_t phases;      /* R2_PHASE_RS, R2_PHASE_AG, both, or R2_PHASE_SENDRECV                 */
+    int32_t phases;      /* R2_PHASE_RS, R2_PHASE_AG, both, or one of the other R2_PHASE_*       */
     uint64_t stage_window_bytes; /* stage bytes one launch may write, summed over ranks; 0 = the
                                     library's default (128 MiB, half the Infinity Cache).  Only
                                     changes how the run is cut into passes, never the result.   */
@@ -202,7 +229,8 @@ typedef struct {
                             through all steps between two channel-state changes; needs chunks that
                             are a multiple of 16 bytes.
                             R2_SCHED_AUTO (0): FUSED for launch-bound sizes, else STEPS.           */
-    int32_t reserved;    /* 0 */
+    int32_t root;        /* R2_PHASE_BROADCAST: the rank whose buffer everybody gets;
+                            R2_PHASE_REDUCE: the rank that gets the sum; otherwise 0              */
 } r2_sim_desc;
 
 /* Pure host arithmetic on a descriptor (0 if the descriptor is invalid). */
@@ -251,8 +279,9 @@ int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t
  * Host arithmetic only. */
 int r2_sim_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs);
 
-/* r2_sim_prepare, then the whole ring in place on the rank buffers, by desc->schedule: for every
- * pass the steps 0..J-1, or fused launches cut wherever a channel state changes mid-slab. */
+/* r2_sim_prepare, then the whole collective that desc->phases names, in place on the rank buffers, by
+ * desc->schedule: for every pass the steps 0..J-1, or fused launches cut wherever a channel state
+ * changes mid-slab. */
 int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           const r2_epoch *epochs, uint32_t n_epochs,
                           void *workspace, uint64_t workspace_bytes,
@@ -265,6 +294,15 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
  * epochs.  Same workspace, epochs, log and passes as r2_ring_allreduce_sim, which this calls with the
  * two pointer lists joined.  Send buffers are only read. */
 int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
+                    const r2_epoch *epochs, uint32_t n_epochs, void *workspace, uint64_t workspace_bytes,
+                    uint64_t *offsets_log, void *stream);
+
+/* All-to-All under R2CCL-Balance (Sec. 5, table of strategies: point-to-point incl. All-to-All;
+ * Sec. 5.1): desc->phases must be R2_PHASE_ALLTOALL.  Afterwards block q of recv_bufs[r] equals
+ * block r of send_bufs[q] byte for byte, whatever the epochs (a block is n_elems/R elements).  Same
+ * workspace, epochs, log and passes as r2_ring_allreduce_sim, which this calls with the two pointer
+ * lists joined.  Send buffers are only read; no receive buffer may be a send buffer. */
+int r2_alltoall_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
                     const r2_epoch *epochs, uint32_t n_epochs, void *workspace, uint64_t workspace_bytes,
                     uint64_t *offsets_log, void *stream);
 

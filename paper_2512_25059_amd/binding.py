@@ -17,10 +17,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libr2ccl.so")
 
 F32, BF16 = 0, 1
-OP_SUM, OP_COPY, OP_SUM_FORWARD = 0, 1, 2
+OP_SUM, OP_COPY, OP_SUM_FORWARD, OP_SUM_SEND = 0, 1, 2, 3
 PHASE_RS, PHASE_AG = 1, 2
 PHASE_AR = PHASE_RS | PHASE_AG
-PHASE_SENDRECV = 4
+PHASE_SENDRECV, PHASE_BROADCAST, PHASE_REDUCE, PHASE_ALLTOALL = 4, 8, 16, 32
 SCHED_AUTO, SCHED_STEPS, SCHED_FUSED = 0, 1, 2
 
 R2_OK = 0
@@ -63,7 +63,7 @@ class _SimDesc(C.Structure):
     _fields_ = [("n_ranks", C.c_uint32), ("n_slabs", C.c_uint32), ("n_channels", C.c_uint32),
                 ("align", C.c_uint32), ("n_elems", C.c_uint64), ("dtype", C.c_int32),
                 ("phases", C.c_int32), ("stage_window_bytes", C.c_uint64), ("schedule", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("root", C.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -77,10 +77,11 @@ class SimDesc:
     phases: int
     stage_window_bytes: int = 0  # 0 = library default
     schedule: int = 0            # SCHED_AUTO
+    root: int = 0                # PHASE_BROADCAST / PHASE_REDUCE
 
     def c(self) -> _SimDesc:
         return _SimDesc(self.n_ranks, self.n_slabs, self.n_channels, self.align, self.n_elems,
-                        self.dtype, self.phases, self.stage_window_bytes, self.schedule, 0)
+                        self.dtype, self.phases, self.stage_window_bytes, self.schedule, self.root)
 
 
 @dataclass(frozen=True)
@@ -201,6 +202,8 @@ def load_library():
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_sendrecv_sim.restype = i32
     lib.r2_sendrecv_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
+    lib.r2_alltoall_sim.restype = i32
+    lib.r2_alltoall_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
     _lib = lib
     return lib
 
@@ -547,3 +550,16 @@ def r2_sendrecv_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epo
                                         wp, wb, _ptr(offsets_log), _stream(stream))
     del sa, ra, keep
     _check(rc, "r2_sendrecv_sim")
+
+
+def r2_alltoall_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epochs, workspace,
+                    offsets_log: Optional[torch.Tensor] = None, stream=None,
+                    workspace_bytes: Optional[int] = None) -> None:
+    sa, sp = _ptr_array(send_bufs)
+    ra, rp = _ptr_array(recv_bufs)
+    ep, keep = _epoch_array(epochs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_alltoall_sim(C.byref(desc.c()), sp, rp, C.cast(ep, C.c_void_p), len(epochs),
+                                        wp, wb, _ptr(offsets_log), _stream(stream))
+    del sa, ra, keep
+    _check(rc, "r2_alltoall_sim")

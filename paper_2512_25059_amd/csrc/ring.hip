@@ -198,12 +198,16 @@ struct ChunkJob {
 // FWD (sums only): the outgoing stage gets the incoming data unchanged instead of the sum.
 // NT_OUT: the outgoing stage is written with non-temporal stores (a chunk too large for the next
 // reader to find it in cache).
-template <Mode M, bool HAS_OUT, bool FWD = false, bool NT_OUT = kNtStageStore, typename InPtr, typename OutPtr>
+// KEEP (sums only): the result goes to the outgoing stage only, the local chunk stays as it was.
+template <Mode M, bool HAS_OUT, bool FWD = false, bool NT_OUT = kNtStageStore, bool KEEP = false, typename InPtr,
+          typename OutPtr>
 __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_ptr, int32_t *status,
                                  ChannelTable &tin, ChannelTable &tout)
 {
     constexpr bool HAS_IN = M != kSend;
     constexpr bool NEED_LOCAL = M != kCopy;
+    constexpr bool PUT_LOCAL = HAS_IN && !KEEP;
+    static_assert(!KEEP || ((M == kSumF32 || M == kSumBF16) && HAS_OUT && !FWD), "KEEP is a sum that is only sent on");
     const uint32_t C = job.C;
 
     // Every wavefront reads the tables for itself and checks them; the verdict is the same in every
@@ -281,7 +285,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
 #pragma unroll
             for (unsigned u = 0; u < kUnroll; ++u) {
                 const u32x4 r = combine<M>(inc[u], loc[u]);
-                if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b + u * (kThreads * 16), r);
+                if constexpr (PUT_LOCAL) store16<kNtLocalStore>(local_addr + b + u * (kThreads * 16), r);
                 if constexpr (HAS_OUT) store16<NT_OUT>(sout.delta + b + u * (kThreads * 16), FWD ? inc[u] : r);
             }
             continue;
@@ -307,7 +311,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
             if (v < nvec) {
                 const uint64_t b = v * 16;
                 const u32x4 r = combine<M>(inc[u], loc[u]);
-                if constexpr (HAS_IN) store16<kNtLocalStore>(local_addr + b, r);
+                if constexpr (PUT_LOCAL) store16<kNtLocalStore>(local_addr + b, r);
                 if constexpr (HAS_OUT) {
                     const uint64_t d = out_one ? sout.delta : tout.delta[find_channel(tout.off, C, b)];
                     store16<NT_OUT>(d + b, FWD ? inc[u] : r);
@@ -336,7 +340,7 @@ __device__ inline void run_chunk(const ChunkJob &job, InPtr in_ptr, OutPtr out_p
         else if constexpr (M == kSumBF16) r = add_bf16(x_in, x_loc);
         else if constexpr (M == kCopy) r = x_in;
         else r = x_loc;
-        if constexpr (HAS_IN) *gptr<Elem>(local_addr + b) = r;
+        if constexpr (PUT_LOCAL) *gptr<Elem>(local_addr + b) = r;
         if constexpr (HAS_OUT) {
             const uint32_t c = find_channel(tout.off, C, b);
             *gptr<Elem>(tout.delta[c] + b) = FWD ? x_in : r;
@@ -350,12 +354,12 @@ struct PtrList {
     uint64_t p[R2_MAX_CHANNELS];
 };
 
-template <Mode M, bool HAS_OUT, bool FWD = false, bool NT_OUT = false>
+template <Mode M, bool HAS_OUT, bool FWD = false, bool NT_OUT = false, bool KEEP = false>
 __global__ __launch_bounds__(kThreads) void reduce_copy_kernel(ChunkJob job, const PtrList in_stage,
                                                                const PtrList out_stage, int32_t *status)
 {
     __shared__ ChannelTable tin, tout;
-    run_chunk<M, HAS_OUT, FWD, NT_OUT>(
+    run_chunk<M, HAS_OUT, FWD, NT_OUT, KEEP>(
         job, [&](unsigned c) { return in_stage.p[c]; }, [&](unsigned c) { return out_stage.p[c]; },
         status, tin, tout);
 }
@@ -371,25 +375,39 @@ struct StepArgs {
     uint32_t step;         // fused step j
     uint32_t T_slab;       // transmissions per slab
     uint32_t chunk_start;  // 1 when the run is an all-gather alone, else 0
-    uint32_t per_slab;     // ring chunks per slab: R, or 1 for point-to-point (every rank moves chunk 0)
+    uint32_t per_slab;     // ring chunks per slab: R, or 1 where a slab is one message chunk
+    uint32_t rank_base;    // the first rank this launch covers (chains: the one rank active at this step)
+    uint32_t a2a_chunks;   // all-to-all: message chunks per block (a slab is chunk l % this of round l / this + 1), else 0
     uint32_t slab_begin, slab_count;  // the slabs this launch covers
     uint64_t lo, hi;                  // and the byte range of every ring chunk it moves
 };
 
-// blockIdx.y = rank * slab_count + (slab - slab_begin), blockIdx.x = workgroup within the range.
-template <Mode M, bool HAS_OUT>
+// blockIdx.y = (rank - rank_base) * slab_count + (slab - slab_begin), blockIdx.x = workgroup within
+// the range.
+template <Mode M, bool HAS_OUT, bool KEEP = false>
 __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
 {
     __shared__ ChannelTable tin, tout;
-    const uint32_t r = blockIdx.y / a.slab_count, l = a.slab_begin + (blockIdx.y - r * a.slab_count);
+    const uint32_t ri = blockIdx.y / a.slab_count, l = a.slab_begin + (blockIdx.y - ri * a.slab_count);
+    const uint32_t r = (a.rank_base + ri) % a.R;
     const uint32_t j = a.step;
-    const uint32_t chunk = a.per_slab == 1 ? 0 : (r + a.chunk_start + 2 * a.R - j) % a.R;  // j <= 2R-2
-    const uint32_t peer = (r + a.R - 1) % a.R;
     const uint64_t row = (uint64_t)a.C + 1;
     const uint64_t t_out = (uint64_t)l * a.T_slab + j;
+    uint32_t peer = (r + a.R - 1) % a.R;  // whose stage is read
+    uint64_t piece;                       // which chunk-sized piece of the rank buffer is worked on
+    if (a.a2a_chunks) {
+        // round k: send the block for rank r+k (step 0), receive the block of rank r-k (step 1)
+        const uint32_t k = l / a.a2a_chunks + 1, part = l - (k - 1) * a.a2a_chunks;
+        peer = (r + a.R - k) % a.R;
+        piece = (uint64_t)(j == 0 ? (r + k) % a.R : peer) * a.a2a_chunks + part;
+    } else if (a.per_slab == 1) {
+        piece = l;
+    } else {
+        piece = (uint64_t)l * a.per_slab + (r + a.chunk_start + 2 * a.R - j) % a.R;  // j <= 2R-2
+    }
 
     ChunkJob job;
-    job.local = reinterpret_cast<uint8_t *>(a.rank_buf[r]) + ((uint64_t)l * a.per_slab + chunk) * a.chunk_bytes;
+    job.local = reinterpret_cast<uint8_t *>(a.rank_buf[r]) + piece * a.chunk_bytes;
     job.bytes = a.chunk_bytes;
     job.lo = a.lo;
     job.hi = a.hi;
@@ -400,9 +418,26 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
     // stage buffer of (parity, rank, slab, channel)
     const uint64_t in_base = a.stage + ((((uint64_t)((j + 1) & 1) * a.R + peer) * a.S + l) * a.C) * a.cap;
     const uint64_t out_base = a.stage + ((((uint64_t)(j & 1) * a.R + r) * a.S + l) * a.C) * a.cap;
-    run_chunk<M, HAS_OUT>(
+    run_chunk<M, HAS_OUT, false, kNtStageStore, KEEP>(
         job, [&](unsigned c) { return in_base + c * a.cap; },
         [&](unsigned c) { return out_base + c * a.cap; }, nullptr, tin, tout);
+}
+
+// All-to-all: a rank's own block goes from its send buffer to its receive buffer without touching a
+// channel.  blockIdx.y = rank; 16-byte vectors where both addresses allow it, 2-byte units otherwise.
+struct OwnBlockArgs {
+    uint64_t src[R2_MAX_RANKS], dst[R2_MAX_RANKS];
+    uint64_t bytes;  // per block; even
+};
+
+__global__ __launch_bounds__(kThreads) void own_block_copy_kernel(const OwnBlockArgs a)
+{
+    const uint64_t src = a.src[blockIdx.y], dst = a.dst[blockIdx.y];
+    const uint64_t tid = (uint64_t)blockIdx.x * kThreads + threadIdx.x, n_threads = (uint64_t)gridDim.x * kThreads;
+    const uint64_t n_vec = ((src | dst) & 15u) ? 0 : a.bytes / 16;
+    for (uint64_t v = tid; v < n_vec; v += n_threads) store16<true>(dst + v * 16, load16<true>(src + v * 16));
+    for (uint64_t i = n_vec * 8 + tid; i < a.bytes / 2; i += n_threads)
+        *gptr<uint16_t>(dst + i * 2) = *gptr<const uint16_t>(src + i * 2);
 }
 
 // ---------------------------------------------------------------- front end 3: fused columns
@@ -1031,7 +1066,14 @@ struct SimShape {
     // passes: the run is cut into groups of slabs, or one slab's chunks into byte ranges
     uint32_t slabs_per_pass, n_sub;
     uint64_t sub_bytes, n_passes;
-    bool p2p;  // point-to-point: two steps, one chunk per slab, separate receive buffers
+    // What the run is.  Everything but the ring moves one message chunk per slab; the chains have one
+    // rank active per step, the point-to-point kinds two steps and separate receive buffers.
+    enum Kind { kRing, kSendRecv, kBroadcast, kReduce, kAllToAll } kind;
+    uint32_t root;        // chains
+    uint32_t a2a_chunks;  // all-to-all: the caller's chunks per block (S = (R-1) * a2a_chunks)
+    bool two_lists() const { return kind == kSendRecv || kind == kAllToAll; }
+    bool chain() const { return kind == kBroadcast || kind == kReduce; }
+    uint32_t active() const { return chain() ? 1 : R; }  // ranks at work in one step
 };
 
 uint64_t round_up(uint64_t x, uint64_t m) { return (x + m - 1) / m * m; }
@@ -1042,24 +1084,36 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     if (!d) return R2_ERR_INVALID;
     if (d->n_ranks < 2 || d->n_ranks > R2_MAX_RANKS) return R2_ERR_INVALID;
     if (d->n_channels == 0 || d->n_channels > R2_MAX_CHANNELS) return R2_ERR_INVALID;
-    if (d->n_slabs == 0 || (uint64_t)d->n_slabs * d->n_ranks > 65535) return R2_ERR_INVALID;
+    if (d->n_slabs == 0) return R2_ERR_INVALID;
     if (d->align == 0 || d->align % 16 != 0) return R2_ERR_INVALID;
     if (!valid_dtype(d->dtype)) return R2_ERR_INVALID;
-    if (d->phases != R2_PHASE_RS && d->phases != R2_PHASE_AG && d->phases != (R2_PHASE_RS | R2_PHASE_AG) &&
-        d->phases != R2_PHASE_SENDRECV)
-        return R2_ERR_INVALID;
+    switch (d->phases) {
+    case R2_PHASE_RS:
+    case R2_PHASE_AG:
+    case R2_PHASE_RS | R2_PHASE_AG: s.kind = SimShape::kRing; break;
+    case R2_PHASE_SENDRECV: s.kind = SimShape::kSendRecv; break;
+    case R2_PHASE_BROADCAST: s.kind = SimShape::kBroadcast; break;
+    case R2_PHASE_REDUCE: s.kind = SimShape::kReduce; break;
+    case R2_PHASE_ALLTOALL: s.kind = SimShape::kAllToAll; break;
+    default: return R2_ERR_INVALID;
+    }
     if (d->schedule != R2_SCHED_AUTO && d->schedule != R2_SCHED_STEPS && d->schedule != R2_SCHED_FUSED)
         return R2_ERR_INVALID;
-    const bool p2p = d->phases == R2_PHASE_SENDRECV;
-    if (p2p && d->schedule == R2_SCHED_FUSED) return R2_ERR_INVALID;
-    const uint64_t per = p2p ? d->n_slabs : (uint64_t)d->n_slabs * d->n_ranks;
+    if (s.kind != SimShape::kRing && d->schedule == R2_SCHED_FUSED) return R2_ERR_INVALID;
+    if (s.chain() ? (d->root < 0 || (uint32_t)d->root >= d->n_ranks) : d->root != 0) return R2_ERR_INVALID;
+    s.R = d->n_ranks;
+    s.root = (uint32_t)d->root;
+    s.a2a_chunks = s.kind == SimShape::kAllToAll ? d->n_slabs : 0;
+    // slabs as the schedule sees them: all-to-all has one per round and message chunk
+    const uint64_t slabs = s.a2a_chunks ? (uint64_t)(s.R - 1) * d->n_slabs : d->n_slabs;
+    if (slabs * s.R > 65535) return R2_ERR_INVALID;
+    const bool blocks = s.kind == SimShape::kRing || s.kind == SimShape::kAllToAll;  // R pieces per slab
+    const uint64_t per = blocks ? (uint64_t)d->n_slabs * s.R : d->n_slabs;
     if (d->n_elems % per != 0) return R2_ERR_INVALID;
     if (d->n_elems > (1ull << 60)) return R2_ERR_OVERFLOW;
-    s.p2p = p2p;
-    s.R = d->n_ranks;
-    s.S = d->n_slabs;
+    s.S = (uint32_t)slabs;
     s.C = d->n_channels;
-    s.J = p2p ? 2 : d->phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
+    s.J = s.two_lists() ? 2 : d->phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
     s.T_slab = s.J - 1;
     s.chunk_bytes = d->n_elems / per * elem_bytes(d->dtype);
     s.cap = round_up(s.chunk_bytes ? s.chunk_bytes : 1, 256);
@@ -1071,7 +1125,7 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     s.total_bytes = s.stage_off + (uint64_t)stage;
 
     const uint64_t window = d->stage_window_bytes ? d->stage_window_bytes : kDefaultStageWindow;
-    const uint64_t per_slab = (uint64_t)s.R * s.chunk_bytes;  // stage bytes a step writes per slab
+    const uint64_t per_slab = (uint64_t)s.active() * s.chunk_bytes;  // stage bytes a step writes per slab
     if (per_slab > window) {
         const uint64_t tile_bytes = (uint64_t)kThreads * kUnroll * 16;
         const uint64_t parts = (per_slab + window - 1) / window;
@@ -1110,16 +1164,16 @@ int check_workspace(const void *ws, uint64_t ws_bytes, const SimShape &s)
     return R2_OK;
 }
 
-template <Mode M, bool HAS_OUT>
+template <Mode M, bool HAS_OUT, bool KEEP = false>
 void launch_step(const StepArgs &a, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT>), grid, dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT, KEEP>), grid, dim3(kThreads), 0, st, a);
 }
 
 // The fused-column schedule needs whole 16-byte vectors everywhere and a grid that fits.
 bool fused_eligible(const SimShape &s)
 {
-    if (s.p2p) return false;
+    if (s.kind != SimShape::kRing) return false;
     if (s.chunk_bytes == 0 || s.chunk_bytes % 16 != 0) return false;
     const uint64_t cols = (s.chunk_bytes + kNarrowColBytes - 1) / kNarrowColBytes;
     return cols * s.S <= 0x7fffffffull;
@@ -1164,16 +1218,16 @@ int plan_schedule(const r2_sim_desc *desc, const SimShape &s, const r2_epoch *ep
 // A stage this large is gone from the caches before anybody reads it back: written around them.
 constexpr uint64_t kNtStageBytes = 128ull << 20;
 
-template <Mode M, bool HAS_OUT, bool FWD = false>
+template <Mode M, bool HAS_OUT, bool FWD = false, bool KEEP = false>
 void launch_single(const ChunkJob &job, const PtrList &in, const PtrList &out, int32_t *status,
                    unsigned blocks, hipStream_t st)
 {
     if (HAS_OUT && job.bytes > kNtStageBytes)
-        hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD, HAS_OUT>), dim3(blocks), dim3(kThreads), 0, st, job,
-                           in, out, status);
+        hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD, HAS_OUT, KEEP>), dim3(blocks), dim3(kThreads), 0, st,
+                           job, in, out, status);
     else
-        hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD, false>), dim3(blocks), dim3(kThreads), 0, st, job, in,
-                           out, status);
+        hipLaunchKernelGGL((reduce_copy_kernel<M, HAS_OUT, FWD, false, KEEP>), dim3(blocks), dim3(kThreads), 0, st, job,
+                           in, out, status);
 }
 
 }  // namespace
@@ -1187,11 +1241,11 @@ extern "C" int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int o
                               uint32_t n_channels, uint64_t stage_capacity, int32_t *status,
                               void *stream)
 {
-    if (!valid_dtype(dtype) || (op != R2_OP_SUM && op != R2_OP_COPY && op != R2_OP_SUM_FORWARD))
+    if (!valid_dtype(dtype) || (op != R2_OP_SUM && op != R2_OP_COPY && op != R2_OP_SUM_FORWARD && op != R2_OP_SUM_SEND))
         return R2_ERR_INVALID;
     if (n_channels == 0 || n_channels > R2_MAX_CHANNELS) return R2_ERR_INVALID;
     if (!in_stage && !out_stage) return R2_ERR_INVALID;
-    if (op == R2_OP_SUM_FORWARD && (!in_stage || !out_stage)) return R2_ERR_INVALID;
+    if ((op == R2_OP_SUM_FORWARD || op == R2_OP_SUM_SEND) && (!in_stage || !out_stage)) return R2_ERR_INVALID;
     if ((in_stage && !in_offsets) || (out_stage && !out_offsets)) return R2_ERR_INVALID;
     if (bytes % elem_bytes(dtype) != 0) return R2_ERR_INVALID;
     if (bytes == 0) return R2_OK;
@@ -1217,11 +1271,13 @@ extern "C" int r2_reduce_copy(void *local, uint64_t bytes, r2_dtype dtype, int o
     case kSend: launch_single<kSend, true>(job, in, out, status, blocks, st); break;
     case kSumF32:
         if (op == R2_OP_SUM_FORWARD) launch_single<kSumF32, true, true>(job, in, out, status, blocks, st);
+        else if (op == R2_OP_SUM_SEND) launch_single<kSumF32, true, false, true>(job, in, out, status, blocks, st);
         else if (has_out) launch_single<kSumF32, true>(job, in, out, status, blocks, st);
         else launch_single<kSumF32, false>(job, in, out, status, blocks, st);
         break;
     case kSumBF16:
         if (op == R2_OP_SUM_FORWARD) launch_single<kSumBF16, true, true>(job, in, out, status, blocks, st);
+        else if (op == R2_OP_SUM_SEND) launch_single<kSumBF16, true, false, true>(job, in, out, status, blocks, st);
         else if (has_out) launch_single<kSumBF16, true>(job, in, out, status, blocks, st);
         else launch_single<kSumBF16, false>(job, in, out, status, blocks, st);
         break;
@@ -1292,7 +1348,7 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     if (!rank_bufs || step >= s.J || pass >= s.n_passes) return R2_ERR_INVALID;
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
     StepArgs a{};
-    const uint32_t first_buf = s.p2p && step == 1 ? s.R : 0;  // point-to-point receives into the second list
+    const uint32_t first_buf = s.two_lists() && step == 1 ? s.R : 0;  // receives go into the second list
     for (uint32_t r = 0; r < s.R; ++r) {
         a.rank_buf[r] = reinterpret_cast<uint64_t>(rank_bufs[first_buf + r]);
         if (s.chunk_bytes && (!a.rank_buf[r] || (a.rank_buf[r] & 15u))) return R2_ERR_INVALID;
@@ -1308,7 +1364,12 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     a.step = step;
     a.T_slab = s.T_slab;
     a.chunk_start = desc->phases == R2_PHASE_AG ? 1 : 0;
-    a.per_slab = s.p2p ? 1 : s.R;
+    a.per_slab = s.kind == SimShape::kRing ? s.R : 1;
+    a.a2a_chunks = s.a2a_chunks;
+    // a chain has one rank at work per step: the step-th after the root, or after the root's successor
+    a.rank_base = s.kind == SimShape::kBroadcast ? (s.root + step) % s.R
+                  : s.kind == SimShape::kReduce  ? (s.root + 1 + step) % s.R
+                                                 : 0;
     if (s.n_sub > 1) {  // one slab, one byte range of its chunks
         a.slab_begin = (uint32_t)(pass / s.n_sub);
         a.slab_count = 1;
@@ -1323,20 +1384,25 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
 
     const bool has_in = step > 0, has_out = step < s.J - 1;
     int op;
-    if (desc->phases == R2_PHASE_AG || s.p2p) op = R2_OP_COPY;
-    else if (desc->phases == R2_PHASE_RS) op = R2_OP_SUM;
+    if (desc->phases == R2_PHASE_AG || s.two_lists() || s.kind == SimShape::kBroadcast) op = R2_OP_COPY;
+    else if (desc->phases == R2_PHASE_RS || s.kind == SimShape::kReduce) op = R2_OP_SUM;
     else op = step <= s.R - 1 ? R2_OP_SUM : R2_OP_COPY;
     const Mode m = mode_of(has_in, op, desc->dtype);
+    const bool keep = s.kind == SimShape::kReduce && has_in && has_out;  // the sum is passed on, not kept
 
-    const dim3 grid(blocks_for(a.hi - a.lo), s.R * a.slab_count);
+    const dim3 grid(blocks_for(a.hi - a.lo), s.active() * a.slab_count);
     hipStream_t st = (hipStream_t)stream;
     switch (m) {
     case kSend: launch_step<kSend, true>(a, grid, st); break;
     case kSumF32:
-        if (has_out) launch_step<kSumF32, true>(a, grid, st); else launch_step<kSumF32, false>(a, grid, st);
+        if (keep) launch_step<kSumF32, true, true>(a, grid, st);
+        else if (has_out) launch_step<kSumF32, true>(a, grid, st);
+        else launch_step<kSumF32, false>(a, grid, st);
         break;
     case kSumBF16:
-        if (has_out) launch_step<kSumBF16, true>(a, grid, st); else launch_step<kSumBF16, false>(a, grid, st);
+        if (keep) launch_step<kSumBF16, true, true>(a, grid, st);
+        else if (has_out) launch_step<kSumBF16, true>(a, grid, st);
+        else launch_step<kSumBF16, false>(a, grid, st);
         break;
     case kCopy:
         if (has_out) launch_step<kCopy, true>(a, grid, st); else launch_step<kCopy, false>(a, grid, st);
@@ -1451,7 +1517,7 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
     int rc = shape_of(desc, s);
     if (rc) return rc;
     if (!rank_bufs) return R2_ERR_INVALID;
-    for (uint32_t r = 0; r < (s.p2p ? 2 * s.R : s.R); ++r) {
+    for (uint32_t r = 0; r < (s.two_lists() ? 2 * s.R : s.R); ++r) {
         const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
         if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
     }
@@ -1489,6 +1555,18 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
     if ((rc = r2_sim_prepare(desc, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream)))
         return rc;
     if (s.chunk_bytes == 0) return R2_OK;
+    if (s.kind == SimShape::kAllToAll) {  // every rank keeps its own block: no channel involved
+        OwnBlockArgs own{};
+        own.bytes = s.chunk_bytes * s.a2a_chunks;
+        for (uint32_t r = 0; r < s.R; ++r) {
+            own.src[r] = reinterpret_cast<uint64_t>(rank_bufs[r]) + r * own.bytes;
+            own.dst[r] = reinterpret_cast<uint64_t>(rank_bufs[s.R + r]) + r * own.bytes;
+        }
+        const uint64_t want = (own.bytes + kThreads * 16 - 1) / (kThreads * 16);
+        const dim3 grid((unsigned)(want < 4096 ? want : 4096), s.R);
+        hipLaunchKernelGGL(own_block_copy_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, own);
+        if ((rc = hip_rc(hipGetLastError()))) return rc;
+    }
     for (uint64_t p = 0; p < s.n_passes; ++p)
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
@@ -1504,6 +1582,22 @@ extern "C" int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_
     void *both[2 * R2_MAX_RANKS];
     for (uint32_t r = 0; r < desc->n_ranks; ++r) {
         both[r] = const_cast<void *>(send_bufs[r]);  // step 0 only reads them
+        both[desc->n_ranks + r] = recv_bufs[r];
+        for (uint32_t q = 0; q < desc->n_ranks; ++q)
+            if (send_bufs[q] == recv_bufs[r] && desc->n_elems) return R2_ERR_INVALID;  // no in-place exchange
+    }
+    return r2_ring_allreduce_sim(desc, both, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream);
+}
+
+extern "C" int r2_alltoall_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
+                               const r2_epoch *epochs, uint32_t n_epochs, void *workspace,
+                               uint64_t workspace_bytes, uint64_t *offsets_log, void *stream)
+{
+    if (!desc || desc->phases != R2_PHASE_ALLTOALL || !send_bufs || !recv_bufs) return R2_ERR_INVALID;
+    if (desc->n_ranks < 2 || desc->n_ranks > R2_MAX_RANKS) return R2_ERR_INVALID;
+    void *both[2 * R2_MAX_RANKS];
+    for (uint32_t r = 0; r < desc->n_ranks; ++r) {
+        both[r] = const_cast<void *>(send_bufs[r]);  // only read
         both[desc->n_ranks + r] = recv_bufs[r];
         for (uint32_t q = 0; q < desc->n_ranks; ++q)
             if (send_bufs[q] == recv_bufs[r] && desc->n_elems) return R2_ERR_INVALID;  // no in-place exchange

@@ -79,7 +79,11 @@ def test_pass_planning(r2):
 @pytest.mark.parametrize("bad", [
     dict(n_ranks=1), dict(n_ranks=65), dict(n_channels=0), dict(n_channels=65), dict(n_slabs=0),
     dict(align=0), dict(align=8), dict(align=24), dict(n_elems=(1 << 20) + 1), dict(dtype=7),
-    dict(phases=0), dict(phases=5), dict(phases=7), dict(phases=8), dict(n_slabs=8192, n_elems=8192 * 8 * 4), dict(schedule=3),
+    dict(phases=0), dict(phases=5), dict(phases=7), dict(phases=9), dict(phases=24), dict(phases=48), dict(phases=64),
+    dict(n_slabs=8192, n_elems=8192 * 8 * 4), dict(schedule=3), dict(root=1),
+    dict(phases=8, root=8), dict(phases=8, root=-1), dict(phases=16, root=8), dict(phases=32, root=1),
+    dict(phases=8, schedule=2), dict(phases=16, schedule=2), dict(phases=32, schedule=2),
+    dict(phases=32, n_slabs=1171, n_elems=1171 * 8 * 16),  # all-to-all: R*(R-1)*S > 65535
 ])
 def test_invalid_descriptors(r2, bad):
     base = dict(n_ranks=8, n_slabs=1, n_channels=8, align=256, n_elems=1 << 20, dtype=r2.BF16,
@@ -103,6 +107,26 @@ def test_sendrecv_descriptor_arithmetic(r2):
     assert r2.r2_sim_resolve_schedule(d, [(0, 0, [1] * 8)]) == r2.SCHED_STEPS
     assert r2.r2_sim_num_steps(r2.SimDesc(8, 6, 8, 256, 6 * 1000 + 1, r2.BF16, r2.PHASE_SENDRECV)) == 0
     assert r2.r2_sim_num_steps(r2.SimDesc(8, 6, 8, 256, 6000, r2.BF16, r2.PHASE_SENDRECV, 0, r2.SCHED_FUSED)) == 0
+
+
+def test_chain_and_alltoall_descriptor_arithmetic(r2):
+    """Broadcast and Reduce: R steps, R-1 transmissions per message chunk, one rank at work per step (so
+    the stage window counts one rank's chunk).  All-to-all: two steps, (R-1)*S internal slabs."""
+    for ph in (r2.PHASE_BROADCAST, r2.PHASE_REDUCE):
+        d = r2.SimDesc(8, 6, 8, 256, 6 * 1000, r2.BF16, ph, root=7)
+        assert r2.r2_sim_num_steps(d) == 8
+        assert r2.r2_sim_num_transmissions(d) == 6 * 7
+        assert r2.r2_sim_stage_capacity(d) == 2048
+        assert r2.r2_sim_resolve_schedule(d, [(0, 0, [1] * 8)]) == r2.SCHED_STEPS
+        assert r2.r2_sim_num_steps(r2.SimDesc(8, 6, 8, 256, 6 * 1000 + 1, r2.BF16, ph)) == 0
+        # 4 chunks of 64 MiB each, one rank per step: two chunks fit the 128 MiB window
+        assert r2.r2_sim_num_passes(r2.SimDesc(8, 4, 8, 256, 1 << 27, r2.BF16, ph)) == 2
+    d = r2.SimDesc(4, 5, 8, 256, 4 * 5 * 100, r2.F32, r2.PHASE_ALLTOALL)
+    assert r2.r2_sim_num_steps(d) == 2
+    assert r2.r2_sim_num_transmissions(d) == 3 * 5
+    assert r2.r2_sim_stage_capacity(d) == 512  # 400 bytes per chunk
+    assert r2.r2_sim_workspace_bytes(d) == r2.r2_sim_stage_offset(d) + 2 * 4 * 15 * 8 * 512
+    assert r2.r2_sim_num_steps(r2.SimDesc(4, 5, 8, 256, 4 * 5 * 100 + 4, r2.F32, r2.PHASE_ALLTOALL)) == 0
 
 
 def test_sim_rejects_bad_epochs_and_buffers_before_any_device_work(r2):
