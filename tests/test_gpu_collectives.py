@@ -225,3 +225,66 @@ def test_collectives_argument_errors(r2):
             r2.r2_sim_fused_steps(d, sb, 0, 2, space)
     torch.cuda.synchronize()
     assert all(float(t.sum()) == 128.0 for t in sb) and all(float(t.abs().sum()) == 0.0 for t in rb)
+
+
+def test_collectives_maximum_ranks_and_channels(r2, oracle):
+    """64 ranks and 64 channels, most of them down: every kernel argument array is used to its end."""
+    rng = np.random.default_rng(805)
+    C = 64
+    w = [int(x) for x in rng.integers(1, 1000, C)]
+    alive = (1 << 3) | (1 << 31) | (1 << 63)
+    epochs = [(0, 0, w), (5, ((1 << C) - 1) & ~alive, w), (40, 1 << 63, w)]
+    say("broadcast / reduce, R=64 C=64")
+    xs = _inputs(rng, 64, 2 * 8 * 33, "bf16")
+    _run_chain(r2, oracle, "broadcast", xs, "bf16", 63, 2, C, 16, epochs)
+    _run_chain(r2, oracle, "reduce", xs, "bf16", 17, 2, C, 16, epochs)
+    say("alltoall, R=64 C=64, 16 chunks per block (the most the grid allows)")
+    send = _inputs(rng, 64, 64 * 16 * 4, "f32")
+    _run_alltoall(r2, oracle, send, "f32", 16, C, 16, epochs)
+
+
+def test_alltoall_and_reduce_in_a_graph(r2, oracle):
+    """The calls only enqueue kernels (the own-block copy included), so they can be captured and
+    replayed; every replay is checked, with eager work in between."""
+    rng = np.random.default_rng(806)
+    R, S, C, E = 4, 2, 8, 8 * 700
+    epochs = [(0, 0, [50000] * C), (3, 0b00010010, [50000] * C)]
+    send = _inputs(rng, R, R * S * E, "bf16")
+    want_a2a = col.alltoall_expected(send)
+    want_red = col.reduce_expected(send, oracle.BF16, 2)
+    d_a2a = r2.SimDesc(R, S, C, 256, R * S * E, r2.BF16, r2.PHASE_ALLTOALL)
+    d_red = r2.SimDesc(R, S, C, 256, R * S * E, r2.BF16, r2.PHASE_REDUCE, root=2)
+    ws1 = torch.empty(r2.r2_sim_workspace_bytes(d_a2a), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(r2.r2_sim_workspace_bytes(d_red), dtype=torch.uint8, device="cuda")
+    pristine = [_dev(x) for x in send]
+    sb = [p.clone() for p in pristine]
+    rb = [torch.zeros_like(p) for p in pristine]
+
+    def both():
+        r2.r2_alltoall_sim(d_a2a, sb, rb, epochs, ws1)
+        r2.r2_ring_allreduce_sim(d_red, sb, epochs, ws2)  # reduces the send buffers in place afterwards
+
+    say("graph capture: all-to-all, then reduce")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        both()  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        both()
+    for replay in range(3):
+        say(f"graph replay {replay}")
+        for b, p in zip(sb, pristine):
+            b.copy_(p)
+        for b in rb:
+            b.zero_()
+        junk = torch.randn(1 << 16, device="cuda").sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for r in range(R):
+            assert rb[r].cpu().numpy().view(np.uint16).tobytes() == want_a2a[r].tobytes(), f"replay {replay}: all-to-all rank {r}"
+            assert sb[r].cpu().numpy().view(np.uint16).tobytes() == want_red[r].tobytes(), f"replay {replay}: reduce rank {r}"
