@@ -55,7 +55,10 @@ enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2, /* both = all-reduce */
        R2_PHASE_SENDRECV = 4,   /* point-to-point to the ring successor */
        R2_PHASE_BROADCAST = 8,  /* ring broadcast from desc->root       */
        R2_PHASE_REDUCE = 16,    /* ring reduce to desc->root            */
-       R2_PHASE_ALLTOALL = 32   /* pairwise exchange of R blocks        */ };
+       R2_PHASE_ALLTOALL = 32,  /* pairwise exchange of R blocks        */
+       /* a flag for the ring phases (RS, AG or both): one table per ring link instead of one per
+          transmission; see r2_ring_rails_sim */
+       R2_PHASE_LINKS = 64 };
 enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2 };
 
 /* Static, human-readable text for a return code. */
@@ -296,6 +299,22 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
 int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
                     const r2_epoch *epochs, uint32_t n_epochs, void *workspace, uint64_t workspace_bytes,
                     uint64_t *offsets_log, void *stream);
+
+/* A ring whose servers have lost different NICs -- Sec. 6 "Topology-Aware Logical Re-ranking": when
+ * node u loses rail r and its neighbour v loses rail r', what they share drops to the rails that
+ * survive at both.  desc->phases must be R2_PHASE_LINKS plus the ring phases.  rank_bufs are given in
+ * ring order (after any re-ranking, e.g. by r2_bridge_rerank); fail_masks[r] are the channels rank r
+ * has lost.  The link r -> r+1 carries every transmission of rank r over the channels up at both
+ * ends, cut in proportion to `weights` (fail mask of the link: fail_masks[r] | fail_masks[r+1]); rank
+ * r+1 reads with that same table.  The tables area of the workspace then holds R rows, row r = the
+ * link r -> r+1 (r2_sim_num_transmissions returns R), and offsets_log, if not NULL, receives them.
+ * The result in the rank buffers is the ring's (all-reduce, reduce-scatter or all-gather), whatever
+ * the masks.  weights, fail_masks: HOST arrays (n_channels, n_ranks).  Only the step schedule runs
+ * it; R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if some link has no channel left -- which is
+ * what re-ranking is for.  Asynchronous on `stream`; allocates nothing. */
+int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs, const uint32_t *weights,
+                      const uint64_t *fail_masks, void *workspace, uint64_t workspace_bytes,
+                      uint64_t *offsets_log, void *stream);
 
 /* All-to-All under R2CCL-Balance (Sec. 5, table of strategies: point-to-point incl. All-to-All;
  * Sec. 5.1): desc->phases must be R2_PHASE_ALLTOALL.  Afterwards block q of recv_bufs[r] equals

@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 OP_SUM, OP_COPY, OP_SUM_FORWARD, OP_SUM_SEND = 0, 1, 2, 3
 PHASE_RS, PHASE_AG = 1, 2
 PHASE_AR = PHASE_RS | PHASE_AG
-PHASE_SENDRECV, PHASE_BROADCAST, PHASE_REDUCE, PHASE_ALLTOALL = 4, 8, 16, 32
+PHASE_SENDRECV, PHASE_BROADCAST, PHASE_REDUCE, PHASE_ALLTOALL, PHASE_LINKS = 4, 8, 16, 32, 64
 SCHED_AUTO, SCHED_STEPS, SCHED_FUSED = 0, 1, 2
 
 R2_OK = 0
@@ -202,6 +202,8 @@ def load_library():
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_sendrecv_sim.restype = i32
     lib.r2_sendrecv_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
+    lib.r2_ring_rails_sim.restype = i32
+    lib.r2_ring_rails_sim.argtypes = [pd, vp, vp, vp, vp, u64, vp, vp]
     lib.r2_alltoall_sim.restype = i32
     lib.r2_alltoall_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
     _lib = lib
@@ -550,6 +552,21 @@ def r2_sendrecv_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epo
                                         wp, wb, _ptr(offsets_log), _stream(stream))
     del sa, ra, keep
     _check(rc, "r2_sendrecv_sim")
+
+
+def r2_ring_rails_sim(desc: SimDesc, rank_bufs: Sequence, weights: Sequence[int], fail_masks: Sequence[int],
+                      workspace, offsets_log: Optional[torch.Tensor] = None, stream=None,
+                      workspace_bytes: Optional[int] = None) -> None:
+    if len(weights) != desc.n_channels or len(fail_masks) != desc.n_ranks or len(rank_bufs) != desc.n_ranks:
+        raise ValueError("r2_ring_rails_sim: one weight per channel, one mask and one buffer per rank")
+    arr, p = _ptr_array(rank_bufs)
+    w = (C.c_uint32 * len(weights))(*[int(x) for x in weights])
+    m = (C.c_uint64 * len(fail_masks))(*[int(x) for x in fail_masks])
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_ring_rails_sim(C.byref(desc.c()), p, C.cast(w, C.c_void_p), C.cast(m, C.c_void_p),
+                                          wp, wb, _ptr(offsets_log), _stream(stream))
+    del arr
+    _check(rc, "r2_ring_rails_sim")
 
 
 def r2_alltoall_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epochs, workspace,

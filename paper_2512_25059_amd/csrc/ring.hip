@@ -378,6 +378,7 @@ struct StepArgs {
     uint32_t per_slab;     // ring chunks per slab: R, or 1 where a slab is one message chunk
     uint32_t rank_base;    // the first rank this launch covers (chains: the one rank active at this step)
     uint32_t a2a_chunks;   // all-to-all: message chunks per block (a slab is chunk l % this of round l / this + 1), else 0
+    uint32_t link_tables;  // 1: row r of `tables` is the link r -> r+1, for every transmission of rank r
     uint32_t slab_begin, slab_count;  // the slabs this launch covers
     uint64_t lo, hi;                  // and the byte range of every ring chunk it moves
 };
@@ -411,8 +412,8 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
     job.bytes = a.chunk_bytes;
     job.lo = a.lo;
     job.hi = a.hi;
-    job.in_off = M != kSend ? a.tables + (t_out - 1) * row : nullptr;
-    job.out_off = HAS_OUT ? a.tables + t_out * row : nullptr;
+    job.in_off = M != kSend ? a.tables + (a.link_tables ? peer : t_out - 1) * row : nullptr;
+    job.out_off = HAS_OUT ? a.tables + (a.link_tables ? r : t_out) * row : nullptr;
     job.cap = a.cap;
     job.C = a.C;
     // stage buffer of (parity, rank, slab, channel)
@@ -1070,6 +1071,7 @@ struct SimShape {
     // rank active per step, the point-to-point kinds two steps and separate receive buffers.
     enum Kind { kRing, kSendRecv, kBroadcast, kReduce, kAllToAll } kind;
     uint32_t root;        // chains
+    bool links;           // ring with one table per link (row r: r -> r+1) instead of one per transmission
     uint32_t a2a_chunks;  // all-to-all: the caller's chunks per block (S = (R-1) * a2a_chunks)
     bool two_lists() const { return kind == kSendRecv || kind == kAllToAll; }
     bool chain() const { return kind == kBroadcast || kind == kReduce; }
@@ -1087,7 +1089,8 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     if (d->n_slabs == 0) return R2_ERR_INVALID;
     if (d->align == 0 || d->align % 16 != 0) return R2_ERR_INVALID;
     if (!valid_dtype(d->dtype)) return R2_ERR_INVALID;
-    switch (d->phases) {
+    s.links = (d->phases & R2_PHASE_LINKS) != 0;
+    switch (d->phases & ~R2_PHASE_LINKS) {
     case R2_PHASE_RS:
     case R2_PHASE_AG:
     case R2_PHASE_RS | R2_PHASE_AG: s.kind = SimShape::kRing; break;
@@ -1099,7 +1102,9 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     }
     if (d->schedule != R2_SCHED_AUTO && d->schedule != R2_SCHED_STEPS && d->schedule != R2_SCHED_FUSED)
         return R2_ERR_INVALID;
-    if (s.kind != SimShape::kRing && d->schedule == R2_SCHED_FUSED) return R2_ERR_INVALID;
+    if (s.links && s.kind != SimShape::kRing) return R2_ERR_INVALID;
+    if ((s.kind != SimShape::kRing || s.links) && d->schedule == R2_SCHED_FUSED) return R2_ERR_INVALID;
+    const int ring_phases = d->phases & ~R2_PHASE_LINKS;
     if (s.chain() ? (d->root < 0 || (uint32_t)d->root >= d->n_ranks) : d->root != 0) return R2_ERR_INVALID;
     s.R = d->n_ranks;
     s.root = (uint32_t)d->root;
@@ -1113,11 +1118,11 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     if (d->n_elems > (1ull << 60)) return R2_ERR_OVERFLOW;
     s.S = (uint32_t)slabs;
     s.C = d->n_channels;
-    s.J = s.two_lists() ? 2 : d->phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
+    s.J = s.two_lists() ? 2 : ring_phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
     s.T_slab = s.J - 1;
     s.chunk_bytes = d->n_elems / per * elem_bytes(d->dtype);
     s.cap = round_up(s.chunk_bytes ? s.chunk_bytes : 1, 256);
-    s.n_tx = (uint64_t)s.S * s.T_slab;
+    s.n_tx = s.links ? s.R : (uint64_t)s.S * s.T_slab;  // rows of the tables
     s.tables_bytes = round_up(s.n_tx * (s.C + 1) * 8, 256);
     s.stage_off = s.tables_bytes;
     const unsigned __int128 stage = (unsigned __int128)2 * s.R * s.S * s.C * s.cap;
@@ -1173,7 +1178,7 @@ void launch_step(const StepArgs &a, dim3 grid, hipStream_t st)
 // The fused-column schedule needs whole 16-byte vectors everywhere and a grid that fits.
 bool fused_eligible(const SimShape &s)
 {
-    if (s.kind != SimShape::kRing) return false;
+    if (s.kind != SimShape::kRing || s.links) return false;
     if (s.chunk_bytes == 0 || s.chunk_bytes % 16 != 0) return false;
     const uint64_t cols = (s.chunk_bytes + kNarrowColBytes - 1) / kNarrowColBytes;
     return cols * s.S <= 0x7fffffffull;
@@ -1363,9 +1368,11 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     a.C = s.C;
     a.step = step;
     a.T_slab = s.T_slab;
-    a.chunk_start = desc->phases == R2_PHASE_AG ? 1 : 0;
+    const int ring_phases = desc->phases & ~R2_PHASE_LINKS;
+    a.chunk_start = ring_phases == R2_PHASE_AG ? 1 : 0;
     a.per_slab = s.kind == SimShape::kRing ? s.R : 1;
     a.a2a_chunks = s.a2a_chunks;
+    a.link_tables = s.links;
     // a chain has one rank at work per step: the step-th after the root, or after the root's successor
     a.rank_base = s.kind == SimShape::kBroadcast ? (s.root + step) % s.R
                   : s.kind == SimShape::kReduce  ? (s.root + 1 + step) % s.R
@@ -1384,8 +1391,8 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
 
     const bool has_in = step > 0, has_out = step < s.J - 1;
     int op;
-    if (desc->phases == R2_PHASE_AG || s.two_lists() || s.kind == SimShape::kBroadcast) op = R2_OP_COPY;
-    else if (desc->phases == R2_PHASE_RS || s.kind == SimShape::kReduce) op = R2_OP_SUM;
+    if (ring_phases == R2_PHASE_AG || s.two_lists() || s.kind == SimShape::kBroadcast) op = R2_OP_COPY;
+    else if (ring_phases == R2_PHASE_RS || s.kind == SimShape::kReduce) op = R2_OP_SUM;
     else op = step <= s.R - 1 ? R2_OP_SUM : R2_OP_COPY;
     const Mode m = mode_of(has_in, op, desc->dtype);
     const bool keep = s.kind == SimShape::kReduce && has_in && has_out;  // the sum is passed on, not kept
@@ -1521,6 +1528,7 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
         if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
     }
+    if (s.links) return R2_ERR_INVALID;  // per-link tables come from r2_ring_rails_sim, not from epochs
     if (desc->schedule == R2_SCHED_FUSED && s.chunk_bytes && !fused_eligible(s)) return R2_ERR_INVALID;
     if ((rc = check_epochs(epochs, n_epochs, s))) return rc;
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
@@ -1567,6 +1575,36 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         hipLaunchKernelGGL(own_block_copy_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, own);
         if ((rc = hip_rc(hipGetLastError()))) return rc;
     }
+    for (uint64_t p = 0; p < s.n_passes; ++p)
+        for (uint32_t j = 0; j < s.J; ++j)
+            if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
+    return R2_OK;
+}
+
+extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs, const uint32_t *weights,
+                                 const uint64_t *fail_masks, void *workspace, uint64_t workspace_bytes,
+                                 uint64_t *offsets_log, void *stream)
+{
+    SimShape s;
+    int rc = shape_of(desc, s);
+    if (rc) return rc;
+    if (!s.links || !rank_bufs || !weights || !fail_masks) return R2_ERR_INVALID;
+    for (uint32_t r = 0; r < s.R; ++r) {
+        const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
+        if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
+    }
+    if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
+    // One table per link, cut by the channels that are up at both of its ends.
+    const uint64_t full = s.C == 64 ? ~0ull : ((1ull << s.C) - 1);
+    r2_epoch links[R2_MAX_RANKS];
+    for (uint32_t r = 0; r < s.R; ++r) {
+        links[r] = r2_epoch{r, (fail_masks[r] | fail_masks[(r + 1) % s.R]) & full, weights};
+        if (!any_healthy(weights, links[r].fail_mask, s.C)) return R2_ERR_NO_HEALTHY_CHANNEL;
+    }
+    if ((rc = launch_partition_epochs(links, s.R, s.C, desc->align, s.chunk_bytes, s.R,
+                                      static_cast<uint64_t *>(workspace), offsets_log, (hipStream_t)stream)))
+        return rc;
+    if (s.chunk_bytes == 0) return R2_OK;
     for (uint64_t p = 0; p < s.n_passes; ++p)
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;

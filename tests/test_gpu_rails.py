@@ -1,0 +1,147 @@
+"""GPU parity: a ring whose ranks lost different rails (R2_PHASE_LINKS, r2_ring_rails_sim; Sec. 6) vs the
+oracle, byte for byte: rank buffers, the per-link tables, the stage area; and the bridge re-ranking
+feeding the ring order."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import FILL, say
+from oracle import rails
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def r2():
+    import paper_2512_25059_amd as pkg
+
+    pkg.load_library()
+    assert torch.cuda.is_available()
+    return pkg
+
+
+def _dev(a):
+    return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+
+def _inputs(rng, R, N, dtype):
+    if dtype == "bf16":
+        return [torch.from_numpy(rng.standard_normal(N).astype(np.float32)).to(torch.bfloat16)
+                .view(torch.int16).numpy().view(np.uint16).copy() for _ in range(R)]
+    return [rng.standard_normal(N).astype(np.float32) for _ in range(R)]
+
+
+def _run(r2, oracle, xs, dtype, phases, S, C, align, weights, masks, window=0, check_stage=True):
+    R, N = len(xs), xs[0].size
+    gdt = r2.F32 if dtype == "f32" else r2.BF16
+    odt = oracle.F32 if dtype == "f32" else oracle.BF16
+    gph = {"rs": r2.PHASE_RS, "ag": r2.PHASE_AG, "ar": r2.PHASE_AR}[phases] | r2.PHASE_LINKS
+    oph = {"rs": oracle.PHASE_RS, "ag": oracle.PHASE_AG, "ar": oracle.PHASE_AR}[phases]
+    desc = r2.SimDesc(R, S, C, align, N, gdt, gph, window, 0)
+    assert r2.r2_sim_num_transmissions(desc) == R  # one table per link
+    assert r2.r2_sim_resolve_schedule(desc, [(0, 0, weights)]) == r2.SCHED_STEPS
+    ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
+    log = torch.full((R, C + 1), -1, dtype=torch.int64, device="cuda")
+    bufs = [_dev(x) for x in xs]
+    r2.r2_ring_rails_sim(desc, bufs, weights, masks, ws, log)
+    torch.cuda.synchronize()
+    o_bufs = [x.copy() for x in xs]
+    tables, stage = rails.ring_rails_sim(o_bufs, odt, S, C, align, weights, masks, oph, FILL)
+    want = oracle.expected(xs, odt, S, oph)
+    for r in range(R):
+        got = bufs[r].cpu().numpy().view(xs[r].dtype)
+        assert got.tobytes() == want[r].tobytes(), f"rank {r} vs definition"
+        assert got.tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
+    assert log.cpu().numpy().view(np.uint64).tolist() == tables.tolist()
+    assert ws[:R * (C + 1) * 8].cpu().numpy().view(np.uint64).reshape(R, C + 1).tolist() == tables.tolist()
+    if check_stage:
+        cap = r2.r2_sim_stage_capacity(desc)
+        off = r2.r2_sim_stage_offset(desc)
+        st = ws[off:off + 2 * R * S * C * cap].cpu().numpy()
+        assert st.tobytes() == stage.tobytes(), "stage area"
+
+
+@pytest.mark.parametrize("phases", ["rs", "ag", "ar"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rails_small(r2, oracle, dtype, phases):
+    rng = np.random.default_rng(900)
+    per16 = 4 if dtype == "f32" else 8
+    w = [50000, 25000, 50000, 12500, 50000, 50000, 1, 50000]
+    for R, S, E in ((2, 1, per16 * 100), (4, 3, per16 * 1031), (8, 2, 7), (3, 2, per16 * 512 * 5 + 3), (5, 1, per16 * 512 * 2)):
+        masks = [int(rng.integers(0, 256)) & ~0b00010000 for _ in range(R)]  # rail 4 survives everywhere
+        say(f"rails {phases} {dtype} R={R} S={S} E={E} masks={masks}")
+        _run(r2, oracle, _inputs(rng, R, S * R * E, dtype), dtype, phases, S, 8, 256, w, masks)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_rails_random_configurations(r2, oracle, seed):
+    rng = np.random.default_rng(910 + seed)
+    for case in range(20):
+        dtype = "f32" if rng.random() < 0.5 else "bf16"
+        phases = ("rs", "ag", "ar")[int(rng.integers(0, 3))]
+        R, S, C = int(rng.integers(2, 12)), int(rng.integers(1, 4)), int(rng.integers(1, 12))
+        E = int(rng.integers(1, 2500))
+        align = (16, 64, 256)[int(rng.integers(0, 3))]
+        w = [int(x) for x in rng.integers(1, 1000, C)]
+        up = int(rng.integers(0, C))
+        masks = [int(rng.integers(0, 1 << C)) & ~(1 << up) if rng.random() < 0.7 else 0 for _ in range(R)]
+        window = (0, 1, 4096, 50000)[int(rng.integers(0, 4))]
+        say(f"rails random {seed}.{case} {phases} {dtype} R={R} S={S} C={C} E={E} align={align} window={window} masks={masks}")
+        _run(r2, oracle, _inputs(rng, R, S * R * E, dtype), dtype, phases, S, C, align, w, masks, window, True)
+
+
+def test_rails_maximum_ranks_and_channels_and_large_chunks(r2, oracle):
+    rng = np.random.default_rng(920)
+    C = 64
+    w = [int(x) for x in rng.integers(1, 1000, C)]
+    masks = [int(rng.integers(0, 1 << 63)) & ~(1 << 40) for _ in range(64)]
+    masks[63] |= 1 << 63
+    say("rails R=64 C=64")
+    _run(r2, oracle, _inputs(rng, 64, 64 * 8 * 5, "bf16"), "bf16", "ar", 1, C, 16, w, masks)
+    say("rails 2 MiB chunks, a window that forces byte-range passes")
+    xs = _inputs(rng, 4, 4 * (1 << 19), "f32")
+    _run(r2, oracle, xs, "f32", "ar", 1, 8, 256, [50000] * 8, [0b1, 0b10, 0, 0b1100], window=3 << 20)
+
+
+def test_rerank_then_ring(r2, oracle):
+    """Neighbours that lost different rails share nothing; the library's bridge re-ranking moves a healthy
+    node between them and the ring over the new order runs."""
+    rng = np.random.default_rng(921)
+    w = [50000, 50000]
+    masks = [0b01, 0b10, 0, 0]
+    N = 4 * 8 * 300
+    xs = _inputs(rng, 4, N, "bf16")
+    desc = r2.SimDesc(4, 1, 2, 256, N, r2.BF16, r2.PHASE_AR | r2.PHASE_LINKS)
+    ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
+    bufs = [_dev(x) for x in xs]
+    say("rails: a link without a channel is refused before any launch")
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_ring_rails_sim(desc, bufs, w, masks, ws)
+    assert e.value.code == -2
+    torch.cuda.synchronize()
+    assert all(b.cpu().numpy().view(np.uint16).tobytes() == x.tobytes() for b, x in zip(bufs, xs))
+    order, moved = r2.r2_bridge_rerank([0, 1, 2, 3], [~m & 0b11 for m in masks])
+    assert moved == 1 and sorted(order) == [0, 1, 2, 3]
+    say(f"rails: re-ranked order {order}")
+    _run(r2, oracle, [xs[n] for n in order], "bf16", "ar", 1, 2, 256, w, [masks[n] for n in order])
+
+
+def test_rails_argument_errors(r2):
+    w = [1] * 4
+    bufs = [torch.ones(4 * 16, dtype=torch.float32, device="cuda") for _ in range(4)]
+    desc = r2.SimDesc(4, 1, 4, 16, 64, r2.F32, r2.PHASE_AR | r2.PHASE_LINKS)
+    ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    plain = r2.SimDesc(4, 1, 4, 16, 64, r2.F32, r2.PHASE_AR)
+    with pytest.raises(r2.R2Error):  # the flag is missing
+        r2.r2_ring_rails_sim(plain, bufs, w, [0] * 4, ws)
+    with pytest.raises(r2.R2Error):  # per-link tables do not come from epochs
+        r2.r2_ring_allreduce_sim(desc, bufs, [(0, 0, w)], ws)
+    with pytest.raises(r2.R2Error):  # too small a workspace
+        r2.r2_ring_rails_sim(desc, bufs, w, [0] * 4, ws[:256])
+    for bad in (r2.PHASE_LINKS, r2.PHASE_LINKS | r2.PHASE_SENDRECV, r2.PHASE_LINKS | r2.PHASE_BROADCAST):
+        assert r2.r2_sim_num_steps(r2.SimDesc(4, 1, 4, 16, 64, r2.F32, bad)) == 0
+    assert r2.r2_sim_num_steps(r2.SimDesc(4, 1, 4, 16, 64, r2.F32, r2.PHASE_AR | r2.PHASE_LINKS, 0, r2.SCHED_FUSED)) == 0
+    with pytest.raises(r2.R2Error):
+        r2.r2_sim_fused_steps(desc, bufs, 0, 2, ws)
+    torch.cuda.synchronize()
+    assert all(float(b.sum()) == 64.0 for b in bufs)
