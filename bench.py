@@ -26,12 +26,14 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure (8 TB/s)
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled
 # by what the same counter reads for a plain 128 MiB device-to-device copy in the same run
 # (FETCH_SIZE reads half the copied bytes there, WRITE_SIZE all of them).  The figures and the
-# commands are in profiles/ring_step_sum_bf16_cfg2_pmc.md (cfg3: ..._f32_cfg3_pmc.md).  Not measured for
+# commands are in profiles/ring_step_sum_bf16_cfg2_pmc.md (cfg3: ..._f32_cfg3_pmc.md, cfg4: ..._bf16_cfg4_pmc.md).  Not measured for
 # other workloads.
 MEASURED_TRAFFIC = {
-    ("cfg2", "sum"): int((131108.5 * (131072.0 / 65550.8) + 262168.1 * (131072.0 / 131072.0)) * 1024),
+    ("cfg2", "sum"): int((131112.8 * (131072.0 / 65550.7) + 262158.2 * (131072.0 / 131072.0)) * 1024),
     # cfg3: the calibration copy is one 256 MiB rank buffer (profiles/ring_step_sum_f32_cfg3_pmc.md)
-    ("cfg3", "sum"): int((131114.0 * (262144.0 / 131087.2) + 262158.7 * (262144.0 / 262144.0)) * 1024),
+    ("cfg3", "sum"): int((131114.8 * (262144.0 / 131087.4) + 262156.1 * (262144.0 / 262144.0)) * 1024),
+    # cfg4: one 64 MiB rank buffer (profiles/ring_step_sum_bf16_cfg4_pmc.md)
+    ("cfg4", "sum"): int((65611.1 * (65536.0 / 32781.6) + 131074.6 * (65536.0 / 65536.0)) * 1024),
 }
 
 
