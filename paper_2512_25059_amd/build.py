@@ -1,6 +1,7 @@
 """Builds libr2ccl.so for gfx950 with hipcc (cross-compiles; no GPU needed)."""
 from __future__ import annotations
 
+import glob
 import os
 import subprocess
 import sys
@@ -8,8 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("partition.hip", "ring.hip", "split.hip", "recursive.hip", "streams.hip", "rerank.cpp")]
-HEADERS = [os.path.join(HERE, "csrc", "r2_internal.h"), os.path.join(HERE, "csrc", "partition_device.h"),
-           os.path.join(ROOT, "include", "r2ccl.h")]
+HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + [os.path.join(ROOT, "include", "r2ccl.h")]
 LIB = os.path.join(HERE, "libr2ccl.so")
 EXAMPLE_SRC = os.path.join(HERE, "examples", "ring_allreduce.c")
 EXAMPLE = os.path.join(HERE, "examples", "ring_allreduce")
