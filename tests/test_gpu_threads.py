@@ -81,7 +81,7 @@ def test_forking_calls_from_two_threads(r2, oracle):
             errors.append(f"thread {tid}: {e!r}")
 
     say(f"two host threads x {rounds} forking calls")
-    threads = [threading.Thread(target=worker, args=(t,)) for t in range(2)]
+    threads = [threading.Thread(target=worker, args=(t,), daemon=True) for t in range(2)]  # daemon: a stuck call must not keep the process alive
     for t in threads:
         t.start()
     for t in threads:
