@@ -36,6 +36,37 @@ def test_header_symbols_are_exported(r2):
         assert hasattr(lib, n), f"{n} is declared in r2ccl.h but not exported"
 
 
+def test_binding_constants_and_structs_follow_the_header(r2):
+    """The Python names carry the header's values, every exported function has a binding of the same name,
+    and the descriptor structs are laid out as the C compiler lays them out."""
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    enums = dict((k, int(v)) for k, v in re.findall(r"\b(R2_[A-Z0-9_]+)\s*=\s*(-?\d+)", text))
+    defines = dict((k, int(v)) for k, v in re.findall(r"#define\s+(R2_[A-Z0-9_]+)\s+(\d+)", text))
+    assert len(enums) >= 20
+    for name, value in enums.items():
+        short = name[3:]
+        if short.startswith("ERR_") or short == "OK":
+            continue  # error codes travel as R2Error.code
+        assert getattr(r2, short) == value, name
+    assert r2.MAX_LEVELS == defines["R2_MAX_LEVELS"]
+    for fn in _declared_functions():
+        assert hasattr(r2, fn) or hasattr(r2.binding, fn), f"no binding for {fn}"
+    # struct sizes as gcc computes them from the header
+    import subprocess
+    import tempfile
+    names = ["r2_sim_desc", "r2_split_desc", "r2_recursive_desc", "r2_level", "r2_epoch"]
+    src = '#include <stdio.h>\n#include "r2ccl.h"\nint main(void){' + "".join(
+        f'printf("%zu\\n", sizeof({n}));' for n in names) + "return 0;}"
+    with tempfile.TemporaryDirectory() as d:
+        c, exe = os.path.join(d, "s.c"), os.path.join(d, "s")
+        open(c, "w").write(src)
+        subprocess.run(["gcc", "-I", os.path.dirname(HEADER), c, "-o", exe], check=True)
+        sizes = [int(x) for x in subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()]
+    b = r2.binding
+    assert sizes == [C.sizeof(b._SimDesc), C.sizeof(b._SplitDesc), C.sizeof(b._RecursiveDesc), C.sizeof(b._Level),
+                     C.sizeof(b._Epoch)]
+
+
 def test_strerror(r2):
     assert r2.r2_strerror(0) == "success"
     for code in (-1, -2, -3, -4, -5):
