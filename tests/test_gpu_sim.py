@@ -297,6 +297,46 @@ def test_sim_random_configurations(r2, oracle, seed):
         _full_compare_small(r2, oracle, w, window=window, check_stage=one_pass or len(eps) == 1, schedule=schedule)
 
 
+def test_sim_random_mid_sizes(r2, oracle):
+    """Random configurations of 0.25 to 17 MiB per rank -- the sizes where the library's own choice flips
+    between fused columns and one launch per step -- with random channel schedules, pass windows and
+    schedules: the buffers against the definition, the offsets log against the oracle's partition."""
+    rng = np.random.default_rng(9100)
+    n_fused = 0
+    for case in range(14):
+        R, S, C = int(rng.integers(2, 17)), int(rng.integers(1, 9)), int(rng.integers(1, 17))
+        dtype = "f32" if rng.random() < 0.5 else "bf16"
+        es = 4 if dtype == "f32" else 2
+        phases = ("ar", "rs", "ag")[int(rng.integers(0, 3))]
+        mib = float(rng.choice([0.25, 1, 3, 8, 17]))
+        E = max(1, int(mib * (1 << 20) / es / (S * R)))
+        if rng.random() < 0.7:
+            E = max(8, E // 8 * 8)  # mostly whole 16-byte vectors
+        n_tx = S * ((2 * R - 2) if phases == "ar" else (R - 1))
+        epochs = [(0, int(rng.integers(0, (1 << C) - 1)), tuple(int(x) for x in rng.integers(1, 100000, C)))]
+        for t in sorted(set(int(x) for x in rng.integers(1, n_tx + 1, int(rng.integers(0, 5))))):
+            epochs.append((t, int(rng.integers(0, (1 << C) - 1)), tuple(int(x) for x in rng.integers(1, 100000, C))))
+        window = int(rng.choice([0, 0, 0, 1 << 20, 7 << 20]))
+        schedule = int(rng.choice([0, 0, 1, 2]))
+        if schedule == 2 and (E * es) % 16:
+            schedule = 0
+        w = wl.Workload(f"mid{case}", R, dtype, E * S * R, S, C, (16, 256)[int(rng.integers(0, 2))], phases, 1.0,
+                        2000 + case, tuple(epochs))
+        say(f"mid-size {case}: R={R} S={S} C={C} {dtype} {phases} {w.N * es / 2 ** 20:.2f} MiB/rank window={window} "
+            f"schedule={schedule} epochs={[(e[0], e[1]) for e in epochs]}")
+        xs = wl.make_inputs(w)
+        outs, log, ws, desc = run_gpu_sim(r2, w, xs, window=window, schedule=schedule)
+        n_fused += r2.r2_sim_resolve_schedule(desc, list(w.epochs)) == r2.SCHED_FUSED
+        dt, ph, odt, oph = codes(r2, oracle, w)
+        want = oracle.expected(xs, odt, S, oph)
+        for r in range(R):
+            assert outs[r].tobytes() == want[r].tobytes(), f"case {case} rank {r}"
+        assert log.tolist() == expected_log(oracle, w).tolist(), f"case {case}: offsets log"
+        del ws, outs, xs, want
+        torch.cuda.empty_cache()
+    assert 2 <= n_fused <= 12  # both schedules were exercised
+
+
 def test_sim_result_independent_of_schedule(r2, oracle):
     """Lossless whatever the failure timing: different schedules, same bits."""
     from dataclasses import replace
