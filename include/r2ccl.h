@@ -238,19 +238,22 @@ typedef struct {
 
 /* Pure host arithmetic on a descriptor (0 if the descriptor is invalid). */
 uint32_t r2_sim_num_steps(const r2_sim_desc *desc);         /* J                                  */
-uint64_t r2_sim_num_transmissions(const r2_sim_desc *desc); /* S * (J-1) = rows of the tables     */
+uint64_t r2_sim_num_transmissions(const r2_sim_desc *desc); /* rows of the tables: S * (J-1), with S
+                                                               the internal slabs ((R-1) * n_slabs for
+                                                               all-to-all); R with R2_PHASE_LINKS     */
 uint64_t r2_sim_workspace_bytes(const r2_sim_desc *desc);
 uint64_t r2_sim_stage_offset(const r2_sim_desc *desc);      /* byte offset of the stage area      */
 uint64_t r2_sim_stage_capacity(const r2_sim_desc *desc);    /* bytes per channel buffer           */
 
 /* Workspace (device, 256-byte aligned, >= r2_sim_workspace_bytes) layout:
- *   [0, ...)                 offsets tables  uint64 [S*(J-1)][C+1], row t = transmission t
+ *   [0, ...)                 offsets tables  uint64 [r2_sim_num_transmissions][C+1], row t = transmission t
+ *                            (with R2_PHASE_LINKS: row r = the link r -> r+1)
  *   [r2_sim_stage_offset)    stage buffers   [2 parities][R][S][C][r2_sim_stage_capacity bytes];
  *                            the transmission of step j uses parity j & 1
  * Stage memory is never initialised or cleared by the library. */
 
 /* Partition every transmission of the run: fills the tables (and, if not NULL, the device array
- * offsets_log [S*(J-1)][C+1]) from the epoch list.  Epoch data travels as kernel arguments, so no
+ * offsets_log [r2_sim_num_transmissions][C+1]) from the epoch list.  Epoch data travels as kernel arguments, so no
  * host-to-device copy is made.  Returns R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if a state
  * that is in force for some transmission has no healthy channel. */
 int r2_sim_prepare(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs,
