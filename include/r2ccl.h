@@ -255,7 +255,8 @@ uint64_t r2_sim_stage_capacity(const r2_sim_desc *desc);    /* bytes per channel
 /* Partition every transmission of the run: fills the tables (and, if not NULL, the device array
  * offsets_log [r2_sim_num_transmissions][C+1]) from the epoch list.  Epoch data travels as kernel arguments, so no
  * host-to-device copy is made.  Returns R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if a state
- * that is in force for some transmission has no healthy channel. */
+ * that is in force for some transmission has no healthy channel.  Not for R2_PHASE_LINKS, whose
+ * tables r2_ring_rails_sim makes. */
 int r2_sim_prepare(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs,
                    void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log, void *stream);
 

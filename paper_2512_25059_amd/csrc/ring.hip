@@ -408,6 +408,7 @@ extern "C" int r2_sim_prepare(const r2_sim_desc *desc, const r2_epoch *epochs, u
     SimShape s;
     int rc = shape_of(desc, s);
     if (rc) return rc;
+    if (s.links) return R2_ERR_INVALID;  // per-link tables are made by r2_ring_rails_sim
     if ((rc = check_epochs(epochs, n_epochs, s))) return rc;
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
     if (s.n_tx == 0) return R2_OK;

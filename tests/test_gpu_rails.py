@@ -136,6 +136,8 @@ def test_rails_argument_errors(r2):
         r2.r2_ring_rails_sim(plain, bufs, w, [0] * 4, ws)
     with pytest.raises(r2.R2Error):  # per-link tables do not come from epochs
         r2.r2_ring_allreduce_sim(desc, bufs, [(0, 0, w)], ws)
+    with pytest.raises(r2.R2Error):
+        r2.r2_sim_prepare(desc, [(0, 0, w)], ws)
     with pytest.raises(r2.R2Error):  # too small a workspace
         r2.r2_ring_rails_sim(desc, bufs, w, [0] * 4, ws[:256])
     for bad in (r2.PHASE_LINKS, r2.PHASE_LINKS | r2.PHASE_SENDRECV, r2.PHASE_LINKS | r2.PHASE_BROADCAST):
