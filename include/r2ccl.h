@@ -225,8 +225,10 @@ typedef struct {
     int32_t dtype;       /* r2_dtype                                                             */
     int32_t phases;      /* R2_PHASE_RS, R2_PHASE_AG, both, or one of the other R2_PHASE_*       */
     uint64_t stage_window_bytes; /* stage bytes one launch may write, summed over ranks; 0 = the
-                                    library's default (128 MiB, half the Infinity Cache).  Only
-                                    changes how the run is cut into passes, never the result.   */
+                                    library's default (128 MiB, half the Infinity Cache; 256 MiB
+                                    for the two-step exchanges, which use one stage parity).
+                                    Only changes how the run is cut into passes, never the
+                                    result.                                                    */
     int32_t schedule;    /* R2_SCHED_STEPS: one launch per fused step and pass.
                             R2_SCHED_FUSED: one launch takes every column (1 or 2 KiB of each ring chunk)
                             through all steps between two channel-state changes; needs chunks that

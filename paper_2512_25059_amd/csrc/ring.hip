@@ -206,7 +206,10 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     if (stage > ((unsigned __int128)1 << 62)) return R2_ERR_OVERFLOW;
     s.total_bytes = s.stage_off + (uint64_t)stage;
 
-    const uint64_t window = d->stage_window_bytes ? d->stage_window_bytes : kDefaultStageWindow;
+    // The two-step exchanges use one stage parity only, so twice as much fits the same cache footprint.
+    const uint64_t window = d->stage_window_bytes ? d->stage_window_bytes
+                            : s.two_lists()       ? 2 * kDefaultStageWindow
+                                                  : kDefaultStageWindow;
     const uint64_t per_slab = (uint64_t)s.active() * s.chunk_bytes;  // stage bytes a step writes per slab
     if (per_slab > window) {
         const uint64_t tile_bytes = (uint64_t)kThreads * kUnroll * 16;
