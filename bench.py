@@ -325,6 +325,38 @@ def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
           file=out, flush=True)
 
 
+def allreduce_size_sweep(r2, torch, np, wl, out=sys.stderr):
+    """Message-size sweep of the whole all-reduce in the manner of the paper's microbenchmarks (Sec. 8,
+    "AllReduce performance": a sweep over message sizes, without and with failures): 8 ranks, bf16,
+    8 channels, 8 KiB ... 128 MiB per rank; no channel down, one down, two down from the start.  The
+    schedule is the library's choice.  Rates are algorithmic bytes over time; those of fused runs are
+    served by cache ("effective").  A failure must not change the time: the same bytes move, cut
+    differently."""
+    R, C = 8, 8
+    weights = [50000] * C
+    print("all-reduce size sweep (8 ranks, bf16): us per op with 0 / 1 / 2 channels down", file=out)
+    print(f"{'bytes/rank':>12s} {'schedule':>8s} {'none down':>11s} {'ch 2 down':>11s} {'ch 2,5 down':>12s} {'GB/s (none)':>12s}", file=out)
+    g = torch.Generator(device="cpu").manual_seed(7)
+    size = 8 << 10
+    while size <= 128 << 20:
+        N = size // 2
+        bufs = [torch.randn(N, generator=g).mul_(0.02).to(torch.bfloat16).cuda() for _ in range(R)]
+        desc = r2.SimDesc(R, 1, C, 256, N, r2.BF16, r2.PHASE_AR)
+        ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+        times = []
+        for mask in (0, 0b00000100, 0b00100100):
+            call = r2.SimCall(desc, bufs, [(0, mask, weights)], ws)
+            n = 2000 if size <= (4 << 20) else 50
+            times.append(_time_calls(torch, call.run, n=n, warm=5))
+        fused = r2.r2_sim_resolve_schedule(desc, [(0, 0, weights)]) == r2.SCHED_FUSED
+        alg = (7 * R - 6) * N * 2
+        print(f"{size:12d} {'fused' if fused else 'steps':>8s} {times[0] * 1e6:11.1f} {times[1] * 1e6:11.1f} {times[2] * 1e6:12.1f} "
+              f"{alg / times[0] / 1e9:12.1f}", file=out, flush=True)
+        del ws, bufs
+        torch.cuda.empty_cache()
+        size *= 4
+
+
 def recursive_line(r2, torch, np, wl, out=sys.stderr):
     """Recursive R2CCL-AllReduce (Sec. 6) on the cfg2 shape: rank 0 has lost four of eight NICs, rank 3
     two, rank 5 one; shares from the planner."""
@@ -368,7 +400,8 @@ def main() -> int:
     ap.add_argument("--stage-window-mib", type=float, default=0.0,
                     help="stage bytes one launch may write (0 = library default)")
     ap.add_argument("--all", action="store_true", help="also print a table of every configuration to stderr")
-    ap.add_argument("--sweep", action="store_true", help="also print a size sweep of r2_reduce_copy to stderr")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also print size sweeps to stderr: r2_reduce_copy, and the whole all-reduce without and with failures")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -504,6 +537,7 @@ def main() -> int:
         other_collectives_lines(r2, torch, np, wl)
     if args.sweep:
         reduce_copy_sweep(r2, torch)
+        allreduce_size_sweep(r2, torch, np, wl)
     return 0
 
 
