@@ -309,7 +309,7 @@ def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
         elif phases == r2.PHASE_ALLTOALL:
             s = _time_calls(torch, lambda: r2.r2_alltoall_sim(desc, bufs, recv, epochs, ws))
         else:
-            s = _time_calls(torch, lambda: r2.r2_ring_allreduce_sim(desc, bufs, epochs, ws))
+            s = _time_calls(torch, lambda: r2.r2_collective_sim(desc, bufs, epochs, ws))
         alg = units * e
         print(f"{name:14s} cfg2 shape, channel 2 down: {s * 1e6:10.1f} us/op  {alg / s / 1e9:9.1f} GB/s  "
               f"{100 * alg / s / 1e9 / HBM_PEAK_GBPS:6.2f} % of HBM peak ({alg} algorithmic bytes)", file=out, flush=True)

@@ -296,6 +296,13 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           void *workspace, uint64_t workspace_bytes,
                           uint64_t *offsets_log, void *stream);
 
+/* The same call under the name that fits the phases which are no all-reduce (R2_PHASE_BROADCAST,
+ * R2_PHASE_REDUCE, a reduce-scatter or an all-gather alone): identical arguments and behaviour. */
+int r2_collective_sim(const r2_sim_desc *desc, void *const *rank_bufs,
+                      const r2_epoch *epochs, uint32_t n_epochs,
+                      void *workspace, uint64_t workspace_bytes,
+                      uint64_t *offsets_log, void *stream);
+
 /* Point-to-point under R2CCL-Balance (Sec. 5.1; measured in Sec. 8 "More results on other
  * collectives" and Appendix E): desc->phases must be R2_PHASE_SENDRECV.  Rank r's send buffer
  * (n_elems elements) goes, chunk by chunk through the partitioned stage buffers, into rank r+1's

@@ -202,6 +202,8 @@ def load_library():
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_sendrecv_sim.restype = i32
     lib.r2_sendrecv_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
+    lib.r2_collective_sim.restype = i32
+    lib.r2_collective_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_ring_rails_sim.restype = i32
     lib.r2_ring_rails_sim.argtypes = [pd, vp, vp, vp, vp, u64, vp, vp]
     lib.r2_alltoall_sim.restype = i32
@@ -539,6 +541,18 @@ def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
                                               wp, wb, _ptr(offsets_log), _stream(stream))
     del arr, keep
     _check(rc, "r2_ring_allreduce_sim")
+
+
+def r2_collective_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
+                      offsets_log: Optional[torch.Tensor] = None, stream=None,
+                      workspace_bytes: Optional[int] = None) -> None:
+    arr, p = _ptr_array(rank_bufs)
+    ep, keep = _epoch_array(epochs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_collective_sim(C.byref(desc.c()), p, C.cast(ep, C.c_void_p), len(epochs),
+                                          wp, wb, _ptr(offsets_log), _stream(stream))
+    del arr, keep
+    _check(rc, "r2_collective_sim")
 
 
 def r2_sendrecv_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epochs, workspace,

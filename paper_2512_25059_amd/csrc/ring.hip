@@ -662,6 +662,13 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
     return R2_OK;
 }
 
+extern "C" int r2_collective_sim(const r2_sim_desc *desc, void *const *rank_bufs, const r2_epoch *epochs,
+                                 uint32_t n_epochs, void *workspace, uint64_t workspace_bytes,
+                                 uint64_t *offsets_log, void *stream)
+{
+    return r2_ring_allreduce_sim(desc, rank_bufs, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream);
+}
+
 extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs, const uint32_t *weights,
                                  const uint64_t *fail_masks, void *workspace, uint64_t workspace_bytes,
                                  uint64_t *offsets_log, void *stream)

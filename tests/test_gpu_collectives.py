@@ -47,7 +47,7 @@ def _run_chain(r2, oracle, kind, xs, dtype, root, S, C, align, epochs, window=0,
     ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
     log = torch.full((S * (R - 1), C + 1), -1, dtype=torch.int64, device="cuda")
     bufs = [_dev(x) for x in xs]
-    r2.r2_ring_allreduce_sim(desc, bufs, epochs, ws, log)
+    r2.r2_collective_sim(desc, bufs, epochs, ws, log)
     torch.cuda.synchronize()
     o_bufs = [x.copy() for x in xs]
     if kind == "broadcast":
