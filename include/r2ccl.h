@@ -56,8 +56,8 @@ enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2, /* both = all-reduce */
        R2_PHASE_BROADCAST = 8,  /* ring broadcast from desc->root       */
        R2_PHASE_REDUCE = 16,    /* ring reduce to desc->root            */
        R2_PHASE_ALLTOALL = 32,  /* pairwise exchange of R blocks        */
-       /* a flag for the ring phases (RS, AG or both): one table per ring link instead of one per
-          transmission; see r2_ring_rails_sim */
+       /* a flag for the ring phases (RS, AG or both): every ring link has tables of its own instead of
+          one table per transmission for all ranks; see r2_ring_rails_sim */
        R2_PHASE_LINKS = 64 };
 enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2 };
 
@@ -242,14 +242,15 @@ typedef struct {
 uint32_t r2_sim_num_steps(const r2_sim_desc *desc);         /* J                                  */
 uint64_t r2_sim_num_transmissions(const r2_sim_desc *desc); /* rows of the tables: S * (J-1), with S
                                                                the internal slabs ((R-1) * n_slabs for
-                                                               all-to-all); R with R2_PHASE_LINKS     */
+                                                               all-to-all); R times that with
+                                                               R2_PHASE_LINKS (one block per link)    */
 uint64_t r2_sim_workspace_bytes(const r2_sim_desc *desc);
 uint64_t r2_sim_stage_offset(const r2_sim_desc *desc);      /* byte offset of the stage area      */
 uint64_t r2_sim_stage_capacity(const r2_sim_desc *desc);    /* bytes per channel buffer           */
 
 /* Workspace (device, 256-byte aligned, >= r2_sim_workspace_bytes) layout:
  *   [0, ...)                 offsets tables  uint64 [r2_sim_num_transmissions][C+1], row t = transmission t
- *                            (with R2_PHASE_LINKS: row r = the link r -> r+1)
+ *                            (with R2_PHASE_LINKS: R blocks of S*(J-1) rows, block r = the link r -> r+1)
  *   [r2_sim_stage_offset)    stage buffers   [2 parities][R][S][C][r2_sim_stage_capacity bytes];
  *                            the transmission of step j uses parity j & 1
  * Stage memory is never initialised or cleared by the library. */
@@ -313,21 +314,25 @@ int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void 
                     const r2_epoch *epochs, uint32_t n_epochs, void *workspace, uint64_t workspace_bytes,
                     uint64_t *offsets_log, void *stream);
 
-/* A ring whose servers have lost different NICs -- Sec. 6 "Topology-Aware Logical Re-ranking": when
- * node u loses rail r and its neighbour v loses rail r', what they share drops to the rails that
- * survive at both.  desc->phases must be R2_PHASE_LINKS plus the ring phases.  rank_bufs are given in
- * ring order (after any re-ranking, e.g. by r2_bridge_rerank); fail_masks[r] are the channels rank r
- * has lost.  The link r -> r+1 carries every transmission of rank r over the channels up at both
- * ends, cut in proportion to `weights` (fail mask of the link: fail_masks[r] | fail_masks[r+1]); rank
- * r+1 reads with that same table.  The tables area of the workspace then holds R rows, row r = the
- * link r -> r+1 (r2_sim_num_transmissions returns R), and offsets_log, if not NULL, receives them.
- * The result in the rank buffers is the ring's (all-reduce, reduce-scatter or all-gather), whatever
- * the masks.  weights, fail_masks: HOST arrays (n_channels, n_ranks).  Only the step schedule runs
- * it; R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if some link has no channel left -- which is
- * what re-ranking is for.  Asynchronous on `stream`; allocates nothing. */
-int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs, const uint32_t *weights,
-                      const uint64_t *fail_masks, void *workspace, uint64_t workspace_bytes,
-                      uint64_t *offsets_log, void *stream);
+/* A ring whose servers each have a channel state of their own -- Sec. 5.1 (R2CCL-Balance acts per
+ * server: server i spreads what it must send over its own healthy NICs) and Sec. 6 "Topology-Aware
+ * Logical Re-ranking" (when node u loses rail r and its neighbour v loses rail r', what they share drops
+ * to the rails that survive at both).  desc->phases must be R2_PHASE_LINKS plus the ring phases.
+ * rank_bufs are given in ring order (after any re-ranking, e.g. by r2_bridge_rerank).  Rank r has the
+ * epoch list rank_epochs[r] (n_rank_epochs[r] entries, the rules of r2_epoch lists, t = l*(J-1) + j as
+ * for the plain ring): which of its channels are down from which transmission on, and how fast each
+ * is.  The link r -> r+1 carries transmission t of rank r over the channels that are up at both ends at
+ * t, cut in proportion to the slower end's weight per channel; rank r+1 reads with that same table.
+ * The tables area of the workspace then holds R blocks of S*(J-1) rows, block r = the link r -> r+1
+ * (r2_sim_num_transmissions returns R*S*(J-1)), and offsets_log, if not NULL, receives the same.  The
+ * result in the rank buffers is the ring's (all-reduce, reduce-scatter or all-gather), whatever the
+ * schedules.  rank_epochs, n_rank_epochs and the weights they point to: HOST memory, read during the
+ * call only.  Only the step schedule runs it; R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if a link
+ * is left without a channel at some transmission -- which is what re-ranking is for.  Asynchronous on
+ * `stream`; allocates no device memory. */
+int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs,
+                      const r2_epoch *const *rank_epochs, const uint32_t *n_rank_epochs,
+                      void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log, void *stream);
 
 /* All-to-All under R2CCL-Balance (Sec. 5, table of strategies: point-to-point incl. All-to-All;
  * Sec. 5.1): desc->phases must be R2_PHASE_ALLTOALL.  Afterwards block q of recv_bufs[r] equals

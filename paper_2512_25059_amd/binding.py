@@ -568,19 +568,28 @@ def r2_sendrecv_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epo
     _check(rc, "r2_sendrecv_sim")
 
 
-def r2_ring_rails_sim(desc: SimDesc, rank_bufs: Sequence, weights: Sequence[int], fail_masks: Sequence[int],
-                      workspace, offsets_log: Optional[torch.Tensor] = None, stream=None,
+def r2_ring_rails_sim(desc: SimDesc, rank_bufs: Sequence, rank_epochs: Sequence, workspace,
+                      offsets_log: Optional[torch.Tensor] = None, stream=None,
                       workspace_bytes: Optional[int] = None) -> None:
-    if len(weights) != desc.n_channels or len(fail_masks) != desc.n_ranks or len(rank_bufs) != desc.n_ranks:
-        raise ValueError("r2_ring_rails_sim: one weight per channel, one mask and one buffer per rank")
+    """rank_epochs[r]: the epoch list [(t_start, fail_mask, weights), ...] of rank r."""
+    if len(rank_epochs) != desc.n_ranks or len(rank_bufs) != desc.n_ranks:
+        raise ValueError("r2_ring_rails_sim: one epoch list and one buffer per rank")
+    if any(len(w) != desc.n_channels for eps in rank_epochs for _, _, w in eps):
+        raise ValueError("r2_ring_rails_sim: one weight per channel in every epoch")
     arr, p = _ptr_array(rank_bufs)
-    w = (C.c_uint32 * len(weights))(*[int(x) for x in weights])
-    m = (C.c_uint64 * len(fail_masks))(*[int(x) for x in fail_masks])
+    lists = [_epoch_array(eps) for eps in rank_epochs]
+    ptrs = (C.c_void_p * len(lists))(*[C.cast(a, C.c_void_p) for a, _ in lists])
+    counts = (C.c_uint32 * len(lists))(*[len(eps) for eps in rank_epochs])
     wp, wb = _ws(workspace, workspace_bytes)
-    rc = load_library().r2_ring_rails_sim(C.byref(desc.c()), p, C.cast(w, C.c_void_p), C.cast(m, C.c_void_p),
+    rc = load_library().r2_ring_rails_sim(C.byref(desc.c()), p, C.cast(ptrs, C.c_void_p), C.cast(counts, C.c_void_p),
                                           wp, wb, _ptr(offsets_log), _stream(stream))
-    del arr
+    del arr, lists
     _check(rc, "r2_ring_rails_sim")
+
+
+def static_rails(weights: Sequence[int], fail_masks: Sequence[int]) -> List[list]:
+    """Epoch lists for ranks whose channel state does not change during the run."""
+    return [[(0, int(m), list(weights))] for m in fail_masks]
 
 
 def r2_alltoall_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epochs, workspace,

@@ -6,6 +6,8 @@
 // (per-NIC send staging buffers, chunk-granular progress), Sec. 5.2 (ring all-reduce = reduce-scatter,
 // then all-gather), Sec. 5 and 5.1 (the other collectives keep their schedule under R2CCL-Balance),
 // Sec. 6 (servers that lost different rails).
+#include <vector>
+
 #include "reduce_copy_device.h"
 #include "ring_fused_device.h"
 
@@ -42,7 +44,7 @@ struct StepArgs {
     uint32_t per_slab;     // ring chunks per slab: R, or 1 where a slab is one message chunk
     uint32_t rank_base;    // the first rank this launch covers (chains: the one rank active at this step)
     uint32_t a2a_chunks;   // all-to-all: message chunks per block (a slab is chunk l % this of round l / this + 1), else 0
-    uint32_t link_tables;  // 1: row r of `tables` is the link r -> r+1, for every transmission of rank r
+    uint64_t link_rows;    // > 0: `tables` holds a block of this many rows per ring link; rank r writes with block r
     uint32_t slab_begin, slab_count;  // the slabs this launch covers
     uint64_t lo, hi;                  // and the byte range of every ring chunk it moves
 };
@@ -76,8 +78,8 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
     job.bytes = a.chunk_bytes;
     job.lo = a.lo;
     job.hi = a.hi;
-    job.in_off = M != kSend ? a.tables + (a.link_tables ? peer : t_out - 1) * row : nullptr;
-    job.out_off = HAS_OUT ? a.tables + (a.link_tables ? r : t_out) * row : nullptr;
+    job.in_off = M != kSend ? a.tables + (peer * a.link_rows + t_out - 1) * row : nullptr;
+    job.out_off = HAS_OUT ? a.tables + (r * a.link_rows + t_out) * row : nullptr;
     job.cap = a.cap;
     job.C = a.C;
     // stage buffer of (parity, rank, slab, channel)
@@ -148,7 +150,8 @@ struct SimShape {
     // rank active per step, the point-to-point kinds two steps and separate receive buffers.
     enum Kind { kRing, kSendRecv, kBroadcast, kReduce, kAllToAll } kind;
     uint32_t root;        // chains
-    bool links;           // ring with one table per link (row r: r -> r+1) instead of one per transmission
+    bool links;           // ring whose links have tables of their own (block r: r -> r+1), one row per transmission
+    uint64_t tx_per_link; // transmissions of one rank: S * T_slab
     uint32_t a2a_chunks;  // all-to-all: the caller's chunks per block (S = (R-1) * a2a_chunks)
     bool two_lists() const { return kind == kSendRecv || kind == kAllToAll; }
     bool chain() const { return kind == kBroadcast || kind == kReduce; }
@@ -199,7 +202,8 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     s.T_slab = s.J - 1;
     s.chunk_bytes = d->n_elems / per * elem_bytes(d->dtype);
     s.cap = round_up(s.chunk_bytes ? s.chunk_bytes : 1, 256);
-    s.n_tx = s.links ? s.R : (uint64_t)s.S * s.T_slab;  // rows of the tables
+    s.tx_per_link = (uint64_t)s.S * s.T_slab;
+    s.n_tx = s.links ? s.R * s.tx_per_link : s.tx_per_link;  // rows of the tables
     s.tables_bytes = round_up(s.n_tx * (s.C + 1) * 8, 256);
     s.stage_off = s.tables_bytes;
     const unsigned __int128 stage = (unsigned __int128)2 * s.R * s.S * s.C * s.cap;
@@ -453,7 +457,7 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     a.chunk_start = ring_phases == R2_PHASE_AG ? 1 : 0;
     a.per_slab = s.kind == SimShape::kRing ? s.R : 1;
     a.a2a_chunks = s.a2a_chunks;
-    a.link_tables = s.links;
+    a.link_rows = s.links ? s.tx_per_link : 0;
     // a chain has one rank at work per step: the step-th after the root, or after the root's successor
     a.rank_base = s.kind == SimShape::kBroadcast ? (s.root + step) % s.R
                   : s.kind == SimShape::kReduce  ? (s.root + 1 + step) % s.R
@@ -669,29 +673,57 @@ extern "C" int r2_collective_sim(const r2_sim_desc *desc, void *const *rank_bufs
     return r2_ring_allreduce_sim(desc, rank_bufs, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream);
 }
 
-extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs, const uint32_t *weights,
-                                 const uint64_t *fail_masks, void *workspace, uint64_t workspace_bytes,
-                                 uint64_t *offsets_log, void *stream)
+extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs,
+                                 const r2_epoch *const *rank_epochs, const uint32_t *n_rank_epochs,
+                                 void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log, void *stream)
 {
     SimShape s;
     int rc = shape_of(desc, s);
     if (rc) return rc;
-    if (!s.links || !rank_bufs || !weights || !fail_masks) return R2_ERR_INVALID;
+    if (!s.links || !rank_bufs || !rank_epochs || !n_rank_epochs) return R2_ERR_INVALID;
     for (uint32_t r = 0; r < s.R; ++r) {
         const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
         if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
+        const r2_epoch *e = rank_epochs[r];
+        const uint32_t n = n_rank_epochs[r];
+        if (!e || n == 0 || e[0].t_start != 0) return R2_ERR_INVALID;
+        for (uint32_t i = 0; i < n; ++i)
+            if (!e[i].weights || (i && e[i].t_start <= e[i - 1].t_start)) return R2_ERR_INVALID;
     }
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
-    // One table per link, cut by the channels that are up at both of its ends.
+
+    // The schedule of the link r -> r+1: it changes whenever either end's does; a channel is down if
+    // either end has it down, and as fast as the slower end.
     const uint64_t full = s.C == 64 ? ~0ull : ((1ull << s.C) - 1);
-    r2_epoch links[R2_MAX_RANKS];
+    std::vector<std::vector<r2_epoch>> link(s.R);
+    std::vector<std::vector<uint32_t>> speed(s.R);
     for (uint32_t r = 0; r < s.R; ++r) {
-        links[r] = r2_epoch{r, (fail_masks[r] | fail_masks[(r + 1) % s.R]) & full, weights};
-        if (!any_healthy(weights, links[r].fail_mask, s.C)) return R2_ERR_NO_HEALTHY_CHANNEL;
+        const r2_epoch *a = rank_epochs[r], *b = rank_epochs[(r + 1) % s.R];
+        const uint32_t na = n_rank_epochs[r], nb = n_rank_epochs[(r + 1) % s.R];
+        speed[r].resize((size_t)(na + nb) * s.C);  // never grows again: the epochs point into it
+        uint32_t ia = 0, ib = 0;
+        for (;;) {
+            const uint64_t t = a[ia].t_start > b[ib].t_start ? a[ia].t_start : b[ib].t_start;
+            uint32_t *w = speed[r].data() + link[r].size() * s.C;
+            for (uint32_t c = 0; c < s.C; ++c) w[c] = a[ia].weights[c] < b[ib].weights[c] ? a[ia].weights[c] : b[ib].weights[c];
+            link[r].push_back(r2_epoch{t, (a[ia].fail_mask | b[ib].fail_mask) & full, w});
+            if (t < s.tx_per_link && !any_healthy(w, link[r].back().fail_mask, s.C)) return R2_ERR_NO_HEALTHY_CHANNEL;
+            // the next change at either end
+            const uint64_t next_a = ia + 1 < na ? a[ia + 1].t_start : ~0ull;
+            const uint64_t next_b = ib + 1 < nb ? b[ib + 1].t_start : ~0ull;
+            if (next_a == ~0ull && next_b == ~0ull) break;
+            if (next_a <= next_b) ++ia;
+            if (next_b <= next_a) ++ib;
+        }
     }
-    if ((rc = launch_partition_epochs(links, s.R, s.C, desc->align, s.chunk_bytes, s.R,
-                                      static_cast<uint64_t *>(workspace), offsets_log, (hipStream_t)stream)))
-        return rc;
+    uint64_t *tables = static_cast<uint64_t *>(workspace);
+    for (uint32_t r = 0; r < s.R && s.tx_per_link; ++r) {
+        const uint64_t at = r * s.tx_per_link * (s.C + 1);
+        if ((rc = launch_partition_epochs(link[r].data(), (uint32_t)link[r].size(), s.C, desc->align, s.chunk_bytes,
+                                          s.tx_per_link, tables + at, offsets_log ? offsets_log + at : nullptr,
+                                          (hipStream_t)stream)))
+            return rc;
+    }
     if (s.chunk_bytes == 0) return R2_OK;
     for (uint64_t p = 0; p < s.n_passes; ++p)
         for (uint32_t j = 0; j < s.J; ++j)

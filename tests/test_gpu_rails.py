@@ -31,29 +31,33 @@ def _inputs(rng, R, N, dtype):
     return [rng.standard_normal(N).astype(np.float32) for _ in range(R)]
 
 
-def _run(r2, oracle, xs, dtype, phases, S, C, align, weights, masks, window=0, check_stage=True):
+def _run(r2, oracle, xs, dtype, phases, S, C, align, weights, masks, window=0, check_stage=True, schedules=None):
+    """``schedules``: per-rank epoch lists; by default the static state (weights, masks[r]) of every rank."""
     R, N = len(xs), xs[0].size
+    if schedules is None:
+        schedules = rails.static_epochs(weights, masks)
     gdt = r2.F32 if dtype == "f32" else r2.BF16
     odt = oracle.F32 if dtype == "f32" else oracle.BF16
     gph = {"rs": r2.PHASE_RS, "ag": r2.PHASE_AG, "ar": r2.PHASE_AR}[phases] | r2.PHASE_LINKS
     oph = {"rs": oracle.PHASE_RS, "ag": oracle.PHASE_AG, "ar": oracle.PHASE_AR}[phases]
     desc = r2.SimDesc(R, S, C, align, N, gdt, gph, window, 0)
-    assert r2.r2_sim_num_transmissions(desc) == R  # one table per link
-    assert r2.r2_sim_resolve_schedule(desc, [(0, 0, weights)]) == r2.SCHED_STEPS
+    n_tx = S * ((2 * R - 2) if phases == "ar" else (R - 1))
+    assert r2.r2_sim_num_transmissions(desc) == R * n_tx  # a block of tables per link
+    assert r2.r2_sim_resolve_schedule(desc, [(0, 0, [1] * C)]) == r2.SCHED_STEPS
     ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
-    log = torch.full((R, C + 1), -1, dtype=torch.int64, device="cuda")
+    log = torch.full((R, n_tx, C + 1), -1, dtype=torch.int64, device="cuda")
     bufs = [_dev(x) for x in xs]
-    r2.r2_ring_rails_sim(desc, bufs, weights, masks, ws, log)
+    r2.r2_ring_rails_sim(desc, bufs, schedules, ws, log)
     torch.cuda.synchronize()
     o_bufs = [x.copy() for x in xs]
-    tables, stage = rails.ring_rails_sim(o_bufs, odt, S, C, align, weights, masks, oph, FILL)
+    tables, stage = rails.ring_rails_sim(o_bufs, odt, S, C, align, schedules, oph, FILL)
     want = oracle.expected(xs, odt, S, oph)
     for r in range(R):
         got = bufs[r].cpu().numpy().view(xs[r].dtype)
         assert got.tobytes() == want[r].tobytes(), f"rank {r} vs definition"
         assert got.tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
     assert log.cpu().numpy().view(np.uint64).tolist() == tables.tolist()
-    assert ws[:R * (C + 1) * 8].cpu().numpy().view(np.uint64).reshape(R, C + 1).tolist() == tables.tolist()
+    assert ws[:R * n_tx * (C + 1) * 8].cpu().numpy().view(np.uint64).reshape(R, n_tx, C + 1).tolist() == tables.tolist()
     if check_stage:
         cap = r2.r2_sim_stage_capacity(desc)
         off = r2.r2_sim_stage_offset(desc)
@@ -86,8 +90,20 @@ def test_rails_random_configurations(r2, oracle, seed):
         up = int(rng.integers(0, C))
         masks = [int(rng.integers(0, 1 << C)) & ~(1 << up) if rng.random() < 0.7 else 0 for _ in range(R)]
         window = (0, 1, 4096, 50000)[int(rng.integers(0, 4))]
-        say(f"rails random {seed}.{case} {phases} {dtype} R={R} S={S} C={C} E={E} align={align} window={window} masks={masks}")
-        _run(r2, oracle, _inputs(rng, R, S * R * E, dtype), dtype, phases, S, C, align, w, masks, window, True)
+        schedules = None
+        if case % 2:  # every rank's state also changes on the way: failures, recoveries, other speeds
+            n_tx = S * ((2 * R - 2) if phases == "ar" else (R - 1))
+            schedules = []
+            for r in range(R):
+                eps = [(0, masks[r], w)]
+                for t in sorted(set(int(x) for x in rng.integers(1, n_tx + 1, int(rng.integers(0, 3))))):
+                    eps.append((t, int(rng.integers(0, 1 << C)) & ~(1 << up), [int(x) for x in rng.integers(1, 1000, C)]))
+                schedules.append(eps)
+        say(f"rails random {seed}.{case} {phases} {dtype} R={R} S={S} C={C} E={E} align={align} window={window} masks={masks} "
+            f"changes={[len(e) - 1 for e in schedules] if schedules else 0}")
+        # with passes and tables that change on the way the stage area's leftovers depend on the pass order
+        _run(r2, oracle, _inputs(rng, R, S * R * E, dtype), dtype, phases, S, C, align, w, masks, window,
+             schedules is None or window == 0, schedules)
 
 
 def test_rails_maximum_ranks_and_channels_and_large_chunks(r2, oracle):
@@ -103,6 +119,17 @@ def test_rails_maximum_ranks_and_channels_and_large_chunks(r2, oracle):
     _run(r2, oracle, xs, "f32", "ar", 1, 8, 256, [50000] * 8, [0b1, 0b10, 0, 0b1100], window=3 << 20)
 
 
+def test_rails_failure_and_recovery_at_one_server(r2, oracle):
+    """Server 2 of 4 loses a NIC at transmission 3 and gets a faster one back at 6, with multi-tile chunks."""
+    rng = np.random.default_rng(922)
+    w = [50000] * 4
+    sched = [[(0, 0, w)] for _ in range(4)]
+    sched[2] = [(0, 0, w), (3, 0b0010, w), (6, 0, [50000, 100000, 50000, 50000])]
+    sched[3] = [(0, 0, w), (6, 0b1000, [50000, 100000, 50000, 50000])]
+    say("rails: failure and recovery at one server")
+    _run(r2, oracle, _inputs(rng, 4, 2 * 4 * 8 * 1500, "bf16"), "bf16", "ar", 2, 4, 256, w, None, 0, True, sched)
+
+
 def test_rerank_then_ring(r2, oracle):
     """Neighbours that lost different rails share nothing; the library's bridge re-ranking moves a healthy
     node between them and the ring over the new order runs."""
@@ -116,7 +143,7 @@ def test_rerank_then_ring(r2, oracle):
     bufs = [_dev(x) for x in xs]
     say("rails: a link without a channel is refused before any launch")
     with pytest.raises(r2.R2Error) as e:
-        r2.r2_ring_rails_sim(desc, bufs, w, masks, ws)
+        r2.r2_ring_rails_sim(desc, bufs, r2.static_rails(w, masks), ws)
     assert e.value.code == -2
     torch.cuda.synchronize()
     assert all(b.cpu().numpy().view(np.uint16).tobytes() == x.tobytes() for b, x in zip(bufs, xs))
@@ -133,13 +160,20 @@ def test_rails_argument_errors(r2):
     ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
     plain = r2.SimDesc(4, 1, 4, 16, 64, r2.F32, r2.PHASE_AR)
     with pytest.raises(r2.R2Error):  # the flag is missing
-        r2.r2_ring_rails_sim(plain, bufs, w, [0] * 4, ws)
+        r2.r2_ring_rails_sim(plain, bufs, r2.static_rails(w, [0] * 4), ws)
     with pytest.raises(r2.R2Error):  # per-link tables do not come from epochs
         r2.r2_ring_allreduce_sim(desc, bufs, [(0, 0, w)], ws)
     with pytest.raises(r2.R2Error):
         r2.r2_sim_prepare(desc, [(0, 0, w)], ws)
     with pytest.raises(r2.R2Error):  # too small a workspace
-        r2.r2_ring_rails_sim(desc, bufs, w, [0] * 4, ws[:256])
+        r2.r2_ring_rails_sim(desc, bufs, r2.static_rails(w, [0] * 4), ws[:256])
+    with pytest.raises(r2.R2Error):  # a rank's list does not start at transmission 0
+        r2.r2_ring_rails_sim(desc, bufs, [[(1, 0, w)]] + r2.static_rails(w, [0] * 3), ws)
+    with pytest.raises(r2.R2Error):  # ... or does not increase
+        r2.r2_ring_rails_sim(desc, bufs, [[(0, 0, w), (2, 1, w), (2, 0, w)]] + r2.static_rails(w, [0] * 3), ws)
+    with pytest.raises(r2.R2Error) as e:  # rank 1 loses, at transmission 4, the only channel rank 2 has left
+        r2.r2_ring_rails_sim(desc, bufs, [[(0, 0, w)], [(0, 0, w), (4, 0b0001, w)], [(0, 0b1110, w)], [(0, 0, w)]], ws)
+    assert e.value.code == -2
     for bad in (r2.PHASE_LINKS, r2.PHASE_LINKS | r2.PHASE_SENDRECV, r2.PHASE_LINKS | r2.PHASE_BROADCAST):
         assert r2.r2_sim_num_steps(r2.SimDesc(4, 1, 4, 16, 64, r2.F32, bad)) == 0
     assert r2.r2_sim_num_steps(r2.SimDesc(4, 1, 4, 16, 64, r2.F32, r2.PHASE_AR | r2.PHASE_LINKS, 0, r2.SCHED_FUSED)) == 0
