@@ -318,8 +318,8 @@ def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
     masks = [0b00000001, 0b00000010, 0, 0, 0b00000100, 0, 0, 0b00001000]
     desc = r2.SimDesc(R, 1, C, w.align, N, r2.BF16, r2.PHASE_AR | r2.PHASE_LINKS, 0, r2.SCHED_STEPS)
     ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
-    rails = r2.static_rails([50000] * C, masks)
-    s = _time_calls(torch, lambda: r2.r2_ring_rails_sim(desc, bufs, rails, ws))
+    call = r2.RailsCall(desc, bufs, r2.static_rails([50000] * C, masks), ws)  # arguments marshalled once
+    s = _time_calls(torch, call.run)
     alg = (7 * R - 6) * N * e
     print(f"{'all-reduce':14s} cfg2 shape, four ranks lost a rail each (per-link tables): {s * 1e6:10.1f} us/op  "
           f"{alg / s / 1e9:9.1f} GB/s  {100 * alg / s / 1e9 / HBM_PEAK_GBPS:6.2f} % of HBM peak ({alg} algorithmic bytes)",

@@ -587,6 +587,32 @@ def r2_ring_rails_sim(desc: SimDesc, rank_bufs: Sequence, rank_epochs: Sequence,
     _check(rc, "r2_ring_rails_sim")
 
 
+class RailsCall:
+    """The arguments of r2_ring_rails_sim marshalled once (see SimCall)."""
+
+    def __init__(self, desc: SimDesc, rank_bufs: Sequence, rank_epochs: Sequence, workspace,
+                 offsets_log: Optional[torch.Tensor] = None, stream=None, workspace_bytes: Optional[int] = None):
+        if len(rank_epochs) != desc.n_ranks or len(rank_bufs) != desc.n_ranks:
+            raise ValueError("RailsCall: one epoch list and one buffer per rank")
+        if any(len(w) != desc.n_channels for eps in rank_epochs for _, _, w in eps):
+            raise ValueError("RailsCall: one weight per channel in every epoch")
+        self._fn = load_library().r2_ring_rails_sim
+        self._desc = desc.c()
+        self._bufs, bufs_p = _ptr_array(rank_bufs)
+        self._lists = [_epoch_array(eps) for eps in rank_epochs]
+        self._ptrs = (C.c_void_p * len(self._lists))(*[C.cast(a, C.c_void_p) for a, _ in self._lists])
+        self._counts = (C.c_uint32 * len(self._lists))(*[len(eps) for eps in rank_epochs])
+        wp, wb = _ws(workspace, workspace_bytes)
+        self._refs = (rank_bufs, workspace, offsets_log)  # keep the device memory alive
+        self._args = (C.byref(self._desc), bufs_p, C.cast(self._ptrs, C.c_void_p), C.cast(self._counts, C.c_void_p),
+                      wp, wb, _ptr(offsets_log), _stream(stream))
+
+    def run(self) -> None:
+        rc = self._fn(*self._args)
+        if rc != R2_OK:
+            raise R2Error(rc, "r2_ring_rails_sim")
+
+
 def static_rails(weights: Sequence[int], fail_masks: Sequence[int]) -> List[list]:
     """Epoch lists for ranks whose channel state does not change during the run."""
     return [[(0, int(m), list(weights))] for m in fail_masks]

@@ -693,21 +693,27 @@ extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
 
     // The schedule of the link r -> r+1: it changes whenever either end's does; a channel is down if
-    // either end has it down, and as fast as the slower end.
+    // either end has it down, and as fast as the slower end.  The links' tables lie one block after
+    // the other, so their schedules are strung together on one axis (block r starts at row
+    // r * tx_per_link) and partitioned in one go.
     const uint64_t full = s.C == 64 ? ~0ull : ((1ull << s.C) - 1);
-    std::vector<std::vector<r2_epoch>> link(s.R);
-    std::vector<std::vector<uint32_t>> speed(s.R);
+    size_t n_all = 0;
+    for (uint32_t r = 0; r < s.R; ++r) n_all += (size_t)n_rank_epochs[r] + n_rank_epochs[(r + 1) % s.R];
+    std::vector<uint32_t> speed(n_all * s.C);  // never grows again: the epochs point into it
+    std::vector<r2_epoch> link;
+    link.reserve(n_all);
     for (uint32_t r = 0; r < s.R; ++r) {
         const r2_epoch *a = rank_epochs[r], *b = rank_epochs[(r + 1) % s.R];
         const uint32_t na = n_rank_epochs[r], nb = n_rank_epochs[(r + 1) % s.R];
-        speed[r].resize((size_t)(na + nb) * s.C);  // never grows again: the epochs point into it
         uint32_t ia = 0, ib = 0;
         for (;;) {
             const uint64_t t = a[ia].t_start > b[ib].t_start ? a[ia].t_start : b[ib].t_start;
-            uint32_t *w = speed[r].data() + link[r].size() * s.C;
+            if (t >= s.tx_per_link) break;  // never in force (and would run into the next link's block)
+            uint32_t *w = speed.data() + link.size() * s.C;
             for (uint32_t c = 0; c < s.C; ++c) w[c] = a[ia].weights[c] < b[ib].weights[c] ? a[ia].weights[c] : b[ib].weights[c];
-            link[r].push_back(r2_epoch{t, (a[ia].fail_mask | b[ib].fail_mask) & full, w});
-            if (t < s.tx_per_link && !any_healthy(w, link[r].back().fail_mask, s.C)) return R2_ERR_NO_HEALTHY_CHANNEL;
+            const uint64_t mask = (a[ia].fail_mask | b[ib].fail_mask) & full;
+            if (!any_healthy(w, mask, s.C)) return R2_ERR_NO_HEALTHY_CHANNEL;
+            link.push_back(r2_epoch{r * s.tx_per_link + t, mask, w});
             // the next change at either end
             const uint64_t next_a = ia + 1 < na ? a[ia + 1].t_start : ~0ull;
             const uint64_t next_b = ib + 1 < nb ? b[ib + 1].t_start : ~0ull;
@@ -716,14 +722,10 @@ extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs
             if (next_b <= next_a) ++ib;
         }
     }
-    uint64_t *tables = static_cast<uint64_t *>(workspace);
-    for (uint32_t r = 0; r < s.R && s.tx_per_link; ++r) {
-        const uint64_t at = r * s.tx_per_link * (s.C + 1);
-        if ((rc = launch_partition_epochs(link[r].data(), (uint32_t)link[r].size(), s.C, desc->align, s.chunk_bytes,
-                                          s.tx_per_link, tables + at, offsets_log ? offsets_log + at : nullptr,
-                                          (hipStream_t)stream)))
-            return rc;
-    }
+    if (s.n_tx && (rc = launch_partition_epochs(link.data(), (uint32_t)link.size(), s.C, desc->align, s.chunk_bytes,
+                                                s.n_tx, static_cast<uint64_t *>(workspace), offsets_log,
+                                                (hipStream_t)stream)))
+        return rc;
     if (s.chunk_bytes == 0) return R2_OK;
     for (uint64_t p = 0; p < s.n_passes; ++p)
         for (uint32_t j = 0; j < s.J; ++j)
