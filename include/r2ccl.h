@@ -338,7 +338,9 @@ int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs,
  * Sec. 5.1): desc->phases must be R2_PHASE_ALLTOALL.  Afterwards block q of recv_bufs[r] equals
  * block r of send_bufs[q] byte for byte, whatever the epochs (a block is n_elems/R elements).  Same
  * workspace, epochs, log and passes as r2_ring_allreduce_sim, which this calls with the two pointer
- * lists joined.  Send buffers are only read; no receive buffer may be a send buffer.  (Driven step
+ * lists joined (so r2_ring_allreduce_sim, r2_collective_sim and r2_sim_step read 2R pointers from
+ * rank_bufs for this phase, as for R2_PHASE_SENDRECV).  Send buffers are only read; no receive buffer
+ * may be a send buffer.  (Driven step
  * by step with r2_sim_step, only the exchanged blocks move: the own-block copy is part of this call.) */
 int r2_alltoall_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
                     const r2_epoch *epochs, uint32_t n_epochs, void *workspace, uint64_t workspace_bytes,

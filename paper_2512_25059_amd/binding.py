@@ -236,6 +236,18 @@ def _ptr_array(ts: Optional[Sequence]) -> Tuple[Optional[C.Array], Optional[int]
     return arr, C.cast(arr, C.c_void_p).value
 
 
+def _check_lists(desc: "SimDesc", rank_bufs: Sequence, epochs) -> None:
+    """The C side reads n_ranks pointers (2 * n_ranks for the two-list phases) and n_channels weights per
+    epoch: make sure they are there."""
+    if not (2 <= desc.n_ranks <= 64 and 1 <= desc.n_channels <= 64):
+        return  # the library rejects the descriptor before it reads any list
+    want = desc.n_ranks * (2 if desc.phases in (PHASE_SENDRECV, PHASE_ALLTOALL) else 1)
+    if len(rank_bufs) != want:
+        raise ValueError(f"expected {want} rank buffers, got {len(rank_bufs)}")
+    if any(len(w) != desc.n_channels for _, _, w in epochs):
+        raise ValueError("every epoch needs one weight per channel")
+
+
 def _epoch_array(epochs: Sequence[Tuple[int, int, Sequence[int]]]):
     keep = []
     arr = (_Epoch * max(len(epochs), 1))()
@@ -506,6 +518,7 @@ class SimCall:
     def __init__(self, desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
                  offsets_log: Optional[torch.Tensor] = None, stream=None,
                  workspace_bytes: Optional[int] = None):
+        _check_lists(desc, rank_bufs, epochs)
         self._fn = load_library().r2_ring_allreduce_sim
         self._desc = desc.c()
         self._bufs, bufs_p = _ptr_array(rank_bufs)
@@ -534,6 +547,7 @@ def r2_sim_fused_steps(desc: SimDesc, rank_bufs: Sequence, step_begin: int, step
 def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
                           offsets_log: Optional[torch.Tensor] = None, stream=None,
                           workspace_bytes: Optional[int] = None) -> None:
+    _check_lists(desc, rank_bufs, epochs)
     arr, p = _ptr_array(rank_bufs)
     ep, keep = _epoch_array(epochs)
     wp, wb = _ws(workspace, workspace_bytes)
@@ -546,6 +560,7 @@ def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
 def r2_collective_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
                       offsets_log: Optional[torch.Tensor] = None, stream=None,
                       workspace_bytes: Optional[int] = None) -> None:
+    _check_lists(desc, rank_bufs, epochs)
     arr, p = _ptr_array(rank_bufs)
     ep, keep = _epoch_array(epochs)
     wp, wb = _ws(workspace, workspace_bytes)

@@ -124,7 +124,8 @@ def test_invalid_descriptors(r2, bad):
     assert r2.r2_sim_num_steps(d) == 0
     assert r2.r2_sim_workspace_bytes(d) == 0
     with pytest.raises(r2.R2Error) as e:
-        r2.r2_ring_allreduce_sim(d, [256] * base["n_ranks"], [(0, 0, [1] * max(base["n_channels"], 1))],
+        lists = 2 if base["phases"] in (r2.PHASE_SENDRECV, r2.PHASE_ALLTOALL) else 1
+        r2.r2_ring_allreduce_sim(d, [256] * (lists * base["n_ranks"]), [(0, 0, [1] * max(base["n_channels"], 1))],
                                  4096, workspace_bytes=1 << 40)
     assert e.value.code == -1
 
@@ -158,6 +159,16 @@ def test_chain_and_alltoall_descriptor_arithmetic(r2):
     assert r2.r2_sim_stage_capacity(d) == 512  # 400 bytes per chunk
     assert r2.r2_sim_workspace_bytes(d) == r2.r2_sim_stage_offset(d) + 2 * 4 * 15 * 8 * 512
     assert r2.r2_sim_num_steps(r2.SimDesc(4, 5, 8, 256, 4 * 5 * 100 + 4, r2.F32, r2.PHASE_ALLTOALL)) == 0
+
+
+def test_binding_checks_list_lengths(r2):
+    """The C side reads as many pointers and weights as the descriptor says: the binding refuses shorter lists."""
+    d = r2.SimDesc(4, 1, 4, 256, 4096, r2.F32, r2.PHASE_ALLTOALL)
+    with pytest.raises(ValueError):
+        r2.r2_collective_sim(d, [256] * 4, [(0, 0, [1] * 4)], 4096, workspace_bytes=1 << 40)  # needs 2R pointers
+    with pytest.raises(ValueError):
+        r2.r2_ring_allreduce_sim(r2.SimDesc(4, 1, 4, 256, 4096, r2.F32, r2.PHASE_AR), [256] * 4, [(0, 0, [1] * 3)],
+                                 4096, workspace_bytes=1 << 40)  # three weights for four channels
 
 
 def test_sim_rejects_bad_epochs_and_buffers_before_any_device_work(r2):
