@@ -310,6 +310,9 @@ def r2_split_workspace_bytes(desc: SplitDesc) -> int:
 
 def r2_split_allreduce_sim(desc: SplitDesc, rank_bufs: Sequence, weights: Sequence[int], degraded_fail_mask: int,
                            workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    if 2 <= desc.n_ranks <= 64 and 1 <= desc.n_channels <= 64:  # else the library rejects it before reading
+        if len(rank_bufs) != desc.n_ranks or len(weights) != desc.n_channels:
+            raise ValueError("r2_split_allreduce_sim: one buffer per rank, one weight per channel")
     arr, p = _ptr_array(rank_bufs)
     w = (C.c_uint32 * max(len(weights), 1))(*[int(x) for x in weights])
     wp, wb = _ws(workspace, workspace_bytes)
@@ -378,6 +381,10 @@ def r2_recursive_workspace_bytes(desc: RecursiveDesc, levels: Sequence[Level], l
 def r2_recursive_allreduce_sim(desc: RecursiveDesc, rank_bufs: Sequence, weights: Sequence[int],
                                fail_masks: Sequence[int], levels: Sequence[Level], level_elems: Sequence[int],
                                workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    if 2 <= desc.n_ranks <= 64 and 1 <= desc.n_channels <= 64 and 1 <= desc.n_levels <= MAX_LEVELS:
+        if (len(rank_bufs) != desc.n_ranks or len(fail_masks) != desc.n_ranks or len(weights) != desc.n_channels
+                or len(levels) != desc.n_levels or len(level_elems) != desc.n_levels):
+            raise ValueError("r2_recursive_allreduce_sim: list lengths do not match the descriptor")
     keep, p = _ptr_array(rank_bufs)
     w, m, arr, e = _u32s(weights), _u64s(fail_masks), _levels(levels), _u64s(level_elems)
     wp, wb = _ws(workspace, workspace_bytes)
