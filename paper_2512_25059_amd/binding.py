@@ -430,6 +430,12 @@ def r2_reduce_copy(local: torch.Tensor, dtype: int, op: int,
                    stream=None, nbytes: Optional[int] = None) -> None:
     if nbytes is None:
         nbytes = local.numel() * local.element_size()
+    if 1 <= n_channels <= 64:  # else the library rejects the call before it reads the lists
+        for what, stage, table in (("in", in_stage, in_offsets), ("out", out_stage, out_offsets)):
+            if stage is not None and len(stage) != n_channels:
+                raise ValueError(f"r2_reduce_copy: {what}_stage needs one buffer per channel")
+            if hasattr(table, "numel") and table.numel() < n_channels + 1:
+                raise ValueError(f"r2_reduce_copy: {what}_offsets needs n_channels + 1 entries")
     in_arr, in_p = _ptr_array(in_stage)
     out_arr, out_p = _ptr_array(out_stage)
     rc = load_library().r2_reduce_copy(_ptr(local), int(nbytes), int(dtype), int(op), in_p,
