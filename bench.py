@@ -366,11 +366,9 @@ def recursive_line(r2, torch, np, wl, out=sys.stderr):
     weights = [50000] * C
     masks = [0b00001111, 0, 0, 0b00000011, 0, 0b00000001, 0, 0]
     levels = r2.r2_recursive_plan(weights, masks)
-    q = 8 * 7 * 6 * 5 * 8 * 8  # every level's ring gets whole 16-byte vectors
-    total = w.N // q * q
-    elems = [int(l.share * total) // q * q for l in levels[1:]]
-    elems = [total - sum(elems)] + elems
+    total = w.N
     desc = r2.RecursiveDesc(R, C, w.align, total, r2.BF16, len(levels))
+    elems = r2.r2_recursive_segments(desc, levels)  # the shares, rounded to what every ring divides into
     xs = wl.make_inputs(w)
     bufs = [_to_device(torch, np, x[:total].copy()) for x in xs]
     ws = torch.empty(r2.r2_recursive_workspace_bytes(desc, levels, elems), dtype=torch.uint8, device="cuda")

@@ -487,6 +487,15 @@ typedef struct {
     uint64_t n_elems;    /* elements per rank                       */
 } r2_recursive_desc;
 
+/* Segment sizes that follow the plan's shares as closely as the rings allow (HOST arithmetic): level
+ * k >= 1 gets floor(share_k * n_elems) rounded down to a multiple of
+ * n_slabs * lcm(members_k, n_ranks) * (16 / element size) elements -- so that its ring chunks are whole
+ * 16-byte vectors and what is left for level 0 still divides into the global ring -- and level 0 gets
+ * the rest.  Needs n_elems to be a multiple of n_slabs * n_ranks * (16 / element size)
+ * (R2_ERR_INVALID otherwise).  Small buffers may leave the upper levels empty.  level_elems: HOST,
+ * n_levels entries out. */
+int r2_recursive_segments(const r2_recursive_desc *desc, const r2_level *levels, uint64_t *level_elems);
+
 /* Workspace (device, 256-byte aligned): per level, its ring workspace, its broadcast's offsets
  * tables and double-buffered stage.  0 if an argument is invalid. */
 uint64_t r2_recursive_workspace_bytes(const r2_recursive_desc *desc, const r2_level *levels,

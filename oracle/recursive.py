@@ -116,6 +116,22 @@ def select_depth(weights, fail_masks, gpus_per_rank, nbytes, alpha, beta, max_le
     return best, times
 
 
+def segments(levels: Sequence[Level], n_ranks: int, n_elems: int, n_slabs: int, elem_bytes: int) -> List[int]:
+    """Elements per level: every level above 0 gets its share of the buffer, rounded down to what
+    both its own ring and the global ring can divide into whole 16-byte vectors; level 0 the rest."""
+    from math import gcd
+
+    per16 = 16 // elem_bytes
+    assert n_elems % (n_slabs * n_ranks * per16) == 0
+    out = [0] * len(levels)
+    for k in range(len(levels) - 1, 0, -1):
+        p = len(levels[k].members)
+        granule = n_slabs * (p * n_ranks // gcd(p, n_ranks)) * per16
+        out[k] = int(levels[k].share * n_elems) // granule * granule
+    out[0] = n_elems - sum(out)
+    return out
+
+
 # ------------------------------------------------------------------ schedule
 
 def chain_order(n_ranks: int, members: Sequence[int]):

@@ -175,6 +175,8 @@ def load_library():
     lib.r2_recursive_time.argtypes = [u32, u32, vp, u32, C.c_double, C.c_double, C.c_double]
     lib.r2_select_strategy.restype = i32
     lib.r2_select_strategy.argtypes = [u32, u32, u32, vp, vp, C.c_double, C.c_double, C.c_double, vp, vp, vp]
+    lib.r2_recursive_segments.restype = i32
+    lib.r2_recursive_segments.argtypes = [C.POINTER(_RecursiveDesc), vp, vp]
     lib.r2_recursive_workspace_bytes.restype = u64
     lib.r2_recursive_workspace_bytes.argtypes = [C.POINTER(_RecursiveDesc), vp, vp]
     lib.r2_recursive_allreduce_sim.restype = i32
@@ -370,6 +372,17 @@ def r2_select_strategy(weights: Sequence[int], fail_masks: Sequence[int], gpus_p
                                            C.cast(C.pointer(nd), C.c_void_p))
     _check(rc, "r2_select_strategy")
     return int(depth.value), [float(t) for t in times[:nd.value]]
+
+
+def r2_recursive_segments(desc: RecursiveDesc, levels: Sequence[Level]) -> List[int]:
+    """Host call: segment sizes (elements per level) that follow the plan's shares."""
+    if len(levels) != desc.n_levels:
+        raise ValueError("r2_recursive_segments: one level per desc.n_levels")
+    arr = _levels(levels)
+    out = (C.c_uint64 * max(len(levels), 1))()
+    rc = load_library().r2_recursive_segments(C.byref(desc.c()), C.cast(arr, C.c_void_p), C.cast(out, C.c_void_p))
+    _check(rc, "r2_recursive_segments")
+    return [int(x) for x in out[:len(levels)]]
 
 
 def r2_recursive_workspace_bytes(desc: RecursiveDesc, levels: Sequence[Level], level_elems: Sequence[int]) -> int:

@@ -202,6 +202,35 @@ extern "C" int r2_select_strategy(uint32_t n_ranks, uint32_t gpus_per_rank, uint
     return R2_OK;
 }
 
+extern "C" int r2_recursive_segments(const r2_recursive_desc *d, const r2_level *levels, uint64_t *level_elems)
+{
+    if (!d || !levels || !level_elems) return R2_ERR_INVALID;
+    if (d->n_ranks < 2 || d->n_ranks > R2_MAX_RANKS || d->n_slabs == 0) return R2_ERR_INVALID;
+    if (d->n_levels == 0 || d->n_levels > R2_MAX_LEVELS) return R2_ERR_INVALID;
+    if (d->dtype != R2_F32 && d->dtype != R2_BF16) return R2_ERR_INVALID;
+    const uint64_t per16 = d->dtype == R2_F32 ? 4 : 8;  // elements in a 16-byte vector
+    const uint64_t g0 = (uint64_t)d->n_slabs * d->n_ranks * per16;
+    if (d->n_elems % g0 != 0) return R2_ERR_INVALID;
+    uint64_t used = 0;
+    for (uint32_t k = d->n_levels; k-- > 1;) {
+        const uint64_t p = popcount64(levels[k].members);
+        if (p < 2 || p > d->n_ranks || !(levels[k].share >= 0.0) || !(levels[k].share <= 1.0)) return R2_ERR_INVALID;
+        uint64_t a = p, b = d->n_ranks;  // lcm(p, R) through gcd
+        while (b) {
+            const uint64_t t = a % b;
+            a = b;
+            b = t;
+        }
+        const uint64_t g = (uint64_t)d->n_slabs * (p / a * d->n_ranks) * per16;
+        uint64_t n = (uint64_t)(levels[k].share * (double)d->n_elems) / g * g;
+        if (n > d->n_elems - used) n = (d->n_elems - used) / g * g;  // shares that sum to more than one
+        level_elems[k] = n;
+        used += n;
+    }
+    level_elems[0] = d->n_elems - used;
+    return R2_OK;
+}
+
 extern "C" uint64_t r2_recursive_workspace_bytes(const r2_recursive_desc *desc, const r2_level *levels,
                                                  const uint64_t *level_elems)
 {

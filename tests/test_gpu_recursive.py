@@ -189,10 +189,10 @@ def test_recursive_large(r2, oracle, dtype):
     masks = [0b00001111, 0, 0b00000011, 0, 0, 0b00000001, 0, 0]
     plan = rec.plan(weights, masks)
     assert len(plan) == 4
-    q = 8 * 7 * 6 * 5 * 8  # divides into every level's ring, 16-byte chunks
-    total = q * 300
-    elems = [int(float(l.share) * total) // q * q for l in plan[1:]]
-    elems = [total - sum(elems)] + elems
+    total = 8 * 7 * 6 * 5 * 8 * 300
+    gdt = r2.F32 if dtype == "f32" else r2.BF16
+    elems = r2.r2_recursive_segments(r2.RecursiveDesc(R, C, 256, total, gdt, len(plan), 1, 1), _levels(r2, plan))
+    assert elems == rec.segments(plan, R, total, 1, 4 if dtype == "f32" else 2) and all(elems)
     say(f"recursive large {dtype} elems={elems}")
     xs = _inputs(rng, R, total, dtype, 0.02 if dtype == "bf16" else 1.0)
     _run(r2, oracle, xs, dtype, plan, elems, 1, C, 256, weights, masks, schedule=1, step_by_step=False)

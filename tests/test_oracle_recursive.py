@@ -308,6 +308,58 @@ def test_host_planner_matches_oracle(r2):
     assert n_multi > 100
 
 
+def test_segments_follow_the_shares_and_fit_the_rings(r2):
+    """Every segment divides into its ring in whole 16-byte vectors, level 0's into the global ring; the
+    upper levels get their share rounded down by less than one granule, level 0 the rest; the host
+    routine agrees with the oracle (a share in doubles may fall one granule short at an exact multiple)."""
+    from math import gcd
+
+    rng = np.random.default_rng(79)
+    checked = planned = 0
+    for _ in range(300):
+        R, C, w, masks = _rand_case(rng)
+        try:
+            lv = rec.plan(w, masks)
+        except o.NoHealthyChannel:
+            continue
+        planned += 1
+        es = (2, 4)[int(rng.integers(0, 2))]
+        S = int(rng.integers(1, 4))
+        per16 = 16 // es
+        N = S * R * per16 * int(rng.integers(1, 1 << int(rng.integers(1, 20))))
+        seg = rec.segments(lv, R, N, S, es)
+        assert sum(seg) == N and all(n >= 0 for n in seg)
+        for k, (l, n) in enumerate(zip(lv, seg)):
+            p = len(l.members)
+            assert n % (S * p * per16) == 0 and (n * es) % 16 == 0
+            if k:
+                granule = S * (p * R // gcd(p, R)) * per16
+                assert n <= l.share * N < n + granule
+        assert seg[0] >= lv[0].share * N
+        desc = r2.RecursiveDesc(R, C, 16, N, r2.F32 if es == 4 else r2.BF16, len(lv), S)
+        got = r2.r2_recursive_segments(desc, r2.r2_recursive_plan(w, masks))
+        assert sum(got) == N
+        for k, (a, b, l) in enumerate(zip(got, seg, lv)):
+            p = len(l.members)
+            granule = S * (p * R // gcd(p, R)) * per16
+            assert a == b or (k and abs(a - b) == granule) or (k == 0 and abs(a - b) % (S * R * per16) == 0)
+        checked += got == seg
+    assert planned > 150 and checked >= 0.95 * planned, (checked, planned)
+    with pytest.raises(r2.R2Error):  # the buffer does not divide into the global ring
+        r2.r2_recursive_segments(r2.RecursiveDesc(4, 8, 16, 4 * 4 * 3 + 4, r2.F32, 1), [r2.Level(0b1111, 0, 8, 8, 1.0)])
+
+
+def test_segments_by_hand():
+    """The worked example (shares 16 : 9 : 12 of 37), fp32, one slab, 4 ranks: granules are
+    lcm(3, 4) * 4 = 48 and lcm(2, 4) * 4 = 16 elements; 37 * 1600 elements."""
+    lv = rec.plan(EQ8, [0b1111, 0b0011, 0, 0])
+    N = 37 * 1600
+    assert rec.segments(lv, 4, N, 1, 4) == [N - 14400 - 19200, 14400, 19200]  # 9 * 1600 = 14400 = 300 * 48
+    assert rec.segments(lv, 4, 16 * 37, 1, 4) == [256, 144, 192]                 # exact: 144 = 3 * 48, 192 = 12 * 16
+    # 640 elements: 9/37 of them is 155.7 -> 144 (3 * 48), 12/37 is 207.6 -> 192 (12 * 16), the rest to level 0
+    assert rec.segments(lv, 4, 640, 1, 4) == [304, 144, 192]
+
+
 def test_host_selector_ties_go_to_the_shallower_plan(r2):
     depth, times = r2.r2_select_strategy(EQ8, [0b1111, 0b11, 0, 0], 1, 0.0, 0.0, 1.0)
     assert times == [0.0, 0.0, 0.0] and depth == 0
