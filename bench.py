@@ -248,8 +248,7 @@ def split_line(r2, torch, np, wl, out=sys.stderr):
     w = wl.cfg2()
     R, N, C = w.R, w.N, w.C
     use, y, thr = r2.r2_split_plan(R, 1, 0.5)
-    granule = R * (R - 1) * 8 * 64
-    npart = int(round(y * N / granule)) * granule
+    npart = r2.r2_split_partial_elems(R, 1, 1, r2.BF16, N, y)  # the share, rounded to what both rings divide into
     desc = r2.SplitDesc(R, 0, C, w.align, N, npart, r2.BF16)
     xs = wl.make_inputs(w)
     bufs = [_to_device(torch, np, x) for x in xs]

@@ -364,6 +364,14 @@ int r2_split_plan(uint32_t n_servers, uint32_t gpus_per_server, double lost_frac
                   int32_t *use_split, double *y_star, double *threshold);
 double r2_split_time(uint32_t n_servers, uint32_t gpus_per_server, double lost_fraction, double y);
 
+/* The tail that goes through partial all-reduce + broadcast when the share y of a buffer of n_elems
+ * elements does (HOST arithmetic): floor(y * n_elems) rounded down to a multiple of
+ * lcm(n_slabs_global * R, n_slabs_partial * (R-1)) * (16 / element size) elements, so that both rings
+ * get chunks of whole 16-byte vectors.  Needs n_elems to be a multiple of
+ * n_slabs_global * R * (16 / element size); 0 if it is not, or if an argument is invalid. */
+uint64_t r2_split_partial_elems(uint32_t n_ranks, uint32_t n_slabs_global, uint32_t n_slabs_partial,
+                                int32_t dtype, uint64_t n_elems, double y);
+
 /* The schedule, over R simulated ranks of which `degraded_rank` d is the one with failed NICs.  Every
  * rank buffer is cut in two: the first n_elems - n_partial elements go through a global ring
  * all-reduce over all R ranks (r2_ring_allreduce_sim, channel state of the degraded server, since the

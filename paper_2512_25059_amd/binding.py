@@ -164,6 +164,8 @@ def load_library():
     lib.r2_split_plan.restype = i32
     lib.r2_split_plan.argtypes = [u32, u32, C.c_double, vp, vp, vp]
     lib.r2_split_time.restype = C.c_double
+    lib.r2_split_partial_elems.restype = u64
+    lib.r2_split_partial_elems.argtypes = [u32, u32, u32, i32, u64, C.c_double]
     lib.r2_split_time.argtypes = [u32, u32, C.c_double, C.c_double]
     lib.r2_split_workspace_bytes.restype = u64
     lib.r2_split_workspace_bytes.argtypes = [C.POINTER(_SplitDesc)]
@@ -304,6 +306,13 @@ def r2_split_plan(n_servers: int, gpus_per_server: int, lost_fraction: float) ->
 
 def r2_split_time(n_servers: int, gpus_per_server: int, lost_fraction: float, y: float) -> float:
     return float(load_library().r2_split_time(int(n_servers), int(gpus_per_server), float(lost_fraction), float(y)))
+
+
+def r2_split_partial_elems(n_ranks: int, n_slabs_global: int, n_slabs_partial: int, dtype: int, n_elems: int,
+                           y: float) -> int:
+    """Host call: the size of the tail for share y, rounded to what both rings divide into."""
+    return int(load_library().r2_split_partial_elems(int(n_ranks), int(n_slabs_global), int(n_slabs_partial),
+                                                     int(dtype), int(n_elems), float(y)))
 
 
 def r2_split_workspace_bytes(desc: SplitDesc) -> int:

@@ -76,6 +76,24 @@ extern "C" double r2_split_time(uint32_t n_servers, uint32_t gpus_per_server, do
     return (t1 > t2 ? t1 : t2) + t3;
 }
 
+extern "C" uint64_t r2_split_partial_elems(uint32_t n_ranks, uint32_t n_slabs_global, uint32_t n_slabs_partial,
+                                           int32_t dtype, uint64_t n_elems, double y)
+{
+    if (n_ranks < 3 || n_ranks > R2_MAX_RANKS || n_slabs_global == 0 || n_slabs_partial == 0) return 0;
+    if ((dtype != R2_F32 && dtype != R2_BF16) || !(y >= 0.0) || !(y <= 1.0)) return 0;
+    const uint64_t per16 = dtype == R2_F32 ? 4 : 8;
+    const uint64_t gg = (uint64_t)n_slabs_global * n_ranks, gp = (uint64_t)n_slabs_partial * (n_ranks - 1);
+    if (n_elems % (gg * per16) != 0) return 0;
+    uint64_t a = gg, b = gp;
+    while (b) {
+        const uint64_t t = a % b;
+        a = b;
+        b = t;
+    }
+    const uint64_t granule = gg / a * gp * per16;
+    return (uint64_t)(y * (double)n_elems) / granule * granule;
+}
+
 extern "C" uint64_t r2_split_workspace_bytes(const r2_split_desc *desc)
 {
     SplitShape s;

@@ -73,6 +73,29 @@ def test_product_planner_matches_oracle():
             r2.r2_split_plan(*bad)
 
 
+def test_partial_elems_follow_the_share_and_fit_both_rings():
+    """The tail for share Y: both parts divide into their rings in whole 16-byte vectors, the tail is Y of
+    the buffer rounded down by less than one granule.  By hand: 8 ranks, bf16, one slab each: granule
+    lcm(8, 7) * 8 = 448 elements; Y = 0.5052 of 2^26 elements is 33 903 398.1 -> 75 677 * 448."""
+    import paper_2512_25059_amd as r2
+    from math import gcd
+
+    assert r2.r2_split_partial_elems(8, 1, 1, r2.BF16, 1 << 26, 0.5052) == 75677 * 448
+    rng = np.random.default_rng(13)
+    for _ in range(300):
+        R, Sg, Sp = int(rng.integers(3, 65)), int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        dt, per16 = ((r2.F32, 4), (r2.BF16, 8))[int(rng.integers(0, 2))]
+        N = Sg * R * per16 * int(rng.integers(1, 1 << 16))
+        y = float(rng.random())
+        n = r2.r2_split_partial_elems(R, Sg, Sp, dt, N, y)
+        granule = (Sg * R) * (Sp * (R - 1)) // gcd(Sg * R, Sp * (R - 1)) * per16
+        assert n % (Sp * (R - 1) * per16) == 0 and (N - n) % (Sg * R * per16) == 0
+        assert n <= y * N < n + granule + 1
+    assert r2.r2_split_partial_elems(8, 1, 1, r2.BF16, (1 << 26) + 8, 0.5) == 0   # does not divide into the global ring
+    assert r2.r2_split_partial_elems(2, 1, 1, r2.BF16, 1 << 20, 0.5) == 0         # no partial ring with one healthy rank
+    assert r2.r2_split_partial_elems(8, 1, 1, 5, 1 << 20, 0.5) == 0 and r2.r2_split_partial_elems(8, 1, 1, r2.F32, 1 << 20, 1.5) == 0
+
+
 # ------------------------------------------------------------------ schedule
 
 def _inputs(rng, R, N, dtype, ints=False):
