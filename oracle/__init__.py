@@ -3,6 +3,12 @@
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
 benchmark's ``cpu_baseline`` leg.  The product package never imports it and it
 never imports the product package.
+
+``r2_oracle`` (plain C behind ctypes) holds the partition, the fused reduce-copy, the ring step by
+step and the ring's result by definition; the other modules compose those in Python:
+``split`` and ``recursive`` (the failure-aware all-reduce schedules and their planners),
+``rerank`` (bridge re-ranking), ``sendrecv`` and ``collectives`` (the other collectives under
+R2CCL-Balance), ``rails`` (rings whose servers each have a channel state of their own).
 """
 from .r2_oracle import (  # noqa: F401
     BF16,
