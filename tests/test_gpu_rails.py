@@ -130,6 +130,29 @@ def test_rails_failure_and_recovery_at_one_server(r2, oracle):
     _run(r2, oracle, _inputs(rng, 4, 2 * 4 * 8 * 1500, "bf16"), "bf16", "ar", 2, 4, 256, w, None, 0, True, sched)
 
 
+def test_rails_call_marshalled_once(r2, oracle):
+    """RailsCall issues the same call from arguments marshalled once: two runs on fresh inputs, same bits."""
+    rng = np.random.default_rng(923)
+    R, C, N = 4, 4, 4 * 8 * 900
+    xs = _inputs(rng, R, N, "bf16")
+    sched = r2.static_rails([3, 1, 4, 1], [0b0001, 0, 0b0100, 0])
+    desc = r2.SimDesc(R, 1, C, 64, N, r2.BF16, r2.PHASE_AR | r2.PHASE_LINKS)
+    ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
+    bufs = [_dev(x) for x in xs]
+    call = r2.RailsCall(desc, bufs, sched, ws)
+    want = oracle.expected(xs, oracle.BF16, 1, oracle.PHASE_AR)
+    say("rails: RailsCall, two runs")
+    for _ in range(2):
+        for b, x in zip(bufs, xs):
+            b.copy_(_dev(x))
+        call.run()
+        torch.cuda.synchronize()
+        for r in range(R):
+            assert bufs[r].cpu().numpy().view(np.uint16).tobytes() == want[r].tobytes()
+    with pytest.raises(ValueError):
+        r2.RailsCall(desc, bufs, sched[:3], ws)
+
+
 def test_rerank_then_ring(r2, oracle):
     """Neighbours that lost different rails share nothing; the library's bridge re-ranking moves a healthy
     node between them and the ring over the new order runs."""
