@@ -431,6 +431,19 @@ def main() -> int:
     ms_per_step = secs / args.steps * 1e3
     gbps = w.algorithmic_bytes / (secs / args.steps) / 1e9
 
+    # the same steps one by one, each between a pair of events on the stream they run on: the median
+    # says how much a slow outlier weighs in the figure above (launch-bound workloads: the events'
+    # own cost shows)
+    singles = []
+    for _ in range(max(args.steps, 1) if not run.fused else 0):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run.step()
+        e1.record()
+        torch.cuda.synchronize()
+        singles.append(e0.elapsed_time(e1))
+    median_ms = sorted(singles)[len(singles) // 2] if singles else None
+
     # dominant kernel: the fused reducing step that also stages (two reads, two writes per element)
     ktimes = run.kernel_times(args.kernel_reps)
     if run.fused:
@@ -458,6 +471,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median_of_single_steps": None if median_ms is None else round(median_ms, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
