@@ -323,6 +323,20 @@ def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
     print(f"{'all-reduce':14s} cfg2 shape, four ranks lost a rail each (per-link tables): {s * 1e6:10.1f} us/op  "
           f"{alg / s / 1e9:9.1f} GB/s  {100 * alg / s / 1e9 / HBM_PEAK_GBPS:6.2f} % of HBM peak ({alg} algorithmic bytes)",
           file=out, flush=True)
+    del ws, call
+    # ... and at the inference sizes of cfg5 (hidden 8192 x tokens), where fused columns take over
+    for tokens in (1, 16, 64, 256):
+        n = 8192 * tokens
+        small = [b[:n] for b in bufs]
+        line = []
+        for sched in (r2.SCHED_AUTO, r2.SCHED_STEPS):
+            desc = r2.SimDesc(R, 1, C, w.align, n, r2.BF16, r2.PHASE_AR | r2.PHASE_LINKS, 0, sched)
+            ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+            call = r2.RailsCall(desc, small, r2.static_rails([50000] * C, masks), ws)
+            line.append(_time_calls(torch, call.run, n=200, warm=20) * 1e6)
+            del ws, call
+        print(f"{'all-reduce':14s} hidden 8192 x {tokens:3d} tokens, per-link tables: {line[0]:8.1f} us/op as scheduled, "
+              f"{line[1]:8.1f} us/op with one launch per step", file=out, flush=True)
 
 
 def allreduce_size_sweep(r2, torch, np, wl, out=sys.stderr):

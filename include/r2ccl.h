@@ -327,12 +327,22 @@ int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void 
  * (r2_sim_num_transmissions returns R*S*(J-1)), and offsets_log, if not NULL, receives the same.  The
  * result in the rank buffers is the ring's (all-reduce, reduce-scatter or all-gather), whatever the
  * schedules.  rank_epochs, n_rank_epochs and the weights they point to: HOST memory, read during the
- * call only.  Only the step schedule runs it; R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if a link
- * is left without a channel at some transmission -- which is what re-ranking is for.  Asynchronous on
- * `stream`; allocates no device memory. */
+ * call only.  R2_ERR_NO_HEALTHY_CHANNEL, before any launch, if a link is left without a channel at
+ * some transmission -- which is what re-ranking is for.  desc->schedule as for the plain ring: one
+ * launch per step and pass, or fused columns cut wherever some link's table changes within a slab
+ * (R2_SCHED_FUSED is R2_ERR_INVALID where ring chunks are no whole 16-byte vectors or where the R
+ * links' table rows of one launch, R * steps * ((C+1)*8 + 24) bytes, exceed 56 KiB of LDS; AUTO then
+ * takes the step schedule).  Fused launches cut the chunks themselves when all links' states fit one
+ * kernel-argument block (32 states, 640 weights); otherwise one partition launch runs in front.
+ * Asynchronous on `stream`; allocates no device memory. */
 int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                       const r2_epoch *const *rank_epochs, const uint32_t *n_rank_epochs,
                       void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log, void *stream);
+
+/* Which schedule r2_ring_rails_sim will use for this descriptor and these epoch lists: R2_SCHED_STEPS
+ * or R2_SCHED_FUSED, or the negative R2_ERR code that call would return before launching.  Host only. */
+int r2_rails_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *const *rank_epochs,
+                              const uint32_t *n_rank_epochs);
 
 /* All-to-All under R2CCL-Balance (Sec. 5, table of strategies: point-to-point incl. All-to-All;
  * Sec. 5.1): desc->phases must be R2_PHASE_ALLTOALL.  Afterwards block q of recv_bufs[r] equals

@@ -210,6 +210,8 @@ def load_library():
     lib.r2_collective_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_ring_rails_sim.restype = i32
     lib.r2_ring_rails_sim.argtypes = [pd, vp, vp, vp, vp, u64, vp, vp]
+    lib.r2_rails_resolve_schedule.restype = i32
+    lib.r2_rails_resolve_schedule.argtypes = [pd, vp, vp]
     lib.r2_alltoall_sim.restype = i32
     lib.r2_alltoall_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
     _lib = lib
@@ -635,6 +637,21 @@ def r2_ring_rails_sim(desc: SimDesc, rank_bufs: Sequence, rank_epochs: Sequence,
                                           wp, wb, _ptr(offsets_log), _stream(stream))
     del arr, lists
     _check(rc, "r2_ring_rails_sim")
+
+
+def r2_rails_resolve_schedule(desc: SimDesc, rank_epochs: Sequence) -> int:
+    if len(rank_epochs) != desc.n_ranks:
+        raise ValueError("r2_rails_resolve_schedule: one epoch list per rank")
+    if any(len(w) != desc.n_channels for eps in rank_epochs for _, _, w in eps):
+        raise ValueError("r2_rails_resolve_schedule: one weight per channel in every epoch")
+    lists = [_epoch_array(eps) for eps in rank_epochs]
+    ptrs = (C.c_void_p * len(lists))(*[C.cast(a, C.c_void_p) for a, _ in lists])
+    counts = (C.c_uint32 * len(lists))(*[len(eps) for eps in rank_epochs])
+    rc = load_library().r2_rails_resolve_schedule(C.byref(desc.c()), C.cast(ptrs, C.c_void_p), C.cast(counts, C.c_void_p))
+    del lists
+    if rc < 0:
+        raise R2Error(rc, "r2_rails_resolve_schedule")
+    return rc
 
 
 class RailsCall:

@@ -161,6 +161,44 @@ def test_chain_and_alltoall_descriptor_arithmetic(r2):
     assert r2.r2_sim_num_steps(r2.SimDesc(4, 5, 8, 256, 4 * 5 * 100 + 4, r2.F32, r2.PHASE_ALLTOALL)) == 0
 
 
+def test_rails_schedule_is_host_arithmetic(r2):
+    """r2_rails_resolve_schedule: fused columns for launch-bound sizes whose ring chunks are whole
+    16-byte vectors and whose links' rows fit LDS, else one launch per step; the errors r2_ring_rails_sim
+    would return before launching."""
+    links = r2.PHASE_AR | r2.PHASE_LINKS
+    w = [50000] * 8
+    rails = r2.static_rails(w, [1, 2, 0, 0, 4, 0, 0, 8])
+    small = r2.SimDesc(8, 1, 8, 256, 8192, r2.BF16, links)
+    assert r2.r2_rails_resolve_schedule(small, rails) == r2.SCHED_FUSED
+    big = r2.SimDesc(8, 1, 8, 256, 1 << 26, r2.BF16, links)  # 128 MiB per rank
+    assert r2.r2_rails_resolve_schedule(big, rails) == r2.SCHED_STEPS
+    assert r2.r2_rails_resolve_schedule(r2.SimDesc(8, 1, 8, 256, 1 << 26, r2.BF16, links, 0, r2.SCHED_FUSED), rails) == r2.SCHED_FUSED
+    assert r2.r2_rails_resolve_schedule(r2.SimDesc(8, 1, 8, 256, 8192, r2.BF16, links, 0, r2.SCHED_STEPS), rails) == r2.SCHED_STEPS
+    ragged = r2.SimDesc(8, 1, 8, 256, 8 * 7, r2.BF16, links)  # 14-byte ring chunks
+    assert r2.r2_rails_resolve_schedule(ragged, rails) == r2.SCHED_STEPS
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_rails_resolve_schedule(r2.SimDesc(8, 1, 8, 256, 8 * 7, r2.BF16, links, 0, r2.SCHED_FUSED), rails)
+    assert e.value.code == -1
+    # 32 ranks x 62 transmissions x (9 * 8 + 24) bytes = 190 KiB of rows: more than a workgroup's LDS
+    many = r2.static_rails(w, [0] * 32)
+    assert r2.r2_rails_resolve_schedule(r2.SimDesc(32, 1, 8, 256, 32 * 64, r2.BF16, links), many) == r2.SCHED_STEPS
+    with pytest.raises(r2.R2Error):
+        r2.r2_rails_resolve_schedule(r2.SimDesc(32, 1, 8, 256, 32 * 64, r2.BF16, links, 0, r2.SCHED_FUSED), many)
+    # ... unless the links' tables change so often that every launch is short: cuts before steps 1..61
+    flapping = [[(t, t & 1, w) for t in range(62)]] + r2.static_rails(w, [0] * 31)
+    assert r2.r2_rails_resolve_schedule(r2.SimDesc(32, 1, 8, 256, 32 * 64, r2.BF16, links, 0, r2.SCHED_FUSED),
+                                        flapping) == r2.SCHED_FUSED
+    assert r2.r2_rails_resolve_schedule(r2.SimDesc(32, 1, 8, 256, 32 * 64, r2.BF16, links), flapping) == r2.SCHED_STEPS  # saves no launch
+    # neighbours that share no rail
+    with pytest.raises(r2.R2Error) as e:
+        r2.r2_rails_resolve_schedule(small, r2.static_rails(w, [0x0f, 0xf0, 0, 0, 0, 0, 0, 0]))
+    assert e.value.code == -2
+    with pytest.raises(r2.R2Error):  # the flag is missing
+        r2.r2_rails_resolve_schedule(r2.SimDesc(8, 1, 8, 256, 8192, r2.BF16, r2.PHASE_AR), rails)
+    with pytest.raises(r2.R2Error):  # one epoch list says nothing about per-link tables
+        r2.r2_sim_resolve_schedule(small, [(0, 0, w)])
+
+
 def test_binding_checks_list_lengths(r2):
     """The C side reads as many pointers and weights as the descriptor says: the binding refuses shorter lists."""
     d = r2.SimDesc(4, 1, 4, 256, 4096, r2.F32, r2.PHASE_ALLTOALL)

@@ -32,7 +32,9 @@ def _inputs(rng, R, N, dtype):
 
 
 def _run(r2, oracle, xs, dtype, phases, S, C, align, weights, masks, window=0, check_stage=True, schedules=None):
-    """``schedules``: per-rank epoch lists; by default the static state (weights, masks[r]) of every rank."""
+    """``schedules``: per-rank epoch lists; by default the static state (weights, masks[r]) of every rank.
+    Runs the case under R2_SCHED_AUTO, under the step schedule and, where the library accepts it, under
+    fused columns; returns the schedules that ran (AUTO as what it resolved to)."""
     R, N = len(xs), xs[0].size
     if schedules is None:
         schedules = rails.static_epochs(weights, masks)
@@ -40,29 +42,43 @@ def _run(r2, oracle, xs, dtype, phases, S, C, align, weights, masks, window=0, c
     odt = oracle.F32 if dtype == "f32" else oracle.BF16
     gph = {"rs": r2.PHASE_RS, "ag": r2.PHASE_AG, "ar": r2.PHASE_AR}[phases] | r2.PHASE_LINKS
     oph = {"rs": oracle.PHASE_RS, "ag": oracle.PHASE_AG, "ar": oracle.PHASE_AR}[phases]
-    desc = r2.SimDesc(R, S, C, align, N, gdt, gph, window, 0)
     n_tx = S * ((2 * R - 2) if phases == "ar" else (R - 1))
-    assert r2.r2_sim_num_transmissions(desc) == R * n_tx  # a block of tables per link
-    assert r2.r2_sim_resolve_schedule(desc, [(0, 0, [1] * C)]) == r2.SCHED_STEPS
-    ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
-    log = torch.full((R, n_tx, C + 1), -1, dtype=torch.int64, device="cuda")
-    bufs = [_dev(x) for x in xs]
-    r2.r2_ring_rails_sim(desc, bufs, schedules, ws, log)
-    torch.cuda.synchronize()
     o_bufs = [x.copy() for x in xs]
     tables, stage = rails.ring_rails_sim(o_bufs, odt, S, C, align, schedules, oph, FILL)
     want = oracle.expected(xs, odt, S, oph)
-    for r in range(R):
-        got = bufs[r].cpu().numpy().view(xs[r].dtype)
-        assert got.tobytes() == want[r].tobytes(), f"rank {r} vs definition"
-        assert got.tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
-    assert log.cpu().numpy().view(np.uint64).tolist() == tables.tolist()
-    assert ws[:R * n_tx * (C + 1) * 8].cpu().numpy().view(np.uint64).reshape(R, n_tx, C + 1).tolist() == tables.tolist()
-    if check_stage:
-        cap = r2.r2_sim_stage_capacity(desc)
-        off = r2.r2_sim_stage_offset(desc)
-        st = ws[off:off + 2 * R * S * C * cap].cpu().numpy()
-        assert st.tobytes() == stage.tobytes(), "stage area"
+    ran = []
+    for sched in (r2.SCHED_AUTO, r2.SCHED_STEPS, r2.SCHED_FUSED):
+        desc = r2.SimDesc(R, S, C, align, N, gdt, gph, window, sched)
+        assert r2.r2_sim_num_transmissions(desc) == R * n_tx  # a block of tables per link
+        with pytest.raises(r2.R2Error):  # one epoch list says nothing about per-link tables
+            r2.r2_sim_resolve_schedule(desc, [(0, 0, [1] * C)])
+        try:
+            resolved = r2.r2_rails_resolve_schedule(desc, schedules)
+        except r2.R2Error as e:  # fused columns do not fit this case (ragged vectors, or too many rows for LDS)
+            assert sched == r2.SCHED_FUSED and e.code == -1
+            continue
+        assert resolved == sched or sched == r2.SCHED_AUTO
+        if resolved in ran:
+            continue  # AUTO already ran this schedule
+        say(f"  schedule {sched} -> {resolved}")
+        ws = torch.full((r2.r2_sim_workspace_bytes(desc),), FILL, dtype=torch.uint8, device="cuda")
+        log = torch.full((R, n_tx, C + 1), -1, dtype=torch.int64, device="cuda")
+        bufs = [_dev(x) for x in xs]
+        r2.r2_ring_rails_sim(desc, bufs, schedules, ws, log)
+        torch.cuda.synchronize()
+        for r in range(R):
+            got = bufs[r].cpu().numpy().view(xs[r].dtype)
+            assert got.tobytes() == want[r].tobytes(), f"rank {r} vs definition"
+            assert got.tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
+        assert log.cpu().numpy().view(np.uint64).tolist() == tables.tolist()
+        assert ws[:R * n_tx * (C + 1) * 8].cpu().numpy().view(np.uint64).reshape(R, n_tx, C + 1).tolist() == tables.tolist()
+        if check_stage or resolved == r2.SCHED_FUSED:  # fused columns run no passes
+            cap = r2.r2_sim_stage_capacity(desc)
+            off = r2.r2_sim_stage_offset(desc)
+            st = ws[off:off + 2 * R * S * C * cap].cpu().numpy()
+            assert st.tobytes() == stage.tobytes(), "stage area"
+        ran.append(resolved)
+    return ran
 
 
 @pytest.mark.parametrize("phases", ["rs", "ag", "ar"])
@@ -74,7 +90,8 @@ def test_rails_small(r2, oracle, dtype, phases):
     for R, S, E in ((2, 1, per16 * 100), (4, 3, per16 * 1031), (8, 2, 7), (3, 2, per16 * 512 * 5 + 3), (5, 1, per16 * 512 * 2)):
         masks = [int(rng.integers(0, 256)) & ~0b00010000 for _ in range(R)]  # rail 4 survives everywhere
         say(f"rails {phases} {dtype} R={R} S={S} E={E} masks={masks}")
-        _run(r2, oracle, _inputs(rng, R, S * R * E, dtype), dtype, phases, S, 8, 256, w, masks)
+        ran = _run(r2, oracle, _inputs(rng, R, S * R * E, dtype), dtype, phases, S, 8, 256, w, masks)
+        assert (r2.SCHED_FUSED in ran) == (E % per16 == 0)  # whole 16-byte vectors: fused columns ran too
 
 
 @pytest.mark.parametrize("seed", [1, 2])
@@ -106,6 +123,43 @@ def test_rails_random_configurations(r2, oracle, seed):
              schedules is None or window == 0, schedules)
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_rails_fused_columns_random(r2, oracle, seed):
+    """Ring chunks of whole 16-byte vectors, so that fused columns run: narrow and wide columns, a ragged
+    last column, more ranks than a workgroup has waves, tables that change on the way (launch cuts)."""
+    rng = np.random.default_rng(930 + seed)
+    fused_runs = 0
+    for case in range(16):
+        dtype = "f32" if rng.random() < 0.5 else "bf16"
+        per16 = 4 if dtype == "f32" else 8
+        phases = ("rs", "ag", "ar")[int(rng.integers(0, 3))]
+        R = int(rng.integers(17, 23)) if case % 4 == 0 or case % 8 == 1 else int(rng.integers(2, 10))
+        S, C = int(rng.integers(1, 4)), int(rng.integers(1, 12))
+        E = per16 * int(rng.integers(1, 700))
+        if case % 5 == 0:
+            R, S, E = int(rng.integers(2, 5)), 2, per16 * int(rng.integers(16400, 17000))  # > 256 KiB chunks: wide columns
+        align = (16, 64, 256)[int(rng.integers(0, 3))]
+        w = [int(x) for x in rng.integers(1, 1000, C)]
+        up = int(rng.integers(0, C))
+        masks = [int(rng.integers(0, 1 << C)) & ~(1 << up) if rng.random() < 0.7 else 0 for _ in range(R)]
+        n_tx = S * ((2 * R - 2) if phases == "ar" else (R - 1))
+        schedules = []
+        for r in range(R):
+            eps = [(0, masks[r], w)]
+            if case % 2:
+                for t in sorted(set(int(x) for x in rng.integers(1, n_tx + 1, int(rng.integers(0, 3))))):
+                    eps.append((t, int(rng.integers(0, 1 << C)) & ~(1 << up), [int(x) for x in rng.integers(1, 1000, C)]))
+            schedules.append(eps)
+        say(f"rails fused {seed}.{case} {phases} {dtype} R={R} S={S} C={C} E={E} align={align} "
+            f"changes={[len(e) - 1 for e in schedules]}")
+        ran = _run(r2, oracle, _inputs(rng, R, S * R * E, dtype), dtype, phases, S, C, align, w, masks, 0, True, schedules)
+        steps = (2 * R - 1) if phases == "ar" else R
+        if R * steps * ((C + 1) * 8 + 24) <= 56 * 1024:  # the rows of even one launch over all steps fit LDS
+            assert r2.SCHED_FUSED in ran
+        fused_runs += r2.SCHED_FUSED in ran
+    assert fused_runs >= 10
+
+
 def test_rails_maximum_ranks_and_channels_and_large_chunks(r2, oracle):
     rng = np.random.default_rng(920)
     C = 64
@@ -114,6 +168,11 @@ def test_rails_maximum_ranks_and_channels_and_large_chunks(r2, oracle):
     masks[63] |= 1 << 63
     say("rails R=64 C=64")
     _run(r2, oracle, _inputs(rng, 64, 64 * 8 * 5, "bf16"), "bf16", "ar", 1, C, 16, w, masks)
+    say("rails R=32, one rank's state changes at every transmission: fused launches of one or two steps")
+    w8 = [50000] * 8
+    flapping = [[(t, t & 1, w8) for t in range(62)]] + rails.static_epochs(w8, [0] * 31)
+    ran = _run(r2, oracle, _inputs(rng, 32, 32 * 64, "bf16"), "bf16", "ar", 1, 8, 16, w8, None, 0, True, flapping)
+    assert ran == [r2.SCHED_STEPS, r2.SCHED_FUSED]
     say("rails 2 MiB chunks, a window that forces byte-range passes")
     xs = _inputs(rng, 4, 4 * (1 << 19), "f32")
     _run(r2, oracle, xs, "f32", "ar", 1, 8, 256, [50000] * 8, [0b1, 0b10, 0, 0b1100], window=3 << 20)
@@ -199,7 +258,12 @@ def test_rails_argument_errors(r2):
     assert e.value.code == -2
     for bad in (r2.PHASE_LINKS, r2.PHASE_LINKS | r2.PHASE_SENDRECV, r2.PHASE_LINKS | r2.PHASE_BROADCAST):
         assert r2.r2_sim_num_steps(r2.SimDesc(4, 1, 4, 16, 64, r2.F32, bad)) == 0
-    assert r2.r2_sim_num_steps(r2.SimDesc(4, 1, 4, 16, 64, r2.F32, r2.PHASE_AR | r2.PHASE_LINKS, 0, r2.SCHED_FUSED)) == 0
+    assert r2.r2_sim_num_steps(r2.SimDesc(4, 1, 4, 16, 64, r2.F32, r2.PHASE_AR | r2.PHASE_LINKS, 0, r2.SCHED_FUSED)) == 7
+    ragged = r2.SimDesc(4, 1, 4, 16, 4 * 5, r2.F32, r2.PHASE_AR | r2.PHASE_LINKS, 0, r2.SCHED_FUSED)  # 20-byte ring chunks
+    with pytest.raises(r2.R2Error):
+        r2.r2_rails_resolve_schedule(ragged, r2.static_rails(w, [0] * 4))
+    with pytest.raises(r2.R2Error):
+        r2.r2_ring_rails_sim(ragged, bufs, r2.static_rails(w, [0] * 4), ws)
     with pytest.raises(r2.R2Error):
         r2.r2_sim_fused_steps(desc, bufs, 0, 2, ws)
     torch.cuda.synchronize()
