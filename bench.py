@@ -313,7 +313,17 @@ def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
         print(f"{name:14s} cfg2 shape, channel 2 down: {s * 1e6:10.1f} us/op  {alg / s / 1e9:9.1f} GB/s  "
               f"{100 * alg / s / 1e9 / HBM_PEAK_GBPS:6.2f} % of HBM peak ({alg} algorithmic bytes)", file=out, flush=True)
         del ws
-    # Sec. 6: every server has lost a different rail; a link uses what both of its ends still have
+    del recv
+    rails_lines(r2, torch, np, wl, out, bufs)
+
+
+def rails_lines(r2, torch, np, wl, out=sys.stderr, bufs=None):
+    """Sec. 6 on top of Sec. 5.1: every server has lost a different rail; a link uses what both of its
+    ends still have (per-link tables).  The all-reduce on the cfg2 shape and at the sizes of cfg5."""
+    w = wl.cfg2()
+    R, N, C, e = w.R, w.N, w.C, 2
+    if bufs is None:
+        bufs = [_to_device(torch, np, x) for x in wl.make_inputs(w)]
     masks = [0b00000001, 0b00000010, 0, 0, 0b00000100, 0, 0, 0b00001000]
     desc = r2.SimDesc(R, 1, C, w.align, N, r2.BF16, r2.PHASE_AR | r2.PHASE_LINKS, 0, r2.SCHED_STEPS)
     ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
@@ -412,6 +422,8 @@ def main() -> int:
     ap.add_argument("--stage-window-mib", type=float, default=0.0,
                     help="stage bytes one launch may write (0 = library default)")
     ap.add_argument("--all", action="store_true", help="also print a table of every configuration to stderr")
+    ap.add_argument("--rails", action="store_true",
+                    help="also print the all-reduce with per-link tables (cfg2 shape and cfg5's sizes) to stderr")
     ap.add_argument("--sweep", action="store_true",
                     help="also print size sweeps to stderr: r2_reduce_copy, and the whole all-reduce without and with failures")
     args = ap.parse_args()
@@ -561,6 +573,8 @@ def main() -> int:
         split_line(r2, torch, np, wl)
         recursive_line(r2, torch, np, wl)
         other_collectives_lines(r2, torch, np, wl)
+    if args.rails and not args.all:
+        rails_lines(r2, torch, np, wl)
     if args.sweep:
         reduce_copy_sweep(r2, torch)
         allreduce_size_sweep(r2, torch, np, wl)
