@@ -41,7 +41,8 @@ enum {
     R2_ERR_NO_HEALTHY_CHANNEL = -2, /* every channel failed or has zero bandwidth (Appendix C: at
                                        least one healthy NIC must remain)                           */
     R2_ERR_OVERFLOW = -3,           /* a size computation does not fit 64 bits                       */
-    R2_ERR_CAPACITY = -4,           /* a slice exceeds its stage buffer, or the workspace is too small */
+    R2_ERR_CAPACITY = -4,           /* a slice exceeds its stage buffer, the workspace is too small, or
+                                       host memory for a call's own bookkeeping ran out              */
     R2_ERR_DEVICE = -5              /* the HIP runtime reported an error                             */
 };
 

@@ -7,6 +7,7 @@
 // leaves behind does not create a narrow edge.
 #include <algorithm>
 #include <cstdint>
+#include <new>
 #include <vector>
 
 #include "r2ccl.h"
@@ -15,12 +16,8 @@ namespace {
 
 inline uint32_t shared_rails(uint64_t a, uint64_t b) { return (uint32_t)__builtin_popcountll(a & b); }
 
-}  // namespace
-
-extern "C" int r2_bridge_rerank(const uint32_t *ring, const uint64_t *rails, uint32_t n,
-                                uint32_t *out_ring, uint32_t *n_relocated)
+int rerank(const uint32_t *ring, const uint64_t *rails, uint32_t n, uint32_t *out_ring, uint32_t *n_relocated)
 {
-    if (!ring || !rails || !out_ring || n == 0) return R2_ERR_INVALID;
     std::vector<char> seen(n, 0);
     for (uint32_t i = 0; i < n; ++i) {
         if (ring[i] >= n || seen[ring[i]]) return R2_ERR_INVALID;  // must be a permutation of 0..n-1
@@ -68,4 +65,17 @@ extern "C" int r2_bridge_rerank(const uint32_t *ring, const uint64_t *rails, uin
     std::copy(cur.begin(), cur.end(), out_ring);
     if (n_relocated) *n_relocated = moved;
     return R2_OK;
+}
+
+}  // namespace
+
+extern "C" int r2_bridge_rerank(const uint32_t *ring, const uint64_t *rails, uint32_t n,
+                                uint32_t *out_ring, uint32_t *n_relocated)
+{
+    if (!ring || !rails || !out_ring || n == 0) return R2_ERR_INVALID;
+    try {
+        return rerank(ring, rails, n, out_ring, n_relocated);
+    } catch (const std::bad_alloc &) {  // the working copies are host allocations; nothing may unwind into C
+        return R2_ERR_CAPACITY;
+    }
 }

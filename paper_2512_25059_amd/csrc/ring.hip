@@ -6,6 +6,7 @@
 // (per-NIC send staging buffers, chunk-granular progress), Sec. 5.2 (ring all-reduce = reduce-scatter,
 // then all-gather), Sec. 5 and 5.1 (the other collectives keep their schedule under R2CCL-Balance),
 // Sec. 6 (servers that lost different rails).
+#include <new>
 #include <vector>
 
 #include "reduce_copy_device.h"
@@ -595,6 +596,14 @@ uint32_t links_lds_bytes(const SimShape &s, uint32_t step_begin, uint32_t step_e
     return bytes <= kLinksLdsBytes ? (uint32_t)bytes : 0;
 }
 
+template <bool BF16, unsigned U>
+void launch_links(dim3 grid, dim3 block, uint32_t lds, hipStream_t st, const FusedArgs &a, uint64_t link_rows,
+                  const EpochBatch *eb)
+{
+    if (eb) hipLaunchKernelGGL((ring_fused_links_partition_kernel<BF16, U>), grid, block, lds, st, a, link_rows, *eb);
+    else hipLaunchKernelGGL((ring_fused_links_kernel<BF16, U>), grid, block, lds, st, a, link_rows);
+}
+
 // One fused launch of a ring with per-link tables.  With `eb` (the links' states on one axis) the
 // kernel partitions on its own and records the rows in the workspace and in `log`.
 int launch_fused_links(const r2_sim_desc *desc, const SimShape &s, void *const *rank_bufs, uint32_t step_begin,
@@ -627,20 +636,12 @@ int launch_fused_links(const r2_sim_desc *desc, const SimShape &s, void *const *
     const unsigned waves = s.R < kMaxFusedWaves ? s.R : kMaxFusedWaves;
     const dim3 grid((unsigned)(a.cols_per_chunk * s.S)), block(waves * kWave);
     const bool bf16 = desc->dtype == R2_BF16;
-    if (eb) {
-        if (unroll == 2) {
-            if (bf16) hipLaunchKernelGGL((ring_fused_links_partition_kernel<true, 2>), grid, block, lds, stream, a, s.tx_per_link, *eb);
-            else hipLaunchKernelGGL((ring_fused_links_partition_kernel<false, 2>), grid, block, lds, stream, a, s.tx_per_link, *eb);
-        } else {
-            if (bf16) hipLaunchKernelGGL((ring_fused_links_partition_kernel<true, 1>), grid, block, lds, stream, a, s.tx_per_link, *eb);
-            else hipLaunchKernelGGL((ring_fused_links_partition_kernel<false, 1>), grid, block, lds, stream, a, s.tx_per_link, *eb);
-        }
-    } else if (unroll == 2) {
-        if (bf16) hipLaunchKernelGGL((ring_fused_links_kernel<true, 2>), grid, block, lds, stream, a, s.tx_per_link);
-        else hipLaunchKernelGGL((ring_fused_links_kernel<false, 2>), grid, block, lds, stream, a, s.tx_per_link);
+    if (unroll == 2) {
+        if (bf16) launch_links<true, 2>(grid, block, lds, stream, a, s.tx_per_link, eb);
+        else launch_links<false, 2>(grid, block, lds, stream, a, s.tx_per_link, eb);
     } else {
-        if (bf16) hipLaunchKernelGGL((ring_fused_links_kernel<true, 1>), grid, block, lds, stream, a, s.tx_per_link);
-        else hipLaunchKernelGGL((ring_fused_links_kernel<false, 1>), grid, block, lds, stream, a, s.tx_per_link);
+        if (bf16) launch_links<true, 1>(grid, block, lds, stream, a, s.tx_per_link, eb);
+        else launch_links<false, 1>(grid, block, lds, stream, a, s.tx_per_link, eb);
     }
     return hip_rc(hipGetLastError());
 }
@@ -778,7 +779,8 @@ int plan_links(const r2_sim_desc *desc, const SimShape &s, const r2_epoch *const
             const uint64_t t = a[ia].t_start > b[ib].t_start ? a[ia].t_start : b[ib].t_start;
             if (t >= s.tx_per_link) break;  // never in force (and would run into the next link's block)
             uint32_t *w = plan.speed.data() + plan.link.size() * s.C;
-            for (uint32_t c = 0; c < s.C; ++c) w[c] = a[ia].weights[c] < b[ib].weights[c] ? a[ia].weights[c] : b[ib].weights[c];
+            for (uint32_t c = 0; c < s.C; ++c)
+                w[c] = a[ia].weights[c] < b[ib].weights[c] ? a[ia].weights[c] : b[ib].weights[c];
             const uint64_t mask = (a[ia].fail_mask | b[ib].fail_mask) & full;
             if (!any_healthy(w, mask, s.C)) return R2_ERR_NO_HEALTHY_CHANNEL;
             plan.link.push_back(r2_epoch{r * s.tx_per_link + t, mask, w});
@@ -825,9 +827,13 @@ extern "C" int r2_rails_resolve_schedule(const r2_sim_desc *desc, const r2_epoch
     SimShape s;
     int rc = shape_of(desc, s);
     if (rc) return rc;
-    LinkPlan plan;
-    if ((rc = plan_links(desc, s, rank_epochs, n_rank_epochs, plan))) return rc;
-    return plan.fused ? R2_SCHED_FUSED : R2_SCHED_STEPS;
+    try {
+        LinkPlan plan;
+        if ((rc = plan_links(desc, s, rank_epochs, n_rank_epochs, plan))) return rc;
+        return plan.fused ? R2_SCHED_FUSED : R2_SCHED_STEPS;
+    } catch (const std::bad_alloc &) {  // the merged epoch lists are host allocations; nothing may unwind into C
+        return R2_ERR_CAPACITY;
+    }
 }
 
 extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs,
@@ -842,35 +848,39 @@ extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs
         const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
         if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
     }
-    LinkPlan plan;
-    if ((rc = plan_links(desc, s, rank_epochs, n_rank_epochs, plan))) return rc;
-    if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
+    try {
+        LinkPlan plan;
+        if ((rc = plan_links(desc, s, rank_epochs, n_rank_epochs, plan))) return rc;
+        if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
 
-    // The fused kernels cut the chunks themselves when every link's states fit one argument block;
-    // otherwise, and for the step schedule, one partition launch makes all tables up front.
-    const bool self = plan.fused && plan.link.size() <= epochs_per_batch(s.C);
-    if (!self && s.n_tx &&
-        (rc = launch_partition_epochs(plan.link.data(), (uint32_t)plan.link.size(), s.C, desc->align, s.chunk_bytes,
-                                      s.n_tx, static_cast<uint64_t *>(workspace), offsets_log, (hipStream_t)stream)))
-        return rc;
-    if (s.chunk_bytes == 0) return R2_OK;
-    if (plan.fused) {
-        EpochBatch eb;
-        if (self) fill_batch(eb, plan.link.data(), 0, (uint32_t)plan.link.size(), s.C);
-        uint32_t j0 = 0;
-        for (uint32_t j = 1; j <= s.J; ++j)
-            if (j == s.J || plan.cut[j]) {
-                if ((rc = launch_fused_links(desc, s, rank_bufs, j0, j, workspace, self ? &eb : nullptr,
-                                             self ? offsets_log : nullptr, (hipStream_t)stream)))
-                    return rc;
-                j0 = j;
-            }
+        // The fused kernels cut the chunks themselves when every link's states fit one argument block;
+        // otherwise, and for the step schedule, one partition launch makes all tables up front.
+        const bool self = plan.fused && plan.link.size() <= epochs_per_batch(s.C);
+        if (!self && s.n_tx &&
+            (rc = launch_partition_epochs(plan.link.data(), (uint32_t)plan.link.size(), s.C, desc->align, s.chunk_bytes,
+                                          s.n_tx, static_cast<uint64_t *>(workspace), offsets_log, (hipStream_t)stream)))
+            return rc;
+        if (s.chunk_bytes == 0) return R2_OK;
+        if (plan.fused) {
+            EpochBatch eb;
+            if (self) fill_batch(eb, plan.link.data(), 0, (uint32_t)plan.link.size(), s.C);
+            uint32_t j0 = 0;
+            for (uint32_t j = 1; j <= s.J; ++j)
+                if (j == s.J || plan.cut[j]) {
+                    if ((rc = launch_fused_links(desc, s, rank_bufs, j0, j, workspace, self ? &eb : nullptr,
+                                                 self ? offsets_log : nullptr, (hipStream_t)stream)))
+                        return rc;
+                    j0 = j;
+                }
+            return R2_OK;
+        }
+        for (uint64_t p = 0; p < s.n_passes; ++p)
+            for (uint32_t j = 0; j < s.J; ++j)
+                if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
         return R2_OK;
+    } catch (const std::bad_alloc &) {
+        return R2_ERR_CAPACITY;
     }
-    for (uint64_t p = 0; p < s.n_passes; ++p)
-        for (uint32_t j = 0; j < s.J; ++j)
-            if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
-    return R2_OK;
 }
 
 extern "C" int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,

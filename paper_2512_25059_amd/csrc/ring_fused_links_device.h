@@ -66,7 +66,8 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
                 const uint32_t ti1 = next_begins - tg0 < n_t ? (uint32_t)(next_begins - tg0) : n_t;
                 const uint32_t weight = lane < C ? eb->weights[e * C + lane] : 0;
                 uint64_t W;
-                const uint64_t cut = partition_lane(weight, (eb->fail_mask[e] >> lane) & 1u, C, a.chunk_bytes, a.align, &W);
+                const bool failed = (eb->fail_mask[e] >> lane) & 1u;
+                const uint64_t cut = partition_lane(weight, failed, C, a.chunk_bytes, a.align, &W);
                 // the last channel whose cut point is at or before b0 (channel 0's is 0)
                 const uint32_t c0 = 63 - (uint32_t)__builtin_clzll(__ballot(lane < C && cut <= b0));
                 const uint64_t lo = __shfl(cut, c0, kWave);
@@ -152,7 +153,9 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
         uint64_t bu[U], din[U];
 #pragma unroll
         for (unsigned u = 0; u < U; ++u) bu[u] = b0 + (uint64_t)(u * kWave + lane) * 16;
-        auto local_of = [&](uint32_t j) { return my_slab + (uint64_t)((r + a.chunk_start + 2 * R - j) % R) * a.chunk_bytes; };
+        auto local_of = [&](uint32_t j) {  // the ring chunk of step j
+            return my_slab + (uint64_t)((r + a.chunk_start + 2 * R - j) % R) * a.chunk_bytes;
+        };
         auto reads_local = [&](uint32_t j) { return j == 0 || j <= a.sum_last; };  // copy-send, or a sum
         // bit i: the table of transmission t_first + i of the own link (the predecessor's) is not the
         // one before it.  With a wave per rank a launch has at most 2 * 16 - 2 transmissions.

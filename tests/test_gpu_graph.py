@@ -99,3 +99,54 @@ def test_split_run_in_a_graph(r2, oracle):
         for r in range(R):
             got = bufs[r].cpu().numpy().view(np.uint16)
             assert np.array_equal(got, want[r]), f"replay {replay}, rank {r}"
+
+
+@pytest.mark.parametrize("schedule", [1, 2])
+def test_rails_run_in_a_graph(r2, oracle, schedule):
+    """The ring with per-link tables merges the ranks' epoch lists on the host and then only launches:
+    captured and replayed under either schedule, with a table change on the way (a launch cut)."""
+    from oracle import rails
+
+    rng = np.random.default_rng(78)
+    R, C, N = 6, 8, 6 * 8 * 1100
+    xs = []
+    for _ in range(R):
+        x = torch.from_numpy(rng.standard_normal(N).astype(np.float32) * 0.02)
+        xs.append(x.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy())
+    w = [50000] * C
+    sched = rails.static_epochs(w, [0b1, 0b10, 0, 0b100, 0, 0b1000])
+    sched[2] = [(0, 0, w), (4, 0b00010000, w)]  # rank 2 loses a rail at transmission 4
+    want = oracle.expected(xs, oracle.BF16, 1, oracle.PHASE_AR)
+    o_bufs = [x.copy() for x in xs]
+    tables, _ = rails.ring_rails_sim(o_bufs, oracle.BF16, 1, C, 256, sched, oracle.PHASE_AR)
+    desc = r2.SimDesc(R, 1, C, 256, N, r2.BF16, r2.PHASE_AR | r2.PHASE_LINKS, 0, schedule)
+    assert r2.r2_rails_resolve_schedule(desc, sched) == schedule
+    pristine = [to_device(x) for x in xs]
+    bufs = [p.clone() for p in pristine]
+    ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    log = torch.zeros((R, 2 * R - 2, C + 1), dtype=torch.int64, device="cuda")
+
+    say(f"graph capture of the per-link ring, schedule={schedule}")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        r2.r2_ring_rails_sim(desc, bufs, sched, ws, log)  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        r2.r2_ring_rails_sim(desc, bufs, sched, ws, log)
+    for replay in range(3):
+        say(f"rails graph replay {replay}")
+        for b, p in zip(bufs, pristine):
+            b.copy_(p)
+        log.zero_()
+        junk = torch.randn(1 << 16, device="cuda").sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for r in range(R):
+            got = bufs[r].cpu().numpy().view(np.uint16)
+            assert np.array_equal(got, want[r]), f"replay {replay}, rank {r}"
+        assert log.cpu().numpy().view(np.uint64).tolist() == tables.tolist()
