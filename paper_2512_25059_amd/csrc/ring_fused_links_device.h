@@ -47,6 +47,16 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
 
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint32_t lane = threadIdx.x % kWave, n_waves = blockDim.x / kWave;
+    // A wave that plays one rank on a full-width column takes the fast path below.  If the launch
+    // starts at step 0 it begins by staging a chunk of its own buffer, whose address depends on
+    // nothing the prologue computes: loaded here, its latency passes while the tables are made.
+    const bool fast = R <= n_waves && b0 + kWidth <= a.chunk_bytes;
+    u32x4 pre[U] = {};
+    if (fast && a.j0 == 0) {
+        const uint64_t src = a.rank_buf[wave] + ((uint64_t)l * R + (wave + a.chunk_start) % R) * a.chunk_bytes + b0;
+#pragma unroll
+        for (unsigned u = 0; u < U; ++u) pre[u] = load16<kNtLocalLoad>(src + (uint64_t)(u * kWave + lane) * 16);
+    }
     uint32_t top = 0;  // the largest power of two below C (0 if C = 1)
     while ((top ? top * 2 : 1) < C) top = top ? top * 2 : 1;
     // ColInfo::pad of a row: it may differ from the row of the link's transmission before (always
@@ -139,13 +149,13 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
         return (uint64_t)c * a.cap - off[c] + b;
     };
 
-    if (R <= n_waves && b0 + kWidth <= a.chunk_bytes) {
-        // A wave that plays one rank on a full-width column.  Everything a step needs besides the
-        // incoming data is fetched off its critical path: the stage offsets it reads with were
-        // looked up during the step before (behind that step's stores), those it writes with are
-        // looked up while its loads are in flight, and the local chunk -- untouched until its step
-        // as long as the ring still sums -- was loaded a step ahead.  Two register sets alternate,
-        // so nothing is moved between steps; the barrier does not wait for loads.
+    if (fast) {
+        // Everything a step needs besides the incoming data is fetched off its critical path: the
+        // stage offsets it reads with were looked up during the step before (behind that step's
+        // stores), those it writes with are looked up while its loads are in flight, and the local
+        // chunk -- untouched until its step as long as the ring still sums -- was loaded a step
+        // ahead.  Two register sets alternate, so nothing is moved between steps; the barrier does
+        // not wait for loads.
         const uint32_t r = wave, peer = (r + R - 1) % R;
         const uint64_t my_slab = a.rank_buf[r] + (uint64_t)l * R * a.chunk_bytes;
         const uint64_t in0 = slab_stage + (uint64_t)peer * per_rank, out0 = slab_stage + (uint64_t)r * per_rank;
@@ -156,7 +166,6 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
         auto local_of = [&](uint32_t j) {  // the ring chunk of step j
             return my_slab + (uint64_t)((r + a.chunk_start + 2 * R - j) % R) * a.chunk_bytes;
         };
-        auto reads_local = [&](uint32_t j) { return j == 0 || j <= a.sum_last; };  // copy-send, or a sum
         // bit i: the table of transmission t_first + i of the own link (the predecessor's) is not the
         // one before it.  With a wave per rank a launch has at most 2 * 16 - 2 transmissions.
         static_assert(2 * kMaxFusedWaves - 2 < kWave, "one ballot must cover a launch's transmissions");
@@ -170,22 +179,32 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
         }
         uint32_t j = a.j0;
         R2_STAMP(3);
-        auto step = [&](u32x4(&cur)[U], u32x4(&nxt)[U]) {
-            const bool has_in = j > 0, has_out = j + 1 < a.J;
-            const bool summing = has_in && j <= a.sum_last;
+        // One step, its kind fixed at compile time so that the code is straight-line and the waits
+        // the compiler places count exactly the loads that variant issued (with a run-time "is the
+        // next local chunk loaded ahead" they would cover the worst case, and the load ahead would
+        // be waited for in the same step).  KIND: 0 copy-send (cur = the chunk, already loaded),
+        // 1 sum (cur = the local chunk, loaded a step ahead; AHEAD: load the next one into nxt),
+        // 2 copy (cur = where the incoming data goes: two sets alternate, so that a step's loads
+        // never wait until the previous step's stores have read their registers).
+        auto step = [&](auto kind_tag, auto out_tag, auto ahead_tag, u32x4(&cur)[U], u32x4(&nxt)[U]) {
+            constexpr int KIND = decltype(kind_tag)::value;
+            constexpr bool HAS_OUT = decltype(out_tag)::value, AHEAD = decltype(ahead_tag)::value;
             const uint64_t local_addr = local_of(j);
             u32x4 inc[U] = {};
-            if (has_in) {
+            if constexpr (KIND != 0) {
                 const uint64_t in_base = in0 + ((j + 1) & 1 ? parity_stride : 0);
 #pragma unroll
-                for (unsigned u = 0; u < U; ++u) inc[u] = load16<false>(in_base + din[u]);
+                for (unsigned u = 0; u < U; ++u) {
+                    if constexpr (KIND == 2) cur[u] = load16<false>(in_base + din[u]);
+                    else inc[u] = load16<false>(in_base + din[u]);
+                }
             }
-            if (j + 1 < a.j1 && reads_local(j + 1)) {
+            if constexpr (AHEAD) {
                 const uint64_t next_addr = local_of(j + 1);
 #pragma unroll
                 for (unsigned u = 0; u < U; ++u) nxt[u] = load16<kNtLocalLoad>(next_addr + bu[u]);
             }
-            if (has_out && j > t_first && ((out_changes >> (j - t_first)) & 1)) {
+            if (HAS_OUT && j > t_first && ((out_changes >> (j - t_first)) & 1)) {
 #pragma unroll
                 for (unsigned u = 0; u < U; ++u) dout[u] = stage_offset(r, j, bu[u]);
             }
@@ -193,11 +212,10 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
 #pragma unroll
             for (unsigned u = 0; u < U; ++u) {
                 u32x4 v;
-                if (!has_in) v = cur[u];
-                else if (!summing) v = inc[u];
-                else v = combine<BF16 ? kSumBF16 : kSumF32>(inc[u], cur[u]);
-                if (has_in) store16<kNtLocalStore>(local_addr + bu[u], v);
-                if (has_out) store16<false>(out_base + dout[u], v);
+                if constexpr (KIND == 1) v = combine<BF16 ? kSumBF16 : kSumF32>(inc[u], cur[u]);
+                else v = cur[u];
+                if constexpr (KIND != 0) store16<kNtLocalStore>(local_addr + bu[u], v);
+                if constexpr (HAS_OUT) store16<false>(out_base + dout[u], v);
             }
             // step j+1 reads what the predecessor stages at this step
             if (j + 1 < a.j1 && j > t_first && ((in_changes >> (j - t_first)) & 1)) {
@@ -208,17 +226,46 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
             R2_STAMP(4 + j);
             ++j;
         };
+        using Send = std::integral_constant<int, 0>;
+        using Sum = std::integral_constant<int, 1>;
+        using Copy = std::integral_constant<int, 2>;
+        using Yes = std::integral_constant<bool, true>;
+        using No = std::integral_constant<bool, false>;
         u32x4 set_a[U] = {}, set_b[U] = {};
-        if (reads_local(j)) {
+        // The steps [j, j_end), all sums that stage onward or all sums that do not: the first loads
+        // its local chunk itself, every other finds it loaded by the step before.
+        auto sums = [&](auto out_tag, uint32_t j_end) {
+            if (j >= j_end) return;
             const uint64_t first_addr = local_of(j);
 #pragma unroll
             for (unsigned u = 0; u < U; ++u) set_a[u] = load16<kNtLocalLoad>(first_addr + bu[u]);
-        }
-        while (j < a.j1) {
-            step(set_a, set_b);
-            if (j >= a.j1) break;
-            step(set_b, set_a);
-        }
+            for (;;) {
+                if (j + 1 >= j_end) {
+                    step(Sum{}, out_tag, No{}, set_a, set_b);
+                    break;
+                }
+                step(Sum{}, out_tag, Yes{}, set_a, set_b);
+                if (j + 1 >= j_end) {
+                    step(Sum{}, out_tag, No{}, set_b, set_a);
+                    break;
+                }
+                step(Sum{}, out_tag, Yes{}, set_b, set_a);
+            }
+        };
+        auto copies = [&](auto out_tag, uint32_t j_end) {
+            while (j < j_end) {
+                step(Copy{}, out_tag, No{}, set_a, set_b);
+                if (j >= j_end) break;
+                step(Copy{}, out_tag, No{}, set_b, set_a);
+            }
+        };
+        const uint32_t last = a.J - 1;  // the one step that stages nothing
+        const uint32_t sum_end = a.sum_last + 1 < a.j1 ? a.sum_last + 1 : a.j1;  // sums are steps 1..sum_last
+        if (j == 0) step(Send{}, Yes{}, No{}, pre, set_b);  // the chunk was loaded before the tables were made
+        sums(Yes{}, sum_end < last ? sum_end : last);
+        sums(No{}, sum_end);
+        copies(Yes{}, a.j1 < last ? a.j1 : last);
+        copies(No{}, a.j1);
         record_rows();
         return;
     }
