@@ -620,18 +620,26 @@ def r2_sendrecv_sim(desc: SimDesc, send_bufs: Sequence, recv_bufs: Sequence, epo
     _check(rc, "r2_sendrecv_sim")
 
 
+def _rails_lists(desc: SimDesc, rank_epochs: Sequence, who: str):
+    """The per-rank epoch lists as the C side takes them: (arrays to keep alive, list pointers, list lengths)."""
+    if len(rank_epochs) != desc.n_ranks:
+        raise ValueError(f"{who}: one epoch list per rank")
+    if any(len(w) != desc.n_channels for eps in rank_epochs for _, _, w in eps):
+        raise ValueError(f"{who}: one weight per channel in every epoch")
+    lists = [_epoch_array(eps) for eps in rank_epochs]
+    ptrs = (C.c_void_p * len(lists))(*[C.cast(a, C.c_void_p) for a, _ in lists])
+    counts = (C.c_uint32 * len(lists))(*[len(eps) for eps in rank_epochs])
+    return lists, ptrs, counts
+
+
 def r2_ring_rails_sim(desc: SimDesc, rank_bufs: Sequence, rank_epochs: Sequence, workspace,
                       offsets_log: Optional[torch.Tensor] = None, stream=None,
                       workspace_bytes: Optional[int] = None) -> None:
     """rank_epochs[r]: the epoch list [(t_start, fail_mask, weights), ...] of rank r."""
-    if len(rank_epochs) != desc.n_ranks or len(rank_bufs) != desc.n_ranks:
-        raise ValueError("r2_ring_rails_sim: one epoch list and one buffer per rank")
-    if any(len(w) != desc.n_channels for eps in rank_epochs for _, _, w in eps):
-        raise ValueError("r2_ring_rails_sim: one weight per channel in every epoch")
+    if len(rank_bufs) != desc.n_ranks:
+        raise ValueError("r2_ring_rails_sim: one buffer per rank")
+    lists, ptrs, counts = _rails_lists(desc, rank_epochs, "r2_ring_rails_sim")
     arr, p = _ptr_array(rank_bufs)
-    lists = [_epoch_array(eps) for eps in rank_epochs]
-    ptrs = (C.c_void_p * len(lists))(*[C.cast(a, C.c_void_p) for a, _ in lists])
-    counts = (C.c_uint32 * len(lists))(*[len(eps) for eps in rank_epochs])
     wp, wb = _ws(workspace, workspace_bytes)
     rc = load_library().r2_ring_rails_sim(C.byref(desc.c()), p, C.cast(ptrs, C.c_void_p), C.cast(counts, C.c_void_p),
                                           wp, wb, _ptr(offsets_log), _stream(stream))
@@ -640,13 +648,7 @@ def r2_ring_rails_sim(desc: SimDesc, rank_bufs: Sequence, rank_epochs: Sequence,
 
 
 def r2_rails_resolve_schedule(desc: SimDesc, rank_epochs: Sequence) -> int:
-    if len(rank_epochs) != desc.n_ranks:
-        raise ValueError("r2_rails_resolve_schedule: one epoch list per rank")
-    if any(len(w) != desc.n_channels for eps in rank_epochs for _, _, w in eps):
-        raise ValueError("r2_rails_resolve_schedule: one weight per channel in every epoch")
-    lists = [_epoch_array(eps) for eps in rank_epochs]
-    ptrs = (C.c_void_p * len(lists))(*[C.cast(a, C.c_void_p) for a, _ in lists])
-    counts = (C.c_uint32 * len(lists))(*[len(eps) for eps in rank_epochs])
+    lists, ptrs, counts = _rails_lists(desc, rank_epochs, "r2_rails_resolve_schedule")
     rc = load_library().r2_rails_resolve_schedule(C.byref(desc.c()), C.cast(ptrs, C.c_void_p), C.cast(counts, C.c_void_p))
     del lists
     if rc < 0:
@@ -659,16 +661,12 @@ class RailsCall:
 
     def __init__(self, desc: SimDesc, rank_bufs: Sequence, rank_epochs: Sequence, workspace,
                  offsets_log: Optional[torch.Tensor] = None, stream=None, workspace_bytes: Optional[int] = None):
-        if len(rank_epochs) != desc.n_ranks or len(rank_bufs) != desc.n_ranks:
-            raise ValueError("RailsCall: one epoch list and one buffer per rank")
-        if any(len(w) != desc.n_channels for eps in rank_epochs for _, _, w in eps):
-            raise ValueError("RailsCall: one weight per channel in every epoch")
+        if len(rank_bufs) != desc.n_ranks:
+            raise ValueError("RailsCall: one buffer per rank")
+        self._lists, self._ptrs, self._counts = _rails_lists(desc, rank_epochs, "RailsCall")
         self._fn = load_library().r2_ring_rails_sim
         self._desc = desc.c()
         self._bufs, bufs_p = _ptr_array(rank_bufs)
-        self._lists = [_epoch_array(eps) for eps in rank_epochs]
-        self._ptrs = (C.c_void_p * len(self._lists))(*[C.cast(a, C.c_void_p) for a, _ in self._lists])
-        self._counts = (C.c_uint32 * len(self._lists))(*[len(eps) for eps in rank_epochs])
         wp, wb = _ws(workspace, workspace_bytes)
         self._refs = (rank_bufs, workspace, offsets_log)  # keep the device memory alive
         self._args = (C.byref(self._desc), bufs_p, C.cast(self._ptrs, C.c_void_p), C.cast(self._counts, C.c_void_p),
