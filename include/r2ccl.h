@@ -281,13 +281,14 @@ int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint64_t pass, 
  * overwrite stage data that another column has not read yet.  (An epoch starting at step c of a
  * slab therefore needs a launch boundary before step c and one before step c+1;
  * r2_ring_allreduce_sim places them.)  The caller is trusted on this.  Needs the tables of
- * r2_sim_prepare and chunk sizes that are a multiple of 16 bytes (R2_ERR_INVALID otherwise). */
+ * r2_sim_prepare and chunk sizes that are a multiple of 16 bytes (R2_ERR_INVALID otherwise; also for
+ * R2_PHASE_LINKS, whose fused launches only r2_ring_rails_sim issues). */
 int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step_begin,
                        uint32_t step_end, void *workspace, uint64_t workspace_bytes, void *stream);
 
 /* Which schedule r2_ring_allreduce_sim will use for this descriptor and epoch list: R2_SCHED_STEPS
- * or R2_SCHED_FUSED (desc->schedule itself unless that is R2_SCHED_AUTO), or a negative R2_ERR code.
- * Host arithmetic only. */
+ * or R2_SCHED_FUSED (desc->schedule itself unless that is R2_SCHED_AUTO), or a negative R2_ERR code
+ * (R2_ERR_INVALID for R2_PHASE_LINKS: ask r2_rails_resolve_schedule).  Host arithmetic only. */
 int r2_sim_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs);
 
 /* r2_sim_prepare, then the whole collective that desc->phases names, in place on the rank buffers, by
