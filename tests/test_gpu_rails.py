@@ -189,6 +189,24 @@ def test_rails_failure_and_recovery_at_one_server(r2, oracle):
     _run(r2, oracle, _inputs(rng, 4, 2 * 4 * 8 * 1500, "bf16"), "bf16", "ar", 2, 4, 256, w, None, 0, True, sched)
 
 
+def test_rails_changes_at_both_ends_at_slab_starts_and_beyond_the_run(r2, oracle):
+    """Neighbours change state at the same transmission (one link epoch, not two), a state begins exactly
+    where a slab begins (no launch cut needed: the slab's stage buffers are its own), and an epoch that
+    starts after the last transmission is never in force."""
+    rng = np.random.default_rng(924)
+    R, S, C = 4, 3, 4
+    T = 2 * R - 2  # transmissions per slab
+    w, fast = [50000] * C, [50000, 100000, 25000, 50000]
+    sched = [[(0, 0, w)] for _ in range(R)]
+    sched[0] = [(0, 0, w), (T, 0b0001, w), (2 * T, 0, fast)]              # changes only where slabs begin
+    sched[1] = [(0, 0, w), (2, 0b0100, w), (T + 3, 0, w), (S * T + 5, 0b1111, w)]  # the last one never applies
+    sched[2] = [(0, 0, w), (2, 0b1000, fast), (T + 3, 0b0010, w)]         # same transmissions as rank 1
+    for dtype in ("f32", "bf16"):
+        say(f"rails: simultaneous changes, slab-start changes, {dtype}")
+        ran = _run(r2, oracle, _inputs(rng, R, S * R * 8 * 350, dtype), dtype, "ar", S, C, 64, w, None, 0, True, sched)
+        assert r2.SCHED_FUSED in ran and r2.SCHED_STEPS in ran
+
+
 def test_rails_call_marshalled_once(r2, oracle):
     """RailsCall issues the same call from arguments marshalled once: two runs on fresh inputs, same bits."""
     rng = np.random.default_rng(923)
