@@ -5,13 +5,9 @@
 // R2CCL paper: Sec. 2.1 (GPU kernels execute the collective over channels), Sec. 4.3 Technique II
 // (per-NIC send staging buffers, chunk-granular progress), Sec. 5.2 (ring all-reduce = reduce-scatter,
 // then all-gather), Sec. 5 and 5.1 (the other collectives keep their schedule under R2CCL-Balance),
-// Sec. 6 (servers that lost different rails).
-#include <new>
-#include <vector>
-
-#include "reduce_copy_device.h"
-#include "ring_fused_device.h"
-#include "ring_fused_links_device.h"
+// Sec. 6 (servers that lost different rails: the step kernel picks its tables per link; the host side
+// of that ring is in rails.hip).
+#include "sim_shape.h"
 
 namespace r2 {
 namespace {
@@ -123,115 +119,11 @@ unsigned blocks_for(uint64_t range_bytes)
     return (unsigned)(want < limit ? want : limit);
 }
 
-bool valid_dtype(int d) { return d == R2_F32 || d == R2_BF16; }
-uint64_t elem_bytes(int d) { return d == R2_F32 ? 4 : 2; }
-
 Mode mode_of(bool has_in, int op, int dtype)
 {
     if (!has_in) return kSend;
     if (op == R2_OP_COPY) return kCopy;
     return dtype == R2_F32 ? kSumF32 : kSumBF16;
-}
-
-// The stage bytes one launch writes are read back by the next launch.  Keeping that window well
-// inside the 256 MiB Infinity Cache lets the read be served from it.
-constexpr uint64_t kDefaultStageWindow = 128ull << 20;
-
-// R2_SCHED_AUTO picks the fused-column schedule when one ring step moves at most this many bytes
-// per stream (summed over ranks and slabs): below it a launch per step is launch-bound.
-constexpr uint64_t kFusedAutoBytes = 8ull << 20;
-
-struct SimShape {
-    uint32_t R, S, C, J, T_slab;
-    uint64_t chunk_bytes, cap, n_tx;
-    uint64_t tables_bytes, stage_off, total_bytes;
-    // passes: the run is cut into groups of slabs, or one slab's chunks into byte ranges
-    uint32_t slabs_per_pass, n_sub;
-    uint64_t sub_bytes, n_passes;
-    // What the run is.  Everything but the ring moves one message chunk per slab; the chains have one
-    // rank active per step, the point-to-point kinds two steps and separate receive buffers.
-    enum Kind { kRing, kSendRecv, kBroadcast, kReduce, kAllToAll } kind;
-    uint32_t root;        // chains
-    bool links;           // ring whose links have tables of their own (block r: r -> r+1), one row per transmission
-    uint64_t tx_per_link; // transmissions of one rank: S * T_slab
-    uint32_t a2a_chunks;  // all-to-all: the caller's chunks per block (S = (R-1) * a2a_chunks)
-    bool two_lists() const { return kind == kSendRecv || kind == kAllToAll; }
-    bool chain() const { return kind == kBroadcast || kind == kReduce; }
-    uint32_t active() const { return chain() ? 1 : R; }  // ranks at work in one step
-};
-
-uint64_t round_up(uint64_t x, uint64_t m) { return (x + m - 1) / m * m; }
-
-// Validates a descriptor and derives the sizes; returns an R2 code.
-int shape_of(const r2_sim_desc *d, SimShape &s)
-{
-    if (!d) return R2_ERR_INVALID;
-    if (d->n_ranks < 2 || d->n_ranks > R2_MAX_RANKS) return R2_ERR_INVALID;
-    if (d->n_channels == 0 || d->n_channels > R2_MAX_CHANNELS) return R2_ERR_INVALID;
-    if (d->n_slabs == 0) return R2_ERR_INVALID;
-    if (d->align == 0 || d->align % 16 != 0) return R2_ERR_INVALID;
-    if (!valid_dtype(d->dtype)) return R2_ERR_INVALID;
-    s.links = (d->phases & R2_PHASE_LINKS) != 0;
-    switch (d->phases & ~R2_PHASE_LINKS) {
-    case R2_PHASE_RS:
-    case R2_PHASE_AG:
-    case R2_PHASE_RS | R2_PHASE_AG: s.kind = SimShape::kRing; break;
-    case R2_PHASE_SENDRECV: s.kind = SimShape::kSendRecv; break;
-    case R2_PHASE_BROADCAST: s.kind = SimShape::kBroadcast; break;
-    case R2_PHASE_REDUCE: s.kind = SimShape::kReduce; break;
-    case R2_PHASE_ALLTOALL: s.kind = SimShape::kAllToAll; break;
-    default: return R2_ERR_INVALID;
-    }
-    if (d->schedule != R2_SCHED_AUTO && d->schedule != R2_SCHED_STEPS && d->schedule != R2_SCHED_FUSED)
-        return R2_ERR_INVALID;
-    if (s.links && s.kind != SimShape::kRing) return R2_ERR_INVALID;
-    if (s.kind != SimShape::kRing && d->schedule == R2_SCHED_FUSED) return R2_ERR_INVALID;
-    const int ring_phases = d->phases & ~R2_PHASE_LINKS;
-    if (s.chain() ? (d->root < 0 || (uint32_t)d->root >= d->n_ranks) : d->root != 0) return R2_ERR_INVALID;
-    s.R = d->n_ranks;
-    s.root = (uint32_t)d->root;
-    s.a2a_chunks = s.kind == SimShape::kAllToAll ? d->n_slabs : 0;
-    // slabs as the schedule sees them: all-to-all has one per round and message chunk
-    const uint64_t slabs = s.a2a_chunks ? (uint64_t)(s.R - 1) * d->n_slabs : d->n_slabs;
-    if (slabs * s.R > 65535) return R2_ERR_INVALID;
-    const bool blocks = s.kind == SimShape::kRing || s.kind == SimShape::kAllToAll;  // R pieces per slab
-    const uint64_t per = blocks ? (uint64_t)d->n_slabs * s.R : d->n_slabs;
-    if (d->n_elems % per != 0) return R2_ERR_INVALID;
-    if (d->n_elems > (1ull << 60)) return R2_ERR_OVERFLOW;
-    s.S = (uint32_t)slabs;
-    s.C = d->n_channels;
-    s.J = s.two_lists() ? 2 : ring_phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
-    s.T_slab = s.J - 1;
-    s.chunk_bytes = d->n_elems / per * elem_bytes(d->dtype);
-    s.cap = round_up(s.chunk_bytes ? s.chunk_bytes : 1, 256);
-    s.tx_per_link = (uint64_t)s.S * s.T_slab;
-    s.n_tx = s.links ? s.R * s.tx_per_link : s.tx_per_link;  // rows of the tables
-    s.tables_bytes = round_up(s.n_tx * (s.C + 1) * 8, 256);
-    s.stage_off = s.tables_bytes;
-    const unsigned __int128 stage = (unsigned __int128)2 * s.R * s.S * s.C * s.cap;
-    if (stage > ((unsigned __int128)1 << 62)) return R2_ERR_OVERFLOW;
-    s.total_bytes = s.stage_off + (uint64_t)stage;
-
-    // The two-step exchanges use one stage parity only, so twice as much fits the same cache footprint.
-    const uint64_t window = d->stage_window_bytes ? d->stage_window_bytes
-                            : s.two_lists()       ? 2 * kDefaultStageWindow
-                                                  : kDefaultStageWindow;
-    const uint64_t per_slab = (uint64_t)s.active() * s.chunk_bytes;  // stage bytes a step writes per slab
-    if (per_slab > window) {
-        const uint64_t tile_bytes = (uint64_t)kThreads * kUnroll * 16;
-        const uint64_t parts = (per_slab + window - 1) / window;
-        s.slabs_per_pass = 1;
-        s.sub_bytes = round_up((s.chunk_bytes + parts - 1) / parts, tile_bytes);
-        s.n_sub = (uint32_t)((s.chunk_bytes + s.sub_bytes - 1) / s.sub_bytes);
-        s.n_passes = (uint64_t)s.S * s.n_sub;
-    } else {
-        const uint64_t fit = per_slab ? window / per_slab : s.S;
-        s.slabs_per_pass = (uint32_t)(fit < 1 ? 1 : (fit > s.S ? s.S : fit));
-        s.sub_bytes = s.chunk_bytes;
-        s.n_sub = 1;
-        s.n_passes = (s.S + s.slabs_per_pass - 1) / s.slabs_per_pass;
-    }
-    return R2_OK;
 }
 
 int check_epochs(const r2_epoch *epochs, uint32_t n, const SimShape &s)
@@ -248,35 +140,13 @@ int check_epochs(const r2_epoch *epochs, uint32_t n, const SimShape &s)
     return R2_OK;
 }
 
-int check_workspace(const void *ws, uint64_t ws_bytes, const SimShape &s)
-{
-    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return R2_ERR_INVALID;
-    if (ws_bytes < s.total_bytes) return R2_ERR_CAPACITY;
-    return R2_OK;
-}
+// The plain ring's fused columns: not for per-link tables (rails.hip has those).
+bool fused_eligible(const SimShape &s) { return !s.links && columns_fit(s); }
 
 template <Mode M, bool HAS_OUT, bool KEEP = false>
 void launch_step(const StepArgs &a, dim3 grid, hipStream_t st)
 {
     hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT, KEEP>), grid, dim3(kThreads), 0, st, a);
-}
-
-// The fused-column schedule needs whole 16-byte vectors everywhere and a grid that fits.
-bool columns_fit(const SimShape &s)
-{
-    if (s.kind != SimShape::kRing) return false;
-    if (s.chunk_bytes == 0 || s.chunk_bytes % 16 != 0) return false;
-    const uint64_t cols = (s.chunk_bytes + kNarrowColBytes - 1) / kNarrowColBytes;
-    return cols * s.S <= 0x7fffffffull;
-}
-
-bool fused_eligible(const SimShape &s) { return !s.links && columns_fit(s); }
-
-// Vectors per lane of a run's columns (see kWideColumnsFrom).
-unsigned fused_col_unroll(const SimShape &s)
-{
-    const uint64_t wide = (s.chunk_bytes + 2 * kNarrowColBytes - 1) / (2 * kNarrowColBytes);
-    return wide * s.S >= kWideColumnsFrom ? 2 : 1;
 }
 
 // Decides between one launch per step and fused columns, and marks the steps before which a fused
@@ -585,67 +455,6 @@ int launch_fused(const r2_sim_desc *desc, const SimShape &s, void *const *rank_b
     return hip_rc(hipGetLastError());
 }
 
-// Dynamic LDS of a fused launch over the steps [step_begin, step_end) of a ring with per-link tables:
-// the rows of every link plus one ColInfo per row; 0 if that does not fit.
-uint32_t links_lds_bytes(const SimShape &s, uint32_t step_begin, uint32_t step_end)
-{
-    const uint32_t t_first = step_begin ? step_begin - 1 : 0;
-    const uint32_t t_end = step_end < s.T_slab ? step_end : s.T_slab;
-    if (t_end <= t_first) return 0;
-    const uint64_t bytes = (uint64_t)s.R * (t_end - t_first) * ((s.C + 1) * 8 + sizeof(ColInfo));
-    return bytes <= kLinksLdsBytes ? (uint32_t)bytes : 0;
-}
-
-template <bool BF16, unsigned U>
-void launch_links(dim3 grid, dim3 block, uint32_t lds, hipStream_t st, const FusedArgs &a, uint64_t link_rows,
-                  const EpochBatch *eb)
-{
-    if (eb) hipLaunchKernelGGL((ring_fused_links_partition_kernel<BF16, U>), grid, block, lds, st, a, link_rows, *eb);
-    else hipLaunchKernelGGL((ring_fused_links_kernel<BF16, U>), grid, block, lds, st, a, link_rows);
-}
-
-// One fused launch of a ring with per-link tables.  With `eb` (the links' states on one axis) the
-// kernel partitions on its own and records the rows in the workspace and in `log`.
-int launch_fused_links(const r2_sim_desc *desc, const SimShape &s, void *const *rank_bufs, uint32_t step_begin,
-                       uint32_t step_end, void *workspace, const EpochBatch *eb, uint64_t *log, hipStream_t stream)
-{
-    FusedArgs a{};
-    for (uint32_t r = 0; r < s.R; ++r) a.rank_buf[r] = reinterpret_cast<uint64_t>(rank_bufs[r]);  // checked by the caller
-    a.tables = static_cast<const uint64_t *>(workspace);
-    a.tables_out = static_cast<uint64_t *>(workspace);
-    a.log_out = log;
-    a.align = desc->align;
-    a.stage = reinterpret_cast<uint64_t>(workspace) + s.stage_off;
-    a.chunk_bytes = s.chunk_bytes;
-    a.cap = s.cap;
-    const unsigned unroll = fused_col_unroll(s);
-    const uint64_t col_bytes = (uint64_t)kNarrowColBytes * unroll;
-    a.cols_per_chunk = (s.chunk_bytes + col_bytes - 1) / col_bytes;
-    a.R = s.R;
-    a.S = s.S;
-    a.C = s.C;
-    a.J = s.J;
-    a.T_slab = s.T_slab;
-    const int ring_phases = desc->phases & ~R2_PHASE_LINKS;
-    a.chunk_start = ring_phases == R2_PHASE_AG ? 1 : 0;
-    a.sum_last = ring_phases == R2_PHASE_AG ? 0 : s.R - 1;
-    a.j0 = step_begin;
-    a.j1 = step_end;
-    const uint32_t lds = links_lds_bytes(s, step_begin, step_end);
-    if (!lds) return R2_ERR_INVALID;
-    const unsigned waves = s.R < kMaxFusedWaves ? s.R : kMaxFusedWaves;
-    const dim3 grid((unsigned)(a.cols_per_chunk * s.S)), block(waves * kWave);
-    const bool bf16 = desc->dtype == R2_BF16;
-    if (unroll == 2) {
-        if (bf16) launch_links<true, 2>(grid, block, lds, stream, a, s.tx_per_link, eb);
-        else launch_links<false, 2>(grid, block, lds, stream, a, s.tx_per_link, eb);
-    } else {
-        if (bf16) launch_links<true, 1>(grid, block, lds, stream, a, s.tx_per_link, eb);
-        else launch_links<false, 1>(grid, block, lds, stream, a, s.tx_per_link, eb);
-    }
-    return hip_rc(hipGetLastError());
-}
-
 }  // namespace
 }  // namespace r2
 
@@ -737,150 +546,6 @@ extern "C" int r2_collective_sim(const r2_sim_desc *desc, void *const *rank_bufs
                                  uint64_t *offsets_log, void *stream)
 {
     return r2_ring_allreduce_sim(desc, rank_bufs, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream);
-}
-
-namespace r2 {
-namespace {
-
-// What r2_ring_rails_sim derives from the ranks' epoch lists before it launches anything.
-struct LinkPlan {
-    std::vector<uint32_t> speed;  // the weights the link epochs point to
-    std::vector<r2_epoch> link;   // the links' epoch lists, strung together on one axis
-    bool cut[2 * R2_MAX_RANKS];   // fused launches end before these steps
-    bool fused;
-};
-
-// The schedule of the link r -> r+1: it changes whenever either end's does; a channel is down if
-// either end has it down, and as fast as the slower end.  The links' tables lie one block after the
-// other, so their schedules are strung together on one axis (block r starts at row r * tx_per_link)
-// and partitioned in one go.  Also decides the schedule, like plan_schedule for the plain ring.
-int plan_links(const r2_sim_desc *desc, const SimShape &s, const r2_epoch *const *rank_epochs,
-               const uint32_t *n_rank_epochs, LinkPlan &plan)
-{
-    if (!s.links || !rank_epochs || !n_rank_epochs) return R2_ERR_INVALID;
-    for (uint32_t r = 0; r < s.R; ++r) {
-        const r2_epoch *e = rank_epochs[r];
-        const uint32_t n = n_rank_epochs[r];
-        if (!e || n == 0 || e[0].t_start != 0) return R2_ERR_INVALID;
-        for (uint32_t i = 0; i < n; ++i)
-            if (!e[i].weights || (i && e[i].t_start <= e[i - 1].t_start)) return R2_ERR_INVALID;
-    }
-    const uint64_t full = s.C == 64 ? ~0ull : ((1ull << s.C) - 1);
-    size_t n_all = 0;
-    for (uint32_t r = 0; r < s.R; ++r) n_all += (size_t)n_rank_epochs[r] + n_rank_epochs[(r + 1) % s.R];
-    plan.speed.assign(n_all * s.C, 0);  // never grows again: the epochs point into it
-    plan.link.clear();
-    plan.link.reserve(n_all);
-    for (uint32_t r = 0; r < s.R; ++r) {
-        const r2_epoch *a = rank_epochs[r], *b = rank_epochs[(r + 1) % s.R];
-        const uint32_t na = n_rank_epochs[r], nb = n_rank_epochs[(r + 1) % s.R];
-        uint32_t ia = 0, ib = 0;
-        for (;;) {
-            const uint64_t t = a[ia].t_start > b[ib].t_start ? a[ia].t_start : b[ib].t_start;
-            if (t >= s.tx_per_link) break;  // never in force (and would run into the next link's block)
-            uint32_t *w = plan.speed.data() + plan.link.size() * s.C;
-            for (uint32_t c = 0; c < s.C; ++c)
-                w[c] = a[ia].weights[c] < b[ib].weights[c] ? a[ia].weights[c] : b[ib].weights[c];
-            const uint64_t mask = (a[ia].fail_mask | b[ib].fail_mask) & full;
-            if (!any_healthy(w, mask, s.C)) return R2_ERR_NO_HEALTHY_CHANNEL;
-            plan.link.push_back(r2_epoch{r * s.tx_per_link + t, mask, w});
-            // the next change at either end
-            const uint64_t next_a = ia + 1 < na ? a[ia + 1].t_start : ~0ull;
-            const uint64_t next_b = ib + 1 < nb ? b[ib + 1].t_start : ~0ull;
-            if (next_a == ~0ull && next_b == ~0ull) break;
-            if (next_a <= next_b) ++ia;
-            if (next_b <= next_a) ++ib;
-        }
-    }
-    // Fused columns, as in the plain ring: a link whose table changes at step c of some slab forces a
-    // launch boundary before step c and before step c+1; every launch's rows must fit LDS.
-    uint32_t n_cuts = 0;
-    for (bool &c : plan.cut) c = false;
-    for (const r2_epoch &e : plan.link) {
-        const uint32_t c = (uint32_t)(e.t_start % s.tx_per_link % s.T_slab);
-        if (c == 0) continue;  // the link's first, or a slab starts here: its stage buffers are its own
-        for (uint32_t j = c; j <= c + 1 && j < s.T_slab; ++j)
-            if (!plan.cut[j]) {
-                plan.cut[j] = true;
-                ++n_cuts;
-            }
-    }
-    plan.fused = desc->schedule != R2_SCHED_STEPS && columns_fit(s);
-    for (uint32_t j = 1, j0 = 0; j <= s.J && plan.fused; ++j)
-        if (j == s.J || plan.cut[j]) {
-            plan.fused = links_lds_bytes(s, j0, j) != 0;
-            j0 = j;
-        }
-    if (desc->schedule == R2_SCHED_FUSED && s.chunk_bytes && !plan.fused) return R2_ERR_INVALID;
-    if (desc->schedule == R2_SCHED_AUTO)  // launch-bound sizes only, and only if it saves launches
-        plan.fused = plan.fused && (uint64_t)s.R * s.S * s.chunk_bytes <= kFusedAutoBytes &&
-                     (uint64_t)(n_cuts + 1) * 2 <= s.n_passes * s.J;
-    return R2_OK;
-}
-
-}  // namespace
-}  // namespace r2
-
-extern "C" int r2_rails_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *const *rank_epochs,
-                                         const uint32_t *n_rank_epochs)
-{
-    SimShape s;
-    int rc = shape_of(desc, s);
-    if (rc) return rc;
-    try {
-        LinkPlan plan;
-        if ((rc = plan_links(desc, s, rank_epochs, n_rank_epochs, plan))) return rc;
-        return plan.fused ? R2_SCHED_FUSED : R2_SCHED_STEPS;
-    } catch (const std::bad_alloc &) {  // the merged epoch lists are host allocations; nothing may unwind into C
-        return R2_ERR_CAPACITY;
-    }
-}
-
-extern "C" int r2_ring_rails_sim(const r2_sim_desc *desc, void *const *rank_bufs,
-                                 const r2_epoch *const *rank_epochs, const uint32_t *n_rank_epochs,
-                                 void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log, void *stream)
-{
-    SimShape s;
-    int rc = shape_of(desc, s);
-    if (rc) return rc;
-    if (!s.links || !rank_bufs) return R2_ERR_INVALID;
-    for (uint32_t r = 0; r < s.R; ++r) {
-        const uint64_t p = reinterpret_cast<uint64_t>(rank_bufs[r]);
-        if (s.chunk_bytes && (!p || (p & 15u))) return R2_ERR_INVALID;
-    }
-    try {
-        LinkPlan plan;
-        if ((rc = plan_links(desc, s, rank_epochs, n_rank_epochs, plan))) return rc;
-        if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
-
-        // The fused kernels cut the chunks themselves when every link's states fit one argument block;
-        // otherwise, and for the step schedule, one partition launch makes all tables up front.
-        const bool self = plan.fused && plan.link.size() <= epochs_per_batch(s.C);
-        if (!self && s.n_tx &&
-            (rc = launch_partition_epochs(plan.link.data(), (uint32_t)plan.link.size(), s.C, desc->align, s.chunk_bytes,
-                                          s.n_tx, static_cast<uint64_t *>(workspace), offsets_log, (hipStream_t)stream)))
-            return rc;
-        if (s.chunk_bytes == 0) return R2_OK;
-        if (plan.fused) {
-            EpochBatch eb;
-            if (self) fill_batch(eb, plan.link.data(), 0, (uint32_t)plan.link.size(), s.C);
-            uint32_t j0 = 0;
-            for (uint32_t j = 1; j <= s.J; ++j)
-                if (j == s.J || plan.cut[j]) {
-                    if ((rc = launch_fused_links(desc, s, rank_bufs, j0, j, workspace, self ? &eb : nullptr,
-                                                 self ? offsets_log : nullptr, (hipStream_t)stream)))
-                        return rc;
-                    j0 = j;
-                }
-            return R2_OK;
-        }
-        for (uint64_t p = 0; p < s.n_passes; ++p)
-            for (uint32_t j = 0; j < s.J; ++j)
-                if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
-        return R2_OK;
-    } catch (const std::bad_alloc &) {
-        return R2_ERR_CAPACITY;
-    }
 }
 
 extern "C" int r2_sendrecv_sim(const r2_sim_desc *desc, const void *const *send_bufs, void *const *recv_bufs,
