@@ -270,15 +270,20 @@ def split_line(r2, torch, np, wl, out=sys.stderr):
           f"({alg} algorithmic bytes)", file=out, flush=True)
 
 
-def _time_calls(torch, fn, n=20, warm=3):
+def _time_calls(torch, fn, n=20, warm=3, rounds=3):
+    """Seconds per call: `rounds` runs of n back-to-back calls each, the median run (one stall of the
+    host or the box inside a 20-call run would otherwise be the figure)."""
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n):
-        fn()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / n
+    runs = []
+    for _ in range(rounds):
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        runs.append((time.perf_counter() - t0) / n)
+    return sorted(runs)[len(runs) // 2]
 
 
 def other_collectives_lines(r2, torch, np, wl, out=sys.stderr):
