@@ -418,7 +418,8 @@ def recursive_line(r2, torch, np, wl, out=sys.stderr):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=200,
+                    help="timed steps (default: 0.2 s of cfg2, so that one stall of the host or the box weighs little)")
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg4 or cfg5_tok{1,16,64,256}")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -466,7 +467,7 @@ def main() -> int:
     # says how much a slow outlier weighs in the figure above (launch-bound workloads: the events'
     # own cost shows)
     singles = []
-    for _ in range(max(args.steps, 1) if not run.fused else 0):
+    for _ in range(min(max(args.steps, 1), 50) if not run.fused else 0):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         run.step()
