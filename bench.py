@@ -89,6 +89,25 @@ class Runner:
         torch.cuda.synchronize()
         return {"fused": (e0.elapsed_time(e1) / (n * len(segs)), n * len(segs))}
 
+    def graph_seconds_per_op(self, ops_per_graph: int = 100, replays: int = 100) -> float:
+        """The same back-to-back ops captured once into a HIP graph and replayed: what a serving loop
+        that captures its launch-bound inner loop pays per op (the entry points only enqueue kernels
+        on the caller's stream, so they can be captured)."""
+        torch, r2 = self.torch, self.r2
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            call = r2.SimCall(self.desc, self.bufs, self.w.epochs, self.ws)  # bound to the capturing stream
+            for _ in range(ops_per_graph):
+                call.run()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / (ops_per_graph * replays)
+
     def restore(self):
         for b, p in zip(self.bufs, self.pristine):
             b.copy_(p)
@@ -573,6 +592,8 @@ def main() -> int:
                     torch.cuda.synchronize()
                     tot += e0.elapsed_time(e1)
                 line += f"  | restored inputs, GPU time per op: {tot / 100 * 1e3:.1f} us"
+            if rk.fused:
+                line += f"  | replayed from a HIP graph of 100 ops: {rk.graph_seconds_per_op() * 1e6:.1f} us/op"
             print(line, file=sys.stderr, flush=True)
             del rk
             torch.cuda.empty_cache()
