@@ -104,9 +104,29 @@ __device__ uint64_t g_dbg[256];
 // PARTITION: the kernel computes the table rows it needs itself, from the channel states in `eb`
 // (every workgroup for its own use, in LDS; the first column of each slab also records them in
 // the workspace and the log), so that no partition launch has to run in front of it.
+// The kernel-argument block (rank buffers, sizes, channel states: up to 4 KiB) is read in several
+// dependent rounds -- sizes, then the wave's rank buffer, then the state in force, then its weights
+// -- and in a launch whose arguments were just written every first touch of one of its 64-byte lines
+// is a trip to memory.  One vector load, a lane per line, asks for all of them at once when the
+// kernel starts; the rounds then meet L2.  The value is handed to keep_touched() once the prologue
+// is over, which only keeps the load from being dropped.
+__device__ inline uint32_t touch_kernel_arguments(uint32_t bytes)
+{
+    const uint32_t at = (threadIdx.x % kWave) * 64;
+    uint32_t v = 0;
+    if (threadIdx.x < kWave && at < bytes) {
+        const char __attribute__((address_space(4))) *args =
+            (const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr();
+        v = *(const uint32_t __attribute__((address_space(4))) *)(args + at);
+    }
+    return v;
+}
+__device__ inline void keep_touched(uint32_t v) { asm volatile("" ::"v"(v)); }
+
 template <bool BF16, bool PARTITION, unsigned U>
 __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
 {
+    const uint32_t touched = touch_kernel_arguments(sizeof(FusedArgs) + (PARTITION ? sizeof(EpochBatch) : 0));
     R2_STAMP(0);
     __shared__ ColInfo info[2 * R2_MAX_RANKS];  // by transmission within the slab
     const uint32_t l = (uint32_t)(blockIdx.x / a.cols_per_chunk);
@@ -257,6 +277,7 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
         const uint32_t chunk = (r + a.chunk_start + 2 * a.R - j) % a.R;
         return a.rank_buf[r] + ((uint64_t)l * a.R + chunk) * a.chunk_bytes;
     };
+    keep_touched(touched);
 
     if (!slow) {
         // Full-width column: straight-line steps and barriers only.  Where the column lies inside

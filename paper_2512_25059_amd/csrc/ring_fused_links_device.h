@@ -29,6 +29,8 @@ constexpr uint32_t kLinksLdsBytes = 56 * 1024;
 template <bool BF16, unsigned U, bool PARTITION>
 __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_rows, const EpochBatch *eb)
 {
+    const uint32_t touched =
+        touch_kernel_arguments(sizeof(FusedArgs) + 8 + (PARTITION ? sizeof(EpochBatch) : 0));
     R2_STAMP(0);
     extern __shared__ uint64_t s_link[];
     constexpr uint64_t kWidth = (uint64_t)kWave * 16 * U;
@@ -135,6 +137,7 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
         }
     };
 
+    keep_touched(touched);
     const uint64_t per_rank = (uint64_t)a.S * C * a.cap;  // stage bytes of one (parity, rank)
     const uint64_t slab_stage = a.stage + (uint64_t)l * C * a.cap;
 
