@@ -173,6 +173,11 @@ def test_rails_maximum_ranks_and_channels_and_large_chunks(r2, oracle):
     flapping = [[(t, t & 1, w8) for t in range(62)]] + rails.static_epochs(w8, [0] * 31)
     ran = _run(r2, oracle, _inputs(rng, 32, 32 * 64, "bf16"), "bf16", "ar", 1, 8, 16, w8, None, 0, True, flapping)
     assert ran == [r2.SCHED_STEPS, r2.SCHED_FUSED]
+    say("rails R=22 C=11 reduce-scatter: 55,440 bytes of link rows, just under the fused kernel's LDS limit")
+    w11 = [int(x) for x in rng.integers(1, 1000, 11)]
+    masks22 = [int(rng.integers(0, 1 << 11)) & ~(1 << 6) for _ in range(22)]
+    ran = _run(r2, oracle, _inputs(rng, 22, 22 * 4 * 300, "f32"), "f32", "rs", 1, 11, 64, w11, masks22)
+    assert r2.SCHED_FUSED in ran
     say("rails 2 MiB chunks, a window that forces byte-range passes")
     xs = _inputs(rng, 4, 4 * (1 << 19), "f32")
     _run(r2, oracle, xs, "f32", "ar", 1, 8, 256, [50000] * 8, [0b1, 0b10, 0, 0b1100], window=3 << 20)
