@@ -299,6 +299,24 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           void *workspace, uint64_t workspace_bytes,
                           uint64_t *offsets_log, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): r2_ring_allreduce_sim without the workspace argument.  The tables and the
+ * stage area live in a device array inside the library, R2_STATIC_WORKSPACE_BYTES long, which every GPU
+ * the library runs on holds from the moment its code is loaded there until the process ends.  A
+ * descriptor whose r2_sim_workspace_bytes exceeds that returns R2_ERR_CAPACITY before anything is
+ * launched (72 MiB holds the 8-rank bf16 all-reduce of 4 MiB per rank over 8 channels, the largest of
+ * the inference sizes).  Same kernels, same result, same other arguments and errors as
+ * r2_ring_allreduce_sim; rank buffers and the optional log are still the caller's.  The call makes no
+ * hipMalloc/hipFree and calls nothing that allocates; the first call on a device asks the runtime once
+ * for the array's address there.  All calls on one GPU share the one array: it keeps what the last call
+ * left (no step ever reads bytes its own run has not written, so nothing is cleared), and calls that
+ * overlap in time on one GPU -- different streams, different host threads -- race on it: keep them in
+ * order on one stream. */
+#define R2_STATIC_WORKSPACE_BYTES (72ull << 20)
+int r2_ring_allreduce_sim_static(const r2_sim_desc *desc, void *const *rank_bufs,
+                                 const r2_epoch *epochs, uint32_t n_epochs,
+                                 uint64_t *offsets_log, void *stream);
+
 /* The same call under the name that fits the phases which are no all-reduce (R2_PHASE_BROADCAST,
  * R2_PHASE_REDUCE, a reduce-scatter or an all-gather alone): identical arguments and behaviour. */
 int r2_collective_sim(const r2_sim_desc *desc, void *const *rank_bufs,

@@ -204,6 +204,8 @@ def load_library():
     lib.r2_sim_fused_steps.argtypes = [pd, vp, u32, u32, vp, u64, vp]
     lib.r2_ring_allreduce_sim.restype = i32
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
+    lib.r2_ring_allreduce_sim_static.restype = i32
+    lib.r2_ring_allreduce_sim_static.argtypes = [pd, vp, vp, u32, vp, vp]
     lib.r2_sendrecv_sim.restype = i32
     lib.r2_sendrecv_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_collective_sim.restype = i32
@@ -592,6 +594,21 @@ def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
                                               wp, wb, _ptr(offsets_log), _stream(stream))
     del arr, keep
     _check(rc, "r2_ring_allreduce_sim")
+
+
+STATIC_WORKSPACE_BYTES = 72 << 20  # R2_STATIC_WORKSPACE_BYTES
+
+
+def r2_ring_allreduce_sim_static(desc: SimDesc, rank_bufs: Sequence, epochs,
+                                 offsets_log: Optional[torch.Tensor] = None, stream=None) -> None:
+    """The run whose workspace is the library's own static device array (nothing is allocated)."""
+    _check_lists(desc, rank_bufs, epochs)
+    arr, p = _ptr_array(rank_bufs)
+    ep, keep = _epoch_array(epochs)
+    rc = load_library().r2_ring_allreduce_sim_static(C.byref(desc.c()), p, C.cast(ep, C.c_void_p), len(epochs),
+                                                     _ptr(offsets_log), _stream(stream))
+    del arr, keep
+    _check(rc, "r2_ring_allreduce_sim_static")
 
 
 def r2_collective_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,

@@ -7,6 +7,8 @@
 // then all-gather), Sec. 5 and 5.1 (the other collectives keep their schedule under R2CCL-Balance),
 // Sec. 6 (servers that lost different rails: the step kernel picks its tables per link; the host side
 // of that ring is in rails.hip).
+#include <mutex>
+
 #include "sim_shape.h"
 
 namespace r2 {
@@ -539,6 +541,56 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
     return R2_OK;
+}
+
+// ---------------------------------------------------------------- the run whose workspace is a static array
+//
+// For callers that cannot allocate.  The tables and the stage area of the run live in a file-scope
+// device array; each GPU the library's code object is loaded on holds its own copy at its own
+// address, which is asked for once per device and kept.  In host code the array's name is only a
+// handle for that query: every use of the memory goes through the address it returned.
+namespace r2 {
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[R2_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices];  // per device: where `scratch` lives there, or null while unknown
+
+// The current device's copy of `scratch`.  The first call on a device looks the address up; nothing
+// is allocated then or later.
+int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return R2_ERR_DEVICE;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return R2_ERR_DEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return R2_OK;
+}
+
+}  // namespace
+}  // namespace r2
+
+extern "C" int r2_ring_allreduce_sim_static(const r2_sim_desc *desc, void *const *rank_bufs,
+                                            const r2_epoch *epochs, uint32_t n_epochs,
+                                            uint64_t *offsets_log, void *stream)
+{
+    SimShape s;
+    int rc = shape_of(desc, s);
+    if (rc) return rc;
+    if (s.total_bytes > R2_STATIC_WORKSPACE_BYTES) return R2_ERR_CAPACITY;
+    void *ws = nullptr;
+    if ((rc = scratch_of_current_device(&ws))) return rc;
+    // Nothing in the workspace has to start at zero: every table row is written (by the partition
+    // launch, or by the fused kernels themselves) before a step reads it, and a step only reads the
+    // stage bytes the step before it wrote.  What an earlier call left there is never looked at.
+    return r2_ring_allreduce_sim(desc, rank_bufs, epochs, n_epochs, ws, R2_STATIC_WORKSPACE_BYTES, offsets_log, stream);
 }
 
 extern "C" int r2_collective_sim(const r2_sim_desc *desc, void *const *rank_bufs, const r2_epoch *epochs,
