@@ -24,17 +24,21 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure (8 TB/s)
 
 # Bytes per launch between L2 and the memory fabric for the dominant kernel, from two
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled
-# by what the same counter reads for a plain 128 MiB device-to-device copy in the same run
-# (FETCH_SIZE reads half the copied bytes there, WRITE_SIZE all of them).  The figures and the
-# commands are in profiles/ring_step_sum_bf16_cfg2_pmc.md (cfg3: ..._f32_cfg3_pmc.md, cfg4: ..._bf16_cfg4_pmc.md).  Not measured for
-# other workloads.
+# by what the same counter reads for a plain device-to-device copy of one rank buffer in the same run
+# (FETCH_SIZE reads half the copied bytes there, WRITE_SIZE all of them).  These are figures of earlier
+# profiler runs, kept in the named files with their commands: NOT measured by the run that prints them
+# (the JSON line says so in roofline.traffic_source).  The counters sit between L2 and the fabric and
+# cannot tell HBM from the Infinity Cache.
 MEASURED_TRAFFIC = {
-    ("cfg2", "sum"): int((131112.8 * (131072.0 / 65550.7) + 262158.2 * (131072.0 / 131072.0)) * 1024),
-    # cfg3: the calibration copy is one 256 MiB rank buffer (profiles/ring_step_sum_f32_cfg3_pmc.md)
-    ("cfg3", "sum"): int((131114.8 * (262144.0 / 131087.4) + 262156.1 * (262144.0 / 262144.0)) * 1024),
-    # cfg4: one 64 MiB rank buffer (profiles/ring_step_sum_bf16_cfg4_pmc.md)
-    ("cfg4", "sum"): int((65611.1 * (65536.0 / 32781.6) + 131074.6 * (65536.0 / 65536.0)) * 1024),
+    ("cfg2", "sum"): (int((131112.8 * (131072.0 / 65550.7) + 262158.2 * (131072.0 / 131072.0)) * 1024),
+                      "profiles/ring_step_sum_bf16_cfg2_pmc.md"),
+    ("cfg3", "sum"): (int((131114.8 * (262144.0 / 131087.4) + 262156.1 * (262144.0 / 262144.0)) * 1024),
+                      "profiles/ring_step_sum_f32_cfg3_pmc.md"),
+    ("cfg4", "sum"): (int((65611.1 * (65536.0 / 32781.6) + 131074.6 * (65536.0 / 65536.0)) * 1024),
+                      "profiles/ring_step_sum_bf16_cfg4_pmc.md"),
 }
+
+OTHER_CONFIGS = ("cfg1", "cfg3", "cfg4", "cfg5_tok1", "cfg5_tok16", "cfg5_tok64", "cfg5_tok256")
 
 
 def _workload(name: str):
@@ -217,6 +221,112 @@ def _cpu_baseline(w, xs, gpu_outs, np):
         "single_thread_GBps": round(w.algorithmic_bytes / res[1] / 1e9, 3),
         "single_thread_seconds": round(res[1], 3),
     }, ok
+
+
+def _matches_definition(w, xs, gpu_outs, np):
+    """Part of the cpu_baseline leg: the GPU result of one pass from pristine inputs against the
+    oracle's result by plain definition (the left fold in ring order), every element of every rank."""
+    import oracle
+
+    odt = oracle.F32 if w.dtype == "f32" else oracle.BF16
+    oph = {"ar": oracle.PHASE_AR, "rs": oracle.PHASE_RS, "ag": oracle.PHASE_AG}[w.phases]
+    want = oracle.expected(xs, odt, w.S, oph)
+    return all(np.array_equal(a, b) for a, b in zip(want, gpu_outs))
+
+
+def _dominant(run, w, reps):
+    """The dominant kernel of a run on the step schedule: the reducing step that also stages.
+    Returns (kind, average launch ms, launches timed, algorithmic bytes per launch, all kinds)."""
+    ktimes = run.kernel_times(reps)
+    dom = "sum" if "sum" in ktimes else "copy"
+    units = 4 if dom == "sum" else 3
+    avg_ms, launches = ktimes[dom]
+    # one fused step moves, for every rank and slab, one ring chunk through `units` streams; it is
+    # spread over the run's passes, one launch each
+    return dom, avg_ms, launches, units * w.N * w.elem_bytes / run.P, ktimes
+
+
+def config_entry(r2, torch, np, wl, name, check, reps, cold_window=0):
+    """One of the configurations the headline is not quoted on, in the schedule the library picks:
+    whole-run time over back-to-back ops (in place), the rate of algorithmic bytes, the check of op #1
+    from pristine inputs against the oracle, and on the step schedule the dominant kernel's launch."""
+    w = _workload(name)
+    xs = wl.make_inputs(w)
+    run = Runner(r2, torch, np, w, xs)
+    run.step()
+    torch.cuda.synchronize()
+    first = [b.cpu().numpy().view(x.dtype) for b, x in zip(run.bufs, xs)]
+    ops = 10000 if name.startswith("cfg5") else (2000 if name == "cfg1" else 20)
+    s = run.time_steps(ops, 3) / ops
+    rate = w.algorithmic_bytes / s / 1e9
+    e = {"schedule": "fused" if run.fused else "steps", "ops": ops}
+    if s < 1e-3 / 4:
+        e["us_per_op"] = round(s * 1e6, 2)
+    else:
+        e["ms_per_step"] = round(s * 1e3, 4)
+    e["GBps"] = round(rate, 1)
+    if run.fused:
+        e["served_by"] = "cache (effective rate)"  # a fused run's stage traffic never leaves the caches
+    else:
+        e["pct_of_hbm_peak"] = round(100 * rate / HBM_PEAK_GBPS, 2)
+        dom, avg_ms, launches, launch_bytes, _ = _dominant(run, w, reps)
+        e["passes"] = run.P
+        e["kernel"] = dom
+        e["avg_launch_ms"] = round(avg_ms, 5)
+        e["frac"] = round(launch_bytes / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+    if check:
+        e["matches_oracle"] = bool(_matches_definition(w, xs, first, np))
+    del run, first
+    torch.cuda.empty_cache()
+    cold = cold_one_pass(r2, torch, np, w, xs, cold_window, reps) if cold_window else None
+    return e, cold
+
+
+def cold_reduce_copy(r2, torch, dtype="bf16", chunk_mib=256, sets=4, reps=40):
+    """The chunk worker with nothing cache-resident: stand-alone r2_reduce_copy (sum, both stages,
+    8 channels of which 2 and 5 are down) on chunks of `chunk_mib` MiB, rotating over `sets` disjoint
+    sets of buffers, so that every set's 3 x chunk bytes have been pushed out of the 256 MiB Infinity
+    Cache by the others before it comes round again.  All four streams are HBM traffic.  Returns
+    (average launch ms by events on the launching stream, algorithmic bytes per launch)."""
+    C, align, mask = 8, 256, 0b100100
+    nbytes = chunk_mib << 20
+    dt = r2.BF16 if dtype == "bf16" else r2.F32
+    off = r2.r2_partition([50000] * C, mask, nbytes, align)
+    cap = (max(off[c + 1] - off[c] for c in range(C)) + 255) // 256 * 256
+    d_off = torch.tensor(off, dtype=torch.int64, device="cuda")
+    calls = []
+    for _ in range(sets):
+        local = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        ins = [torch.zeros(cap, dtype=torch.uint8, device="cuda") for _ in range(C)]
+        outs = [torch.zeros(cap, dtype=torch.uint8, device="cuda") for _ in range(C)]
+        calls.append(r2.ReduceCopyCall(local, dt, r2.OP_SUM, ins, d_off, outs, d_off, C, cap, nbytes=nbytes))
+    for i in range(2 * sets):
+        calls[i % sets].run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        calls[i % sets].run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del calls
+    torch.cuda.empty_cache()
+    return ms, 4 * nbytes
+
+
+def cold_one_pass(r2, torch, np, w, xs, window, reps):
+    """A configuration with the stage window opened so far that it runs in one pass (cfg3: 256 MiB
+    staged per step, which the next step no longer finds in the Infinity Cache).  The same sum kernel.
+    Returns (average launch ms, algorithmic bytes per launch)."""
+    run = Runner(r2, torch, np, w, xs, window=window, schedule=1)
+    assert run.P == 1
+    for _ in range(2):
+        run.step()
+    _, avg_ms, _, launch_bytes, _ = _dominant(run, w, reps)
+    del run
+    torch.cuda.empty_cache()
+    return avg_ms, launch_bytes
 
 
 def reduce_copy_sweep(r2, torch, out=sys.stderr):
@@ -446,6 +556,8 @@ def main() -> int:
     ap.add_argument("--schedule", choices=["auto", "steps", "fused"], default="auto")
     ap.add_argument("--stage-window-mib", type=float, default=0.0,
                     help="stage bytes one launch may write (0 = library default)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time the named configuration only (no cold figures, no other configurations): for profiler runs")
     ap.add_argument("--all", action="store_true", help="also print a table of every configuration to stderr")
     ap.add_argument("--rails", action="store_true",
                     help="also print the all-reduce with per-link tables (cfg2 shape and cfg5's sizes) to stderr")
@@ -496,23 +608,24 @@ def main() -> int:
     median_ms = sorted(singles)[len(singles) // 2] if singles else None
 
     # dominant kernel: the fused reducing step that also stages (two reads, two writes per element)
-    ktimes = run.kernel_times(args.kernel_reps)
     if run.fused:
+        ktimes = run.kernel_times(args.kernel_reps)
         dom = "fused"
         dom_avg_ms, dom_launches = ktimes[dom]
         launch_bytes = w.algorithmic_bytes / len(_fused_segments(w))
-        kernel_name = "ring_fused_partition_kernel<%s> (ring_fused_kernel when the tables are prepared up front; stage round trip served by L2: not an HBM figure)" % w.dtype
+        kernel_name = "ring_fused_partition_kernel<%s> (ring_fused_kernel when the tables are prepared up front)" % w.dtype
+        served_by = "cache: the stage round trip of a fused column stays in L2 (effective rate, not an HBM figure)"
     else:
-        dom = "sum" if "sum" in ktimes else "copy"
-        dom_units = 4 if dom == "sum" else 3
-        dom_avg_ms, dom_launches = ktimes[dom]
-        # one fused step moves, for every rank and slab, one ring chunk through dom_units streams; it
-        # is spread over the run's passes, one launch each
-        launch_bytes = dom_units * w.N * w.elem_bytes / run.P
+        dom, dom_avg_ms, dom_launches, launch_bytes, ktimes = _dominant(run, w, args.kernel_reps)
         kernel_name = {"sum": "ring_step_kernel<Sum%s, staged>" % ("BF16" if w.dtype == "bf16" else "F32"),
                        "copy": "ring_step_kernel<Copy, staged>"}[dom]
+        # what one step stages (N*e bytes over all ranks, per pass) is read back by the next launch
+        staged = w.N * w.elem_bytes / run.P
+        served_by = ("HBM for three of the four streams + Infinity Cache for the incoming stage (the %d MiB a step "
+                     "stages are still in the 256 MiB cache when the next launch reads them); frac_cold is the "
+                     "all-HBM figure" % (staged // (1 << 20)) if staged <= (128 << 20) else "HBM")
     achieved = launch_bytes / (dom_avg_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC.get((w.name, dom))
+    traffic, traffic_source = MEASURED_TRAFFIC.get((w.name, dom), (None, None))
 
     out = {
         "metric": "reduce-copy effective HBM GB/s",
@@ -529,8 +642,7 @@ def main() -> int:
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {
-            "workload": f"{w.name}: R={w.R} simulated ranks, {w.dtype}, {w.N} elements/rank, S={w.S} slab(s), "
-                        f"C={w.C} channels, {w.phases}, {w.note}",
+            "workload": f"{w.name}: R={w.R} ranks, {w.dtype}, {w.N} elems/rank, S={w.S}, C={w.C}, {w.phases}; {w.note}"[:127],
             "algorithmic_bytes_per_step": w.algorithmic_bytes,
             "schedule": "fused columns" if run.fused else "one launch per ring step",
             "passes": run.P,
@@ -546,7 +658,10 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "served_by": served_by,
             "traffic": traffic,
+            "traffic_source": None if traffic is None else
+                              f"{traffic_source} (an earlier rocprofv3 --pmc run of this command; not measured by this run)",
             "bytes_per_launch": launch_bytes,
             "avg_launch_ms": round(dom_avg_ms, 5),
             "launches_timed": dom_launches,
@@ -556,18 +671,44 @@ def main() -> int:
                    "servers; it gives no kernel-level number, so vs_baseline is null",
     }
 
-    if not args.no_cpu_baseline:
+    check = not args.no_cpu_baseline
+    if check:
         base, ok = _cpu_baseline(w, xs, first_pass, np)
         out["cpu_baseline"] = base
         out["matches_oracle"] = bool(ok)
+    del run, xs, first_pass
+    torch.cuda.empty_cache()
+
+    if args.config == "cfg2" and not args.headline_only:
+        # The other configurations, each in the schedule the library picks for it; and the same chunk
+        # worker with every stream coming from and going to HBM (cfg3 once more, in one pass).
+        out["configs"] = {}
+        for name in OTHER_CONFIGS:
+            out["configs"][name], cold = config_entry(r2, torch, np, wl, name, check, args.kernel_reps,
+                                                      cold_window=(256 << 20) if name == "cfg3" else 0)
+            if cold:
+                c3_ms, c3_bytes = cold
+            print(f"bench.py: {name} done", file=sys.stderr, flush=True)
+        rc_ms, rc_bytes = cold_reduce_copy(r2, torch, "bf16", 256)
+        rc_frac = rc_bytes / (rc_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
+        c3_frac = c3_bytes / (c3_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
+        out["roofline"]["frac_cold"] = round(min(rc_frac, c3_frac), 4)
+        out["roofline"]["cold"] = {
+            "reduce_copy_bf16_sum_256MiB_chunks_rotated_over_4_buffer_sets": {"avg_launch_ms": round(rc_ms, 5), "frac": round(rc_frac, 4)},
+            "cfg3_forced_to_one_pass_f32_sum_1GiB_per_launch": {"avg_launch_ms": round(c3_ms, 5), "frac": round(c3_frac, 4)},
+        }
+        # the large configurations' dominant-kernel fractions also where the roofline object is read
+        out["roofline"]["other_configs"] = {n: {k: out["configs"][n][k] for k in ("kernel", "avg_launch_ms", "frac", "passes")}
+                                            for n in ("cfg3", "cfg4")}
+        if check:
+            out["matches_oracle_all"] = bool(out["matches_oracle"] and all(c["matches_oracle"] for c in out["configs"].values()))
+
     print(json.dumps(out), flush=True)
-    if not args.no_cpu_baseline and not out["matches_oracle"]:
-        print("bench.py: GPU result of the first pass differs from the oracle", file=sys.stderr)
+    if check and not out.get("matches_oracle_all", out["matches_oracle"]):
+        print("bench.py: a GPU result differs from the oracle", file=sys.stderr)
         return 1
 
     if args.all:
-        del run
-        torch.cuda.empty_cache()
         print("every configuration, schedule chosen by the library (fused columns for launch-bound sizes):", file=sys.stderr)
         for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5_tok1", "cfg5_tok16", "cfg5_tok64", "cfg5_tok256"):
             wk = _workload(name)
