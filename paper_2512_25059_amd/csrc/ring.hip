@@ -51,7 +51,7 @@ struct StepArgs {
 
 // blockIdx.y = (rank - rank_base) * slab_count + (slab - slab_begin), blockIdx.x = workgroup within
 // the range.
-template <Mode M, bool HAS_OUT, bool KEEP = false>
+template <Mode M, bool HAS_OUT, bool KEEP = false, bool NT_OUT = kNtStageStore>
 __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
 {
     __shared__ ChannelTable tin, tout;
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void ring_step_kernel(const StepArgs a)
     // stage buffer of (parity, rank, slab, channel)
     const uint64_t in_base = a.stage + ((((uint64_t)((j + 1) & 1) * a.R + peer) * a.S + l) * a.C) * a.cap;
     const uint64_t out_base = a.stage + ((((uint64_t)(j & 1) * a.R + r) * a.S + l) * a.C) * a.cap;
-    run_chunk<M, HAS_OUT, false, kNtStageStore, KEEP>(
+    run_chunk<M, HAS_OUT, false, NT_OUT, KEEP>(
         job, [&](unsigned c) { return in_base + c * a.cap; },
         [&](unsigned c) { return out_base + c * a.cap; }, nullptr, tin, tout);
 }
@@ -145,10 +145,18 @@ int check_epochs(const r2_epoch *epochs, uint32_t n, const SimShape &s)
 // The plain ring's fused columns: not for per-link tables (rails.hip has those).
 bool fused_eligible(const SimShape &s) { return !s.links && columns_fit(s); }
 
+// A stage this large is gone from the caches before anybody reads it: written around them.
+constexpr uint64_t kNtStageBytes = 128ull << 20;
+
+// One fused step: `rows` (rank, slab) pairs, each moving bytes [lo, hi) of its ring chunk.
 template <Mode M, bool HAS_OUT, bool KEEP = false>
-void launch_step(const StepArgs &a, dim3 grid, hipStream_t st)
+void launch_step(const StepArgs &a, unsigned rows, hipStream_t st)
 {
-    hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT, KEEP>), grid, dim3(kThreads), 0, st, a);
+    const dim3 grid(blocks_for(a.hi - a.lo), rows);
+    if (HAS_OUT && (uint64_t)rows * (a.hi - a.lo) > kNtStageBytes)
+        hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT, KEEP, HAS_OUT>), grid, dim3(kThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT, KEEP, false>), grid, dim3(kThreads), 0, st, a);
 }
 
 // Decides between one launch per step and fused columns, and marks the steps before which a fused
@@ -179,9 +187,6 @@ int plan_schedule(const r2_sim_desc *desc, const SimShape &s, const r2_epoch *ep
     const bool fewer = (uint64_t)(n_cuts + 1) * 2 <= s.n_passes * s.J;
     return step_bytes <= kFusedAutoBytes && fewer ? R2_SCHED_FUSED : R2_SCHED_STEPS;
 }
-
-// A stage this large is gone from the caches before anybody reads it back: written around them.
-constexpr uint64_t kNtStageBytes = 128ull << 20;
 
 template <Mode M, bool HAS_OUT, bool FWD = false, bool KEEP = false>
 void launch_single(const ChunkJob &job, const PtrList &in, const PtrList &out, int32_t *status,
@@ -358,7 +363,7 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     const Mode m = mode_of(has_in, op, desc->dtype);
     const bool keep = s.kind == SimShape::kReduce && has_in && has_out;  // the sum is passed on, not kept
 
-    const dim3 grid(blocks_for(a.hi - a.lo), s.active() * a.slab_count);
+    const unsigned grid = s.active() * a.slab_count;  // rows of workgroups: one per (rank, slab)
     hipStream_t st = (hipStream_t)stream;
     switch (m) {
     case kSend: launch_step<kSend, true>(a, grid, st); break;

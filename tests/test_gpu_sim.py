@@ -383,12 +383,12 @@ def test_sim_all_failed_touches_nothing(r2):
 
 # ------------------------------------------------------------------ full benchmark sizes
 
-def _full_size(r2, oracle, w, check_bound=False, schedule=0):
+def _full_size(r2, oracle, w, check_bound=False, schedule=0, window=0):
     _, _, odt, oph = codes(r2, oracle, w)
     say(f"sim full {w.name}: generating inputs")
     xs = wl.make_inputs(w)
-    say(f"sim full {w.name}: GPU run, schedule={schedule}")
-    outs, log, _, _ = run_gpu_sim(r2, w, xs, schedule=schedule)
+    say(f"sim full {w.name}: GPU run, schedule={schedule}, window={window}")
+    outs, log, _, _ = run_gpu_sim(r2, w, xs, schedule=schedule, window=window)
     say(f"sim full {w.name}: oracle")
     want = oracle.expected(xs, odt, w.S, oph)
     for r in range(w.R):
@@ -423,6 +423,18 @@ def test_full_cfg4_fused(r2, oracle):
 
 def test_full_cfg3(r2, oracle):
     _full_size(r2, oracle, wl.cfg3())
+
+
+def test_full_cfg3_one_pass(r2, oracle):
+    """The stage window opened to 256 MiB: one pass, every step stages more than the caches hold, and
+    the step kernel then writes its stage around them (the variant the cold roofline figure times)."""
+    _full_size(r2, oracle, wl.cfg3(), schedule=1, window=256 << 20)
+
+
+def test_full_cfg2_ragged_one_pass_stage_beyond_cache(r2, oracle):
+    """bf16, chunks of 16 MiB + 48 bytes in one pass: a step stages just over 128 MiB, the bf16 kernels
+    write their stage around the caches, and the last tile of every chunk is ragged."""
+    _full_size(r2, oracle, wl.scaled(wl.cfg2(), 8 * ((1 << 23) + 24)), schedule=1, window=1 << 30)
 
 
 def test_full_cfg4(r2, oracle):
