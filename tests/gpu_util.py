@@ -69,3 +69,22 @@ def expected_log(oracle, w: wl.Workload) -> np.ndarray:
         ep = [e for e in w.epochs if e[0] <= t][-1]
         rows.append(oracle.partition(ep[2], ep[1], w.chunk_bytes, w.align))
     return np.array(rows, dtype=np.uint64).reshape(T, w.C + 1)
+
+
+def windows_around(points, total: int, radius: int, unit: int = 1):
+    """Merged, sorted index ranges [a, b) within [0, total) that cover `radius` on either side of every
+    point (a point at `total` gives the tail).  Bounds are multiples of `unit`, except `total` itself."""
+    spans = []
+    for p in points:
+        a = max(0, (int(p) - radius) // unit * unit)
+        b = min(total, (int(p) + radius + unit - 1) // unit * unit)
+        if a < b:
+            spans.append((a, b))
+    spans.sort()
+    merged = []
+    for a, b in spans:
+        if merged and a <= merged[-1][1]:
+            merged[-1] = (merged[-1][0], max(merged[-1][1], b))
+        else:
+            merged.append((a, b))
+    return merged

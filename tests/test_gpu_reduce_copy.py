@@ -204,9 +204,15 @@ def test_reduce_copy_zero_bytes(r2):
 
 def test_reduce_copy_chunk_beyond_4GiB(r2, oracle):
     """A chunk of 4 GiB + 1 MiB + 6 bytes of bf16 (2^31 + 2^19 + 3 elements): slice offsets, stage
-    addresses and the ragged tail all lie beyond 32 bits.  Too large for the host oracle in a test, so the
-    expected values are built on the GPU with library operations from the definition: per element
-    bf16(float(incoming) + float(local)), incoming and outgoing slices cut at the oracle's tables."""
+    addresses and the ragged tail all lie beyond 32 bits.  Too large for the host oracle as a whole, so
+    `oracle.reduce_copy` checks windows of it byte for byte -- the first tile, a MiB either side of the
+    2^32-byte boundary, of every cut of the incoming and of the outgoing table, and the ragged end: the
+    window's incoming bytes are taken out of the stage buffers by the oracle's incoming table, the
+    oracle adds them to the window's local bytes, and the local chunk and the outgoing stage (read back
+    through the oracle's outgoing table) must hold exactly that.  The rest of the chunk is compared with
+    values built on the GPU with library operations from the definition."""
+    from gpu_util import windows_around
+
     n_el = (1 << 31) + (1 << 19) + 3
     nbytes = n_el * 2
     C = 3
@@ -231,11 +237,33 @@ def test_reduce_copy_chunk_beyond_4GiB(r2, oracle):
         buf[:b - a] = raw_in[a:b]
         d_in.append(buf)
     d_out = [torch.full((cap,), FILL, dtype=torch.uint8, device="cuda") for _ in range(C)]
+
+    def through_table(bufs, off, a, b):
+        """Bytes [a, b) of the chunk as the stage buffers hold them under table `off` (host copy)."""
+        parts = []
+        for k in range(C):
+            lo, hi = max(a, int(off[k])), min(b, int(off[k + 1]))
+            if lo < hi:
+                parts.append(bufs[k][lo - int(off[k]):hi - int(off[k])].cpu().numpy())
+        return np.concatenate(parts)
+
+    points = [0, 1 << 32, nbytes] + [int(x) for x in in_off] + [int(x) for x in out_off]
+    spans = windows_around(points, nbytes, 1 << 20, unit=2)
+    local_before = [local.view(torch.uint8)[a:b].cpu().numpy().copy() for a, b in spans]
     status = torch.zeros(1, dtype=torch.int32, device="cuda")
     r2.r2_reduce_copy(local.view(torch.int16), r2.BF16, r2.OP_SUM, d_in, _dev(in_off), d_out, _dev(out_off), C, cap,
                       status, nbytes=nbytes)
     torch.cuda.synchronize()
     assert int(status.item()) == 0
+    for (a, b), loc in zip(spans, local_before):
+        n = b - a
+        one = np.array([0, n], dtype=np.uint64)  # the window as a chunk of its own, one channel each way
+        o_local = loc.view(np.uint16).copy()
+        o_in = [through_table(d_in, in_off, a, b)]
+        o_out = [np.full(n, FILL, np.uint8)]
+        oracle.reduce_copy(o_local, oracle.BF16, oracle.OP_SUM, o_in, one, o_out, one, 1, n)
+        assert local.view(torch.uint8)[a:b].cpu().numpy().tobytes() == o_local.tobytes(), f"local bytes [{a}, {b})"
+        assert through_table(d_out, out_off, a, b).tobytes() == o_out[0].tobytes(), f"outgoing stage, bytes [{a}, {b})"
     assert torch.equal(local.view(torch.int16), want.view(torch.int16))
     raw_want = want.view(torch.uint8)
     for k in range(C):

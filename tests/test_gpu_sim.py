@@ -232,29 +232,47 @@ def test_sim_maximum_slabs(r2, oracle, schedule):
 
 def test_sim_chunks_beyond_4GiB(r2, oracle):
     """Byte offsets that do not fit 32 bits: two ranks of 8 GiB + 8 MiB each, i.e. ring chunks of
-    4 GiB + 4 MiB, moved in byte-range passes.  Too large for the oracle's step-by-step ring on the host, so
-    the result is checked by what it must be for two ranks -- one fp32 addition per element, the same bits in
-    either order -- and the tables against the oracle's partition."""
+    4 GiB + 4 MiB, moved in byte-range passes.  Too large for the oracle's step-by-step ring on the host
+    as a whole, so the oracle checks windows of it element by element: the first tile, a MiB either side
+    of every 2^32-byte boundary (of the chunk and of the rank buffer), of every slice cut of both channel
+    states and of the chunk's end.  A window takes the same element range of every ring chunk of every
+    rank, which is an all-reduce of its own with the same fold order, so `oracle.expected` gives its
+    result.  Everything else is checked by what the result must be for two ranks (one fp32 addition per
+    element, the same bits in either order, made with a library call), and the tables against the oracle's
+    partition."""
+    from gpu_util import windows_around
+
     R, C = 2, 3
     N = (1 << 31) + (1 << 21)
     weights = (3, 1, 2)
     epochs = [(0, 0, weights), (1, 0b010, weights)]
     desc = r2.SimDesc(R, 1, C, 256, N, r2.F32, r2.PHASE_AR, 0, r2.SCHED_STEPS)
-    chunk_bytes = N // R * 4
+    E = N // R
+    chunk_bytes = E * 4
     assert chunk_bytes > 1 << 32 and r2.r2_sim_num_passes(desc) > 1
     say(f"sim beyond 4 GiB: R={R} N={N} chunk={chunk_bytes} B passes={r2.r2_sim_num_passes(desc)}")
     g = torch.Generator(device="cuda").manual_seed(4096)
     xs = [torch.randn(N, generator=g, dtype=torch.float32, device="cuda") for _ in range(R)]
+    tables = [oracle.partition(w, mask, chunk_bytes, 256) for _, mask, w in epochs]
+    points = [0, 1 << 32, (1 << 33) - chunk_bytes, chunk_bytes] + [int(x) for t in tables for x in t]
+    spans = windows_around([p // 4 for p in points], E, (1 << 20) // 4)
+    before = [[np.concatenate([xs[r][c * E + a:c * E + b].cpu().numpy() for c in range(R)]) for r in range(R)]
+              for a, b in spans]
     want = xs[0] + xs[1]
     ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
     log = torch.full((2, C + 1), -1, dtype=torch.int64, device="cuda")
     r2.r2_ring_allreduce_sim(desc, xs, epochs, ws, log)
     torch.cuda.synchronize()
+    for (a, b), mini in zip(spans, before):
+        exp = oracle.expected(mini, oracle.F32, 1, oracle.PHASE_AR)
+        for r in range(R):
+            got = np.concatenate([xs[r][c * E + a:c * E + b].cpu().numpy() for c in range(R)])
+            assert got.tobytes() == exp[r].tobytes(), f"rank {r}, elements [{a}, {b}) of every chunk vs the oracle"
     for r in range(R):
         assert torch.equal(xs[r].view(torch.int32), want.view(torch.int32)), f"rank {r}"
     got = log.cpu().numpy().view(np.uint64)
-    for t, (_, mask, w) in enumerate(epochs):
-        assert got[t].tolist() == oracle.partition(w, mask, chunk_bytes, 256).tolist()
+    for t in range(len(epochs)):
+        assert got[t].tolist() == tables[t].tolist()
     assert int(got[0][-1]) == chunk_bytes and int(got[0][1]) > 1 << 31  # cuts beyond 2 GiB and 4 GiB
     del xs, want, ws
     torch.cuda.empty_cache()
