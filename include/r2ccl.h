@@ -17,8 +17,11 @@
  * Conventions
  *   - Every function returns an R2_* code (0 = success); nothing throws or aborts.
  *   - "device" pointers are HIP device memory of the current device, "host" pointers
- *     are ordinary process memory.  The caller owns every buffer.  Unless a function
- *     says otherwise the library allocates nothing.
+ *     are ordinary process memory.  The caller owns every buffer.  The library allocates no
+ *     device memory.  The only state it keeps for the life of the process, per device: the side
+ *     streams and events of r2_split_allreduce_sim / r2_recursive_allreduce_sim, created at their
+ *     first call, and two device arrays that are part of its code (see r2_ring_allreduce_sim_static
+ *     and r2_partition).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and return; r2_partition alone waits for its result.
  *   - Data buffers (rank buffers, stage buffers) must be 16-byte aligned.
@@ -92,8 +95,9 @@ int r2_partition_device(const uint32_t *weights, const uint64_t *fail_mask, cons
                         uint64_t *offsets, int32_t *status, void *stream);
 
 /* One partition with HOST pointers: weights[n_channels] in, offsets[n_channels+1] out.  Runs the
- * same device code, on the default stream, and waits for it.  Convenience call: it allocates and
- * frees a few hundred bytes of device memory. */
+ * same device code, on the default stream, and waits for it (so it cannot be captured into a graph).
+ * Convenience call; it allocates nothing: the row is written to a small device array inside the
+ * library and copied back, and concurrent calls take turns. */
 int r2_partition(const uint32_t *weights, uint64_t fail_mask, uint32_t n_channels, uint64_t bytes,
                  uint32_t align, uint64_t *offsets);
 

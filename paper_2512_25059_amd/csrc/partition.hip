@@ -3,6 +3,8 @@
 // Follows the R2CCL paper, Sec. 5.1 (R2CCL-Balance): the data a server must move is spread over
 // its healthy NICs in proportion to their bandwidth, a failed NIC carries nothing, and the volume
 // itself is unchanged ("Overhead Analysis").  The rounding rule is stated in r2ccl.h.
+#include <mutex>
+
 #include "partition_device.h"
 
 namespace r2 {
@@ -66,6 +68,9 @@ __global__ __launch_bounds__(kBlock) void rollback_plan_kernel(
     // a problem's status only ever goes from R2_OK to an error (the caller clears it beforehand)
     if (lane == 0 && status && st != R2_OK) atomicMin(status + p, st);
 }
+
+// The row r2_partition (host pointers in, host pointers out) has the device write.
+static __device__ __align__(256) uint64_t host_call_row[R2_MAX_CHANNELS + 1];
 
 }  // namespace
 
@@ -136,12 +141,23 @@ extern "C" int r2_partition(const uint32_t *weights, uint64_t fail_mask, uint32_
         for (uint32_t c = 0; c <= n_channels; ++c) offsets[c] = 0;
         return R2_ERR_NO_HEALTHY_CHANNEL;
     }
-    const size_t row = (size_t)(n_channels + 1) * sizeof(uint64_t);
-    uint64_t *d_row = nullptr;
-    if (hipMalloc((void **)&d_row, row) != hipSuccess) return R2_ERR_DEVICE;
+    // The one row this call needs lives in a small static device array (each GPU has its own copy,
+    // whose address is asked for once per device): nothing is allocated.  Calls are serialised, since
+    // they share the row.
+    static std::mutex lock;
+    static uint64_t *rows[64];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return R2_ERR_DEVICE;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!rows[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(r2::host_call_row)) != hipSuccess || !p) return R2_ERR_DEVICE;
+        rows[dev] = static_cast<uint64_t *>(p);
+    }
+    uint64_t *d_row = rows[dev];
     const r2_epoch ep = {0, fail_mask, weights};
     int rc = r2::launch_partition_epochs(&ep, 1, n_channels, align, bytes, 1, d_row, nullptr, nullptr);
-    if (rc == R2_OK) rc = r2::hip_rc(hipMemcpy(offsets, d_row, row, hipMemcpyDeviceToHost));
-    (void)hipFree(d_row);
+    if (rc == R2_OK)
+        rc = r2::hip_rc(hipMemcpy(offsets, d_row, (size_t)(n_channels + 1) * sizeof(uint64_t), hipMemcpyDeviceToHost));
     return rc;
 }

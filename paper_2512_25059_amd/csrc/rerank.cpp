@@ -1,11 +1,15 @@
 // Bridge-based logical re-ranking of a ring (R2CCL paper, Sec. 6 "Topology-Aware Logical Re-ranking",
 // Appendix D Algorithm 1).  Host-side integer work on a handful of nodes; no device code.
 //
-// A node's rail set is a 64-bit mask; the capacity of a ring edge is the number of rails its two
-// ends share.  Edges narrower than the narrowest node (B_global) are repaired, worst first, by
-// moving a "bridge" node with wide enough connectivity in between, provided that closing the gap it
-// leaves behind does not create a narrow edge.
-#include <algorithm>
+// A node's rail set is a 64-bit mask; the width of a ring edge is the number of rails its two ends
+// share.  Edges narrower than the narrowest node are repaired, worst first, by moving a "bridge" node
+// with wide enough connectivity in between, provided that closing the gap it leaves behind does not
+// create a narrow edge.
+//
+// Layout: the ring is a doubly linked list over node ids (succ/pred arrays), so taking a bridge out
+// and putting it between two neighbours is a constant number of pointer updates; the pairwise rail
+// overlaps are counted once into an n x n byte matrix; the broken edges wait in one bucket per gap
+// size (a gap is at most 64 rails), which gives "worst first, ties in ring order" without a sort.
 #include <cstdint>
 #include <new>
 #include <vector>
@@ -14,7 +18,43 @@
 
 namespace {
 
-inline uint32_t shared_rails(uint64_t a, uint64_t b) { return (uint32_t)__builtin_popcountll(a & b); }
+class LinkedRing {
+public:
+    LinkedRing(const uint32_t *order, uint32_t n) : succ_(n), pred_(n), first_(order[0]), n_(n)
+    {
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint32_t a = order[i], b = order[(i + 1) % n];
+            succ_[a] = b;
+            pred_[b] = a;
+        }
+    }
+    uint32_t first() const { return first_; }
+    uint32_t after(uint32_t node) const { return succ_[node]; }
+    uint32_t before(uint32_t node) const { return pred_[node]; }
+    // Takes `node` out of the ring and puts it right behind `anchor`.  The walk's starting point stays
+    // where it was, unless the node that moves was that point: then its successor takes over.
+    void move_behind(uint32_t node, uint32_t anchor)
+    {
+        const uint32_t left = pred_[node], right = succ_[node];
+        succ_[left] = right;
+        pred_[right] = left;
+        if (first_ == node) first_ = right;
+        const uint32_t follower = succ_[anchor];
+        succ_[anchor] = node;
+        pred_[node] = anchor;
+        succ_[node] = follower;
+        pred_[follower] = node;
+    }
+    void write(uint32_t *out) const
+    {
+        uint32_t node = first_;
+        for (uint32_t i = 0; i < n_; ++i, node = succ_[node]) out[i] = node;
+    }
+
+private:
+    std::vector<uint32_t> succ_, pred_;
+    uint32_t first_, n_;
+};
 
 int rerank(const uint32_t *ring, const uint64_t *rails, uint32_t n, uint32_t *out_ring, uint32_t *n_relocated)
 {
@@ -23,46 +63,47 @@ int rerank(const uint32_t *ring, const uint64_t *rails, uint32_t n, uint32_t *ou
         if (ring[i] >= n || seen[ring[i]]) return R2_ERR_INVALID;  // must be a permutation of 0..n-1
         seen[ring[i]] = 1;
     }
-    std::vector<uint32_t> cur(ring, ring + n);
-    uint32_t moved = 0;
 
-    uint32_t b_global = 65;
-    for (uint32_t i = 0; i < n; ++i) b_global = std::min(b_global, (uint32_t)__builtin_popcountll(rails[i]));
-
-    struct Cand {
-        uint32_t u, v, gap;
-    };
-    std::vector<Cand> cands;
-    for (uint32_t i = 0; i < n; ++i) {
-        const uint32_t u = ring[i], v = ring[(i + 1) % n];
-        const uint32_t cap = shared_rails(rails[u], rails[v]);
-        if (cap < b_global) cands.push_back({u, v, b_global - cap});
+    // rails two nodes have in common, and the fewest rails any node has left
+    std::vector<uint8_t> common((size_t)n * n);
+    uint32_t floor_width = 64;
+    for (uint32_t a = 0; a < n; ++a) {
+        const uint32_t own = (uint32_t)__builtin_popcountll(rails[a]);
+        if (own < floor_width) floor_width = own;
+        for (uint32_t b = 0; b < n; ++b) common[(size_t)a * n + b] = (uint8_t)__builtin_popcountll(rails[a] & rails[b]);
     }
-    // worst gap first; equal gaps keep their order round the ring
-    std::stable_sort(cands.begin(), cands.end(), [](const Cand &a, const Cand &b) { return a.gap > b.gap; });
+    auto wide = [&](uint32_t a, uint32_t b) { return common[(size_t)a * n + b] >= floor_width; };
 
-    for (const Cand &c : cands) {
-        // position of u; the pair is only repaired while v still follows u
-        uint32_t pu = 0;
-        while (cur[pu] != c.u) ++pu;
-        if (n < 3 || cur[(pu + 1) % n] != c.v) continue;
-        for (uint32_t pw = 0; pw < n; ++pw) {
-            const uint32_t w = cur[pw];
-            if (w == c.u || w == c.v) continue;
-            const uint32_t x = cur[(pw + n - 1) % n], y = cur[(pw + 1) % n];
-            const uint32_t new_cap = std::min(shared_rails(rails[c.u], rails[w]), shared_rails(rails[w], rails[c.v]));
-            const uint32_t removal_cap = shared_rails(rails[x], rails[y]);
-            if (new_cap >= b_global && removal_cap >= b_global) {
-                cur.erase(cur.begin() + pw);
-                uint32_t qu = 0;
-                while (cur[qu] != c.u) ++qu;
-                cur.insert(cur.begin() + qu + 1, w);
-                ++moved;
-                break;
+    // the edges of the ring as given that are too narrow, bucketed by how many rails they lack
+    struct Edge {
+        uint32_t tail, head;
+    };
+    std::vector<std::vector<Edge>> by_gap(65);
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t a = ring[i], b = ring[(i + 1) % n];
+        const uint32_t have = common[(size_t)a * n + b];
+        if (have < floor_width) by_gap[floor_width - have].push_back({a, b});
+    }
+
+    LinkedRing lr(ring, n);
+    uint32_t moved = 0;
+    for (uint32_t gap = 64; gap >= 1 && n >= 3; --gap) {
+        for (const Edge &e : by_gap[gap]) {
+            if (lr.after(e.tail) != e.head) continue;  // an earlier move already separated the pair
+            uint32_t w = lr.first();
+            for (uint32_t seen_nodes = 0; seen_nodes < n; ++seen_nodes, w = lr.after(w)) {
+                if (w == e.tail || w == e.head) continue;
+                // w bridges the pair if it is wide towards both, and its own neighbours are wide
+                // towards each other once it has left
+                if (wide(e.tail, w) && wide(w, e.head) && wide(lr.before(w), lr.after(w))) {
+                    lr.move_behind(w, e.tail);
+                    ++moved;
+                    break;
+                }
             }
         }
     }
-    std::copy(cur.begin(), cur.end(), out_ring);
+    lr.write(out_ring);
     if (n_relocated) *n_relocated = moved;
     return R2_OK;
 }

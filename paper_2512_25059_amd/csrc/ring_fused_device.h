@@ -94,13 +94,6 @@ __device__ inline uint32_t find_channel_flat(RowPtr off, uint32_t C, uint32_t to
     return c;
 }
 
-#ifdef R2_FUSED_TIMING
-__device__ uint64_t g_dbg[256];
-#define R2_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_dbg[i] = wall_clock64(); } while (0)
-#else
-#define R2_STAMP(i) do {} while (0)
-#endif
-
 // PARTITION: the kernel computes the table rows it needs itself, from the channel states in `eb`
 // (every workgroup for its own use, in LDS; the first column of each slab also records them in
 // the workspace and the log), so that no partition launch has to run in front of it.
@@ -127,7 +120,6 @@ template <bool BF16, bool PARTITION, unsigned U>
 __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
 {
     const uint32_t touched = touch_kernel_arguments(sizeof(FusedArgs) + (PARTITION ? sizeof(EpochBatch) : 0));
-    R2_STAMP(0);
     __shared__ ColInfo info[2 * R2_MAX_RANKS];  // by transmission within the slab
     const uint32_t l = (uint32_t)(blockIdx.x / a.cols_per_chunk);
     const uint64_t k = blockIdx.x - (uint64_t)l * a.cols_per_chunk;
@@ -223,7 +215,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             if (c == 0) changed[t] = t == ts;  // the first transmission of a state, or of this launch
         }
         __syncthreads();
-        R2_STAMP(1);
         rows = s_rows - (uint64_t)t_first * row;
         slow = ragged_width;
     } else {
@@ -242,7 +233,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
             info[t].c = c;
         }
         __syncthreads();
-        R2_STAMP(1);
         // (lane c compares entry c of the two rows)
         for (uint32_t t = t_first + wave; t < t_end; t += n_waves) {
             bool eq = false;
@@ -390,7 +380,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                             store16<false>(out_base + dcur[u], v);
                         }
                         __syncthreads();  // the next step reads what other waves of this workgroup just staged
-                        R2_STAMP(2 + j);
                         ++j;
                     };
                     using Yes = std::integral_constant<bool, true>;
@@ -434,7 +423,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                         }
                         next_chunk();
                         __syncthreads();  // the next step reads what other waves of this workgroup just staged
-                        R2_STAMP(2 + j);
                         ++j;
                     };
                     while (j < j_end) {
@@ -459,7 +447,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                     column_step<U, KIND, HAS_OUT, BF16>(ain, aout, aloc);
                     next_chunk();
                     __syncthreads();  // the next step reads what other waves of this workgroup just staged
-                    R2_STAMP(2 + j);
                 }
             };
             using std::integral_constant;
@@ -481,7 +468,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                 }
                 next_chunk();
                 __syncthreads();
-                R2_STAMP(2);
                 j = 1;
             } else {
                 deltas_for(j - 1, dcur);  // the table the launch's first step reads with
@@ -512,7 +498,6 @@ __device__ inline void fused_body(const FusedArgs &a, const EpochBatch *eb)
                               slab_stage + ((uint64_t)(j & 1) * a.R + r) * per_rank, din, dout);
                 }
                 __syncthreads();  // the next step reads what other waves of this workgroup just staged
-                R2_STAMP(2 + j);
             }
         }
         record_rows();
@@ -604,17 +589,6 @@ __global__ __launch_bounds__(kMaxFusedWaves *kWave) void ring_fused_partition_ke
 {
     fused_body<BF16, true, U>(a, &eb);
 }
-
-#ifdef R2_FUSED_TIMING
-}  // namespace
-}  // namespace r2
-extern "C" __attribute__((weak)) int r2_debug_read(uint64_t *out, int n)  // weak: two translation units include this header
-{
-    return hipMemcpyFromSymbol(out, HIP_SYMBOL(r2::g_dbg), n * 8) == hipSuccess ? 0 : -5;
-}
-namespace r2 {
-namespace {
-#endif
 
 }  // namespace
 }  // namespace r2

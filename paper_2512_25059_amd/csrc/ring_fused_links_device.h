@@ -31,7 +31,6 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
 {
     const uint32_t touched =
         touch_kernel_arguments(sizeof(FusedArgs) + 8 + (PARTITION ? sizeof(EpochBatch) : 0));
-    R2_STAMP(0);
     extern __shared__ uint64_t s_link[];
     constexpr uint64_t kWidth = (uint64_t)kWave * 16 * U;
     const uint32_t l = (uint32_t)(blockIdx.x / a.cols_per_chunk);
@@ -102,14 +101,12 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
             }
         }
         __syncthreads();
-        R2_STAMP(1);
     } else {
         for (uint32_t i = threadIdx.x; i < R * link_entries; i += blockDim.x) {
             const uint32_t link = i / link_entries, e = i - link * link_entries;
             s_link[i] = a.tables[((uint64_t)link * link_rows + (uint64_t)l * a.T_slab + t_first) * row + e];
         }
         __syncthreads();
-        R2_STAMP(1);
         for (uint32_t i = threadIdx.x; i < R * n_t; i += blockDim.x) {
             const R2_LDS uint64_t *off = rows + (uint64_t)i * row;
             const uint32_t c = find_channel_flat(off, C, top, b0);
@@ -123,7 +120,6 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
         }
         __syncthreads();
     }
-    R2_STAMP(2);
     // The first column of a slab records the rows for the caller: last of all, so that no step waits
     // for these stores.
     auto record_rows = [&]() {
@@ -181,7 +177,6 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
             dout[u] = stage_offset(r, t_first, bu[u]);
         }
         uint32_t j = a.j0;
-        R2_STAMP(3);
         // One step, its kind fixed at compile time so that the code is straight-line and the waits
         // the compiler places count exactly the loads that variant issued (with a run-time "is the
         // next local chunk loaded ahead" they would cover the worst case, and the load ahead would
@@ -226,7 +221,6 @@ __device__ inline void fused_links_body(const FusedArgs &a, const uint64_t link_
                 for (unsigned u = 0; u < U; ++u) din[u] = stage_offset(peer, j, bu[u]);
             }
             __syncthreads();  // the next step reads what other waves of this workgroup just staged
-            R2_STAMP(4 + j);
             ++j;
         };
         using Send = std::integral_constant<int, 0>;

@@ -19,6 +19,10 @@ def r2():
     return pkg
 
 
+def _as_masks(rails, n):
+    return [sum(1 << r for r in rails[i]) for i in range(n)]
+
+
 def _narrow_edges(ring, rails):
     b = min(len(rails[x]) for x in ring)
     n = len(ring)
@@ -34,6 +38,42 @@ def test_paper_scenario_adjacent_nodes_lose_different_rails():
     assert moved == 1
     assert ring == [0, 2, 1, 3]  # pencil: H1 (node 2) qualifies first; its old neighbours B and H2 share 7
     assert _narrow_edges(ring, rails) == 0
+
+
+# More rings worked by hand from Algorithm 1 and the readings in the oracle's header.  Each one is a
+# (ring, rails per node, ring afterwards, relocations) tuple; the reasoning is in the comments.
+HAND_RINGS = [
+    # Six nodes, four rails, nodes 0 and 1 each lost a different rail: they share 2 < 3.  Walking the
+    # ring from its start, node 2 (all rails) is the first that is wide towards both, and its own
+    # neighbours 1 and 3 share 3 rails once it has left.
+    ([0, 1, 2, 3, 4, 5],
+     {0: {1, 2, 3}, 1: {0, 2, 3}, 2: {0, 1, 2, 3}, 3: {0, 1, 2, 3}, 4: {0, 1, 2, 3}, 5: {0, 1, 2, 3}},
+     [0, 2, 1, 3, 4, 5], 1),
+    # The first node that would fit must stay where it is: node 2 is wide towards 0 and 1, but its
+    # neighbours 1 = {0,2,3} and 3 = {0,1,2} would share only 2 rails.  Node 3 is narrow towards 0.
+    # Node 4 fits and its neighbours 3 and 5 share 3: it moves.
+    ([0, 1, 2, 3, 4, 5],
+     {0: {1, 2, 3}, 1: {0, 2, 3}, 2: {0, 1, 2, 3}, 3: {0, 1, 2}, 4: {0, 1, 2, 3}, 5: {0, 1, 2, 3}},
+     [0, 4, 1, 2, 3, 5], 1),
+    # Seven rails, the narrowest node has 3.  Four edges in a row lack 2 rails each: (0,1), (1,2),
+    # (2,3), (3,4); equal gaps are taken in ring order.  (0,1): node 2 shares only {0,2} with node 0;
+    # node 3 = {0,1,3,4,5} shares 3 with node 0 and 3 with node 1, and its neighbours 2 and 4 share
+    # {0,2,6}: it moves behind node 0.  (1,2): nobody is wide towards both.  (2,3) and (3,4): node 3
+    # has gone from between them, the pairs are no longer neighbours and are skipped.
+    ([0, 1, 2, 3, 4, 5],
+     {0: {0, 1, 2, 3}, 1: {3, 4, 5, 6}, 2: {0, 2, 6}, 3: {0, 1, 3, 4, 5}, 4: {0, 2, 6}, 5: {0, 1, 2, 3, 6}},
+     [0, 3, 1, 2, 4, 5], 1),
+]
+
+
+@pytest.mark.parametrize("ring,rails,want,moves", HAND_RINGS, ids=["first_fit", "first_fit_must_stay", "ties_and_separated_pairs"])
+def test_hand_worked_rings(ring, rails, want, moves):
+    assert bridge_rerank(ring, rails) == (want, moves)
+
+
+@pytest.mark.parametrize("ring,rails,want,moves", HAND_RINGS, ids=["first_fit", "first_fit_must_stay", "ties_and_separated_pairs"])
+def test_product_on_hand_worked_rings(r2, ring, rails, want, moves):
+    assert r2.r2_bridge_rerank(ring, _as_masks(rails, len(ring))) == (want, moves)
 
 
 def test_healthy_ring_is_left_alone():
@@ -95,10 +135,6 @@ def test_worst_gap_is_repaired_first():
         assert still_adjacent == (not feasible)
         checked += 1
     assert checked > 500
-
-
-def _as_masks(rails, n):
-    return [sum(1 << r for r in rails[i]) for i in range(n)]
 
 
 def test_product_matches_oracle_exhaustive_tiny(r2):
