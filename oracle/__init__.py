@@ -8,7 +8,8 @@ never imports the product package.
 step and the ring's result by definition; the other modules compose those in Python:
 ``split`` and ``recursive`` (the failure-aware all-reduce schedules and their planners),
 ``rerank`` (bridge re-ranking), ``sendrecv`` and ``collectives`` (the other collectives under
-R2CCL-Balance), ``rails`` (rings whose servers each have a channel state of their own).
+R2CCL-Balance), ``rails`` (rings whose servers each have a channel state of their own), ``inflight`` (the ring when a
+channel fails while a transmission is in flight).
 """
 from .r2_oracle import (  # noqa: F401
     BF16,
