@@ -303,6 +303,36 @@ int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_bufs,
                           void *workspace, uint64_t workspace_bytes,
                           uint64_t *offsets_log, void *stream);
 
+/* The ring run when failures strike while a transmission is in flight -- Sec. 4.3, Technique II (a
+ * failure may leave a chunk partially transferred; send buffers stay intact until completion and every
+ * NIC is registered on every buffer, so the sender rewinds to the first chunk without a completion and
+ * retransmits it over the NICs that are left; completed chunks stay as they are) with the shares of
+ * Sec. 5.1.
+ *
+ * As r2_ring_allreduce_sim, plus in_flight: a HOST array of n_epochs bytes (NULL = all zero).
+ * in_flight[i] != 0 says that the failures of epoch i strike DURING transmission k = epochs[i].t_start
+ * instead of before it:
+ *   - transmission k is staged, and read, with the table of the state before the epoch (epoch i-1):
+ *     row k of the tables and of offsets_log is that state's partition; the receiver's layout does not
+ *     change and no data moves because of the failure;
+ *   - the slices of the channels that newly failed are re-carried by the channels the epoch leaves up:
+ *     block i of `plans` is the failover plan of that transmission exactly as r2_rollback_plan_device
+ *     defines it (offsets = row k, weights = epoch i's, mask_before = epoch i-1's, mask_after = epoch
+ *     i's), made by a launch of the same call in front of the run, without a host synchronisation;
+ *   - transmissions after k are cut by epoch i's own state, as for an ordinary epoch.
+ * An in-flight epoch may only add failures to the state before it (recoveries are found by re-probing
+ * between transmissions, Sec. 4.2, and come as ordinary epochs) and cannot be the first epoch:
+ * R2_ERR_INVALID otherwise.  One that starts beyond the run has no effect.
+ *   plans  DEVICE [n_epochs][n_channels][n_channels+1], out; every row is written, zero for epochs
+ *          that are not in flight or start beyond the run, for channels that did not newly fail and for
+ *          empty slices.  May be NULL if no epoch is in flight.
+ * The result in the rank buffers is the plain run's.  Asynchronous on `stream`; allocates no device
+ * memory (a host copy of the epoch list is made for the duration of the call). */
+int r2_ring_allreduce_sim_inflight(const r2_sim_desc *desc, void *const *rank_bufs,
+                                   const r2_epoch *epochs, const uint8_t *in_flight, uint32_t n_epochs,
+                                   void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log,
+                                   uint64_t *plans, void *stream);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid it): r2_ring_allreduce_sim without the workspace argument.  The tables and the
  * stage area live in a device array inside the library, R2_STATIC_WORKSPACE_BYTES long, which every GPU

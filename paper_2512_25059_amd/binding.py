@@ -206,6 +206,8 @@ def load_library():
     lib.r2_ring_allreduce_sim.argtypes = [pd, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_ring_allreduce_sim_static.restype = i32
     lib.r2_ring_allreduce_sim_static.argtypes = [pd, vp, vp, u32, vp, vp]
+    lib.r2_ring_allreduce_sim_inflight.restype = i32
+    lib.r2_ring_allreduce_sim_inflight.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp, vp]
     lib.r2_sendrecv_sim.restype = i32
     lib.r2_sendrecv_sim.argtypes = [pd, vp, vp, vp, u32, vp, u64, vp, vp]
     lib.r2_collective_sim.restype = i32
@@ -594,6 +596,28 @@ def r2_ring_allreduce_sim(desc: SimDesc, rank_bufs: Sequence, epochs, workspace,
                                               wp, wb, _ptr(offsets_log), _stream(stream))
     del arr, keep
     _check(rc, "r2_ring_allreduce_sim")
+
+
+def r2_ring_allreduce_sim_inflight(desc: SimDesc, rank_bufs: Sequence, epochs, in_flight: Optional[Sequence[bool]],
+                                   workspace, offsets_log: Optional[torch.Tensor] = None,
+                                   plans: Optional[torch.Tensor] = None, stream=None,
+                                   workspace_bytes: Optional[int] = None) -> None:
+    """in_flight[i]: epoch i's failures strike during transmission epochs[i][0]; plans: device tensor of
+    n_epochs * C * (C+1) 8-byte integers."""
+    _check_lists(desc, rank_bufs, epochs)
+    if in_flight is not None and len(in_flight) != len(epochs):
+        raise ValueError("r2_ring_allreduce_sim_inflight: one flag per epoch")
+    if plans is not None:
+        assert plans.element_size() == 8 and plans.numel() >= len(epochs) * desc.n_channels * (desc.n_channels + 1)
+    arr, p = _ptr_array(rank_bufs)
+    ep, keep = _epoch_array(epochs)
+    fl = (C.c_uint8 * max(len(epochs), 1))(*[1 if x else 0 for x in in_flight]) if in_flight is not None else None
+    wp, wb = _ws(workspace, workspace_bytes)
+    rc = load_library().r2_ring_allreduce_sim_inflight(C.byref(desc.c()), p, C.cast(ep, C.c_void_p),
+                                                       C.cast(fl, C.c_void_p) if fl is not None else None, len(epochs),
+                                                       wp, wb, _ptr(offsets_log), _ptr(plans), _stream(stream))
+    del arr, keep, fl
+    _check(rc, "r2_ring_allreduce_sim_inflight")
 
 
 STATIC_WORKSPACE_BYTES = 72 << 20  # R2_STATIC_WORKSPACE_BYTES

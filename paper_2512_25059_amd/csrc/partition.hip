@@ -69,6 +69,43 @@ __global__ __launch_bounds__(kBlock) void rollback_plan_kernel(
     if (lane == 0 && status && st != R2_OK) atomicMin(status + p, st);
 }
 
+// Failover plans of a run's in-flight epochs (Sec. 4.3 Technique II): wave (k, f) looks at epoch k of
+// the batch.  If that epoch strikes in flight within the run and channel f newly fails in it, the wave
+// cuts the chunk by the state before (epoch k-1) to find slice f, and shares that slice's bytes out
+// over the channels the epoch leaves up; otherwise row f of the epoch's plan is zero.  Epoch 0 of a
+// batch only serves as the state before epoch 1, unless `first_is_real` (then it is the run's first
+// epoch, which has no plan: zero rows).
+__global__ __launch_bounds__(kBlock) void inflight_plan_kernel(const EpochBatch batch, uint32_t in_flight_bits,
+                                                               uint32_t first_epoch, bool first_is_real, uint32_t C,
+                                                               uint32_t align, uint64_t bytes, uint64_t n_tx,
+                                                               uint64_t *__restrict__ plans)
+{
+    const uint64_t w_id = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (w_id >= (uint64_t)batch.n * C) return;  // whole wavefront leaves together
+    const uint32_t k = (uint32_t)(w_id / C), f = (uint32_t)(w_id - (uint64_t)k * C);
+    if (k == 0 && !first_is_real) return;
+    const unsigned lane = threadIdx.x & (kWave - 1);
+    uint64_t *row = plans + (((uint64_t)first_epoch + k) * C + f) * (C + 1);
+    const bool struck = k > 0 && ((in_flight_bits >> k) & 1u) && batch.t_start[k] < n_tx;
+    const uint64_t before = k > 0 ? batch.fail_mask[k - 1] : 0, after = batch.fail_mask[k];
+    uint64_t len = 0;
+    if (struck && ((after >> f) & 1u) && !((before >> f) & 1u)) {
+        uint64_t W;
+        const uint32_t w_old = lane < C ? batch.weights[(k - 1) * C + lane] : 0;
+        const uint64_t cut = partition_lane(w_old, (before >> lane) & 1u, C, bytes, align, &W);
+        const uint64_t lo = __shfl(cut, f, kWave);
+        const uint64_t hi = f + 1 < C ? __shfl(cut, f + 1, kWave) : bytes;
+        len = W ? hi - lo : 0;
+    }
+    if (len == 0) {
+        if (lane <= C) row[lane] = 0;
+        if (C == kWave && lane == 0) row[C] = 0;
+        return;
+    }
+    const uint32_t w_new = lane < C ? batch.weights[k * C + lane] : 0;
+    partition_wave(w_new, (after >> lane) & 1u, C, len, align, row, nullptr, nullptr);
+}
+
 // The row r2_partition (host pointers in, host pointers out) has the device write.
 static __device__ __align__(256) uint64_t host_call_row[R2_MAX_CHANNELS + 1];
 
@@ -94,6 +131,29 @@ int launch_partition_epochs(const r2_epoch *epochs, uint32_t n_epochs, uint32_t 
                            b, C, align, chunk_bytes, t_begin, t_end, tables, log);
         const int rc = hip_rc(hipGetLastError());
         if (rc) return rc;
+    }
+    return R2_OK;
+}
+
+int launch_inflight_plans(const r2_epoch *epochs, const uint8_t *in_flight, uint32_t n_epochs, uint32_t C,
+                          uint32_t align, uint64_t chunk_bytes, uint64_t n_tx, uint64_t *plans, hipStream_t stream)
+{
+    const uint32_t per_batch = epochs_per_batch(C);  // >= 10: a batch holds the state before and its successors
+    for (uint32_t i0 = 0; i0 < n_epochs;) {
+        const uint32_t i1 = i0 + per_batch < n_epochs ? i0 + per_batch : n_epochs;
+        EpochBatch b;
+        fill_batch(b, epochs, i0, i1, C);
+        uint32_t bits = 0;
+        for (uint32_t k = 1; k < b.n; ++k)
+            if (in_flight && in_flight[i0 + k]) bits |= 1u << k;
+        const uint64_t waves = (uint64_t)b.n * C;
+        const unsigned blocks = (unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock);
+        hipLaunchKernelGGL(inflight_plan_kernel, dim3(blocks), dim3(kBlock), 0, stream, b, bits, i0, i0 == 0, C,
+                           align, chunk_bytes, n_tx, plans);
+        const int rc = hip_rc(hipGetLastError());
+        if (rc) return rc;
+        if (i1 == n_epochs) break;
+        i0 = i1 - 1;  // the last epoch of this batch is the state before the next batch's first
     }
     return R2_OK;
 }

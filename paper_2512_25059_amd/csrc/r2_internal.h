@@ -27,6 +27,12 @@ int launch_partition_epochs(const r2_epoch *epochs, uint32_t n_epochs, uint32_t 
                             uint64_t chunk_bytes, uint64_t n_tx, uint64_t *tables, uint64_t *log,
                             hipStream_t stream);
 
+// Enqueue the failover plans of the epochs marked in flight (in_flight[i] != 0; may be null): plans is
+// device [n_epochs][C][C+1], every row of which is written (zero where there is nothing to re-carry).
+// Epochs and flags must already be validated.
+int launch_inflight_plans(const r2_epoch *epochs, const uint8_t *in_flight, uint32_t n_epochs, uint32_t C,
+                          uint32_t align, uint64_t chunk_bytes, uint64_t n_tx, uint64_t *plans, hipStream_t stream);
+
 // Independent pieces of one call (the rings of a split or recursive all-reduce) run side by side:
 // the caller's stream forks into a few library-owned streams of default priority and joins them
 // again before the call's dependent work, all with events, so the call stays asynchronous and in

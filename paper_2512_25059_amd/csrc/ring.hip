@@ -8,6 +8,8 @@
 // Sec. 6 (servers that lost different rails: the step kernel picks its tables per link; the host side
 // of that ring is in rails.hip).
 #include <mutex>
+#include <new>
+#include <vector>
 
 #include "sim_shape.h"
 
@@ -546,6 +548,62 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
     return R2_OK;
+}
+
+// ---------------------------------------------------------------- failures that strike in flight
+//
+// Sec. 4.3 Technique II.  An epoch marked in flight leaves the transmission it strikes in with the
+// table of the state before it; the tables therefore see that epoch one transmission later, and an
+// epoch that a later one overtakes that way never cuts a table.  Its failover plan is made by a
+// launch of its own in front of the run.
+extern "C" int r2_ring_allreduce_sim_inflight(const r2_sim_desc *desc, void *const *rank_bufs,
+                                              const r2_epoch *epochs, const uint8_t *in_flight, uint32_t n_epochs,
+                                              void *workspace, uint64_t workspace_bytes, uint64_t *offsets_log,
+                                              uint64_t *plans, void *stream)
+{
+    SimShape s;
+    int rc = shape_of(desc, s);
+    if (rc) return rc;
+    if (s.links) return R2_ERR_INVALID;
+    if ((rc = check_epochs(epochs, n_epochs, s))) return rc;
+    bool any = false;
+    for (uint32_t i = 0; in_flight && i < n_epochs; ++i) {
+        if (!in_flight[i]) continue;
+        if (i == 0) return R2_ERR_INVALID;  // no table before the first state
+        if (epochs[i - 1].fail_mask & ~epochs[i].fail_mask) return R2_ERR_INVALID;  // failures only: recoveries
+                                                                                    // come between transmissions
+        any = true;
+    }
+    if (any && !plans) return R2_ERR_INVALID;
+    if (!any) {
+        if (plans && s.chunk_bytes) {  // every row is written: zero
+            rc = launch_inflight_plans(epochs, nullptr, n_epochs, s.C, desc->align, s.chunk_bytes, s.n_tx, plans,
+                                       (hipStream_t)stream);
+            if (rc) return rc;
+        }
+        return r2_ring_allreduce_sim(desc, rank_bufs, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream);
+    }
+    try {
+        std::vector<r2_epoch> seen;  // the list as the tables see it
+        seen.reserve(n_epochs);
+        for (uint32_t i = 0; i < n_epochs; ++i) {
+            r2_epoch e = epochs[i];
+            if (in_flight[i]) ++e.t_start;
+            while (!seen.empty() && seen.back().t_start >= e.t_start) seen.pop_back();
+            seen.push_back(e);
+        }
+        if (!rank_bufs) return R2_ERR_INVALID;
+        if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
+        if (s.chunk_bytes) {
+            rc = launch_inflight_plans(epochs, in_flight, n_epochs, s.C, desc->align, s.chunk_bytes, s.n_tx, plans,
+                                       (hipStream_t)stream);
+            if (rc) return rc;
+        }
+        return r2_ring_allreduce_sim(desc, rank_bufs, seen.data(), (uint32_t)seen.size(), workspace, workspace_bytes,
+                                     offsets_log, stream);
+    } catch (const std::bad_alloc &) {
+        return R2_ERR_CAPACITY;
+    }
 }
 
 // ---------------------------------------------------------------- the run whose workspace is a static array
