@@ -490,19 +490,25 @@ int r2_split_allreduce_sim(const r2_split_desc *desc, void *const *rank_bufs, co
  *
  * Plan (HOST, integer and double arithmetic): rank r's own bandwidth is the weight of the channels it
  * still has.  Level 0 holds all ranks.  The next level drops every rank whose own bandwidth is the
- * smallest among the current members, as long as two ranks remain; a level's ring runs on the
- * channels that are up at ALL its members (fail_mask = union of the members' failed channels), its
- * bandwidth is their weight, its increment the gain over the previous level; a peel that gains
- * nothing makes no level and the peeling goes on.  share_k is proportional to
- * increment_k / (2(p_k-1)/p_k), p_k = members_k * gpus_per_rank, so that all rings finish together
- * when latency is ignored (for two levels: T1 = T2 of Sec. 5.2).
- * R2_ERR_NO_HEALTHY_CHANNEL if no channel is up at every rank. */
+ * smallest among the current members, as long as two ranks remain.  A level's ring takes its members in
+ * rank order, starting after the highest-numbered rank left out (level 0: from rank 0), re-ranked by
+ * r2_bridge_rerank (Sec. 6: re-ranking is applied at every level, since skipping the slower nodes puts
+ * nodes side by side that lost different rails); it runs link by link as r2_ring_rails_sim does, a link
+ * carrying what both its ends still have, so its bandwidth is its narrowest link's and its increment the
+ * gain over the previous level; a peel that gains nothing makes no level and the peeling goes on.
+ * Shares minimise the completion time below with alpha = 0: with u_k = share_k / increment_k and
+ * f_k = 2(p_k-1)/p_k, p_k = members_k * gpus_per_rank, that time is max_k f_k u_k + max_{k>=1} u_k, and
+ * its minimum lies where the rings of the levels up to some j finish together (u_k = tau/f_k) and the
+ * levels from j on share one u (= tau/f_j; their shares are then exactly proportional to the bandwidth
+ * they add, as Sec. 6 words it); every j is tried, ties go to the smallest.  For two levels this is
+ * T1 = T2 of Sec. 5.2.  R2_ERR_NO_HEALTHY_CHANNEL if a link of the global ring is left without a
+ * channel even after re-ranking. */
 #define R2_MAX_LEVELS 16
 
 typedef struct {
     uint64_t members;   /* bit r: rank r takes part in this level's ring           */
-    uint64_t fail_mask; /* channel state of the level's ring                       */
-    uint64_t bandwidth; /* weight of the channels healthy under fail_mask          */
+    uint64_t fail_mask; /* channels down at some member (the ring itself runs link by link) */
+    uint64_t bandwidth; /* the ring's: that of its narrowest link, in its re-ranked order   */
     uint64_t increment; /* bandwidth minus the previous level's (level 0: itself)  */
     double share;       /* fraction of the data this level reduces                 */
 } r2_level;
@@ -512,11 +518,18 @@ typedef struct {
 int r2_recursive_plan(uint32_t n_ranks, uint32_t gpus_per_rank, uint32_t n_channels, const uint32_t *weights,
                       const uint64_t *fail_masks, uint32_t max_levels, r2_level *levels, uint32_t *n_levels);
 
+/* The order in which the ring of a level visits its members (HOST): `members` in rank order starting
+ * after the highest-numbered rank that is not a member, re-ranked by r2_bridge_rerank with every rank's
+ * surviving channels as its rails.  order: HOST, room for popcount(members) ranks.  fail_masks: HOST
+ * [n_ranks].  R2_ERR_INVALID for fewer than two members or members beyond n_ranks. */
+int r2_recursive_ring_order(uint32_t n_ranks, uint32_t n_channels, const uint64_t *fail_masks,
+                            uint64_t members, uint32_t *order);
+
 /* alpha-beta completion time of a plan (Sec. 6, last paragraph; Sec. 8 "AllReduce performance"):
  *   max_k [ 2(p_k-1) alpha + 2(p_k-1)/p_k * share_k * bytes / (increment_k * beta) ]
  * + max_{k>=1} [ hops_k * alpha + share_k * bytes / (increment_k * beta) ],
- * hops_k = members_k + 2 * (n_ranks - members_k) - 1 (the broadcast chain), beta = bytes per second
- * per unit of weight.  With alpha = 0 and two levels this is T(Y) = max(T1, T2) + T3 of Sec. 5.2;
+ * hops_k = members_k + 2 * (n_ranks - members_k) - 1 (the broadcast chain; relay hops are not counted),
+ * beta = bytes per second per unit of weight.  With alpha = 0 and two levels this is T(Y) = max(T1, T2) + T3 of Sec. 5.2;
  * one level is the plain ring at the slowest server's balanced rate (R2CCL-Balance).
  * Negative if an argument is invalid. */
 double r2_recursive_time(uint32_t n_ranks, uint32_t gpus_per_rank, const r2_level *levels, uint32_t n_levels,
@@ -533,15 +546,19 @@ int r2_select_strategy(uint32_t n_ranks, uint32_t gpus_per_rank, uint32_t n_chan
 
 /* The schedule on simulated ranks (a rank stands for a server).  Every rank buffer is cut into
  * n_levels consecutive segments of level_elems[k] elements.  Segment k goes through
- *   1. a ring all-reduce over level k's members under the level's channel state, the members taken
- *      in ring order starting after the highest-numbered excluded rank (level 0: ranks 0..R-1), and,
- *   2. if the level excludes ranks, the broadcast chain: the excluded ranks, in ascending order,
- *      add their segments up hop by hop; each member in the order above adds that sum to its ring
- *      result and relays it unchanged (R2_OP_SUM_FORWARD); the last member sends its finished result
- *      on, and the excluded ranks copy it and pass it along in ascending order.  The transfer between
- *      two ranks is cut by the union of their failed channels.
- * Afterwards every rank holds, in segment k, fold(members in that order) + (running sum of the
- * excluded ranks), rounded to the buffer type after every addition.  The levels touch disjoint
+ *   1. a ring all-reduce over level k's members in the order r2_recursive_ring_order gives, with a
+ *      table per link (r2_ring_rails_sim: a link carries what both its ends still have), and,
+ *   2. if the level leaves ranks out, the broadcast chain: the ranks left out, in ascending order, add
+ *      their segments up hop by hop; each member, in the ring's order, adds that sum to its ring result
+ *      and relays it unchanged (R2_OP_SUM_FORWARD); the last member sends its finished result on, and
+ *      the ranks left out copy it and pass it along in ascending order.  The transfer between two ranks
+ *      is cut by the union of their failed channels.  Where two consecutive ranks of that walk have no
+ *      channel in common (they lost complementary rails), the hop goes through a third rank that has a
+ *      channel in common with both and forwards the data untouched, its own segment not involved: the
+ *      first such rank among the members in the ring's order, then among the ranks left out in
+ *      ascending order; R2_ERR_NO_HEALTHY_CHANNEL, before anything is launched, if there is none.
+ * Afterwards every rank holds, in segment k, fold(members in the ring's order) + (running sum of the
+ * ranks left out), rounded to the buffer type after every addition.  The levels touch disjoint
  * segments and have workspaces of their own, so they run side by side, as the paper's reductions
  * do: level k on one of a few library-owned streams (default priority, created once per device),
  * forked off `stream` and joined to it again with events before the call returns to the caller's
@@ -569,12 +586,12 @@ typedef struct {
 int r2_recursive_segments(const r2_recursive_desc *desc, const r2_level *levels, uint64_t *level_elems);
 
 /* Workspace (device, 256-byte aligned): per level, its ring workspace, its broadcast's offsets
- * tables and double-buffered stage.  0 if an argument is invalid. */
+ * tables, double-buffered stage and a landing place for relayed data.  0 if an argument is invalid. */
 uint64_t r2_recursive_workspace_bytes(const r2_recursive_desc *desc, const r2_level *levels,
                                       const uint64_t *level_elems);
 
 /* levels, level_elems, weights, fail_masks: HOST arrays (n_levels, n_levels, n_channels, n_ranks).
- * Only `members` and `fail_mask` of a level are read; members must be nested and hold >= 2 ranks.
+ * Only `members` of a level is read; members must be nested and hold >= 2 ranks.
  * Asynchronous on `stream`; allocates nothing. */
 int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *const *rank_bufs, const uint32_t *weights,
                                const uint64_t *fail_masks, const r2_level *levels, const uint64_t *level_elems,

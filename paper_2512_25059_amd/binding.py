@@ -173,6 +173,8 @@ def load_library():
     lib.r2_split_allreduce_sim.argtypes = [C.POINTER(_SplitDesc), vp, vp, u64, vp, u64, vp]
     lib.r2_recursive_plan.restype = i32
     lib.r2_recursive_plan.argtypes = [u32, u32, u32, vp, vp, u32, vp, vp]
+    lib.r2_recursive_ring_order.restype = i32
+    lib.r2_recursive_ring_order.argtypes = [u32, u32, vp, u64, vp]
     lib.r2_recursive_time.restype = C.c_double
     lib.r2_recursive_time.argtypes = [u32, u32, vp, u32, C.c_double, C.c_double, C.c_double]
     lib.r2_select_strategy.restype = i32
@@ -366,6 +368,17 @@ def r2_recursive_plan(weights: Sequence[int], fail_masks: Sequence[int], gpus_pe
     _check(rc, "r2_recursive_plan")
     return [Level(int(l.members), int(l.fail_mask), int(l.bandwidth), int(l.increment), float(l.share))
             for l in out[:n.value]]
+
+
+def r2_recursive_ring_order(n_channels: int, fail_masks: Sequence[int], members: int) -> List[int]:
+    """Host call: the order in which the ring over `members` (a bit mask of ranks) visits them."""
+    m = _u64s(fail_masks)
+    n = bin(int(members)).count("1")
+    out = (C.c_uint32 * max(n, 1))()
+    rc = load_library().r2_recursive_ring_order(len(fail_masks), int(n_channels), C.cast(m, C.c_void_p), int(members),
+                                                C.cast(out, C.c_void_p))
+    _check(rc, "r2_recursive_ring_order")
+    return list(out)[:n]
 
 
 def r2_recursive_time(n_ranks: int, gpus_per_rank: int, levels: Sequence[Level], nbytes: float, alpha: float,

@@ -1,8 +1,13 @@
 // Recursive R2CCL-AllReduce (R2CCL paper, Sec. 6, on top of Sec. 5.2): with several failures the
 // servers form a spectrum of bandwidths; a global ring runs at the slowest server's rate, the
-// slowest is left out and a faster sub-ring formed from the rest, and so on.  This file holds the
-// host planner (the peel, the shares, the alpha-beta time, the choice of depth) and the schedule on
-// simulated ranks, which is built from the ring simulation and the fused reduce-copy of ring.hip.
+// slowest is left out and a faster sub-ring formed from the rest, and so on, every ring re-ranked so
+// that neighbours share as many rails as the narrowest member has (Sec. 6, "Topology-Aware Logical
+// Re-ranking").  This file holds the host planner (the peel, the rings' orders and bandwidths, the
+// shares, the alpha-beta time, the choice of depth) and the schedule on simulated ranks, which is built
+// from the ring with per-link tables (rails.hip) and the fused reduce-copy of ring.hip.
+#include <new>
+#include <vector>
+
 #include "r2_internal.h"
 
 namespace {
@@ -31,24 +36,119 @@ double ring_factor(double p) { return 2.0 * (p - 1.0) / p; }
 
 unsigned popcount64(uint64_t x) { return (unsigned)__builtin_popcountll(x); }
 
-// The order in which a level's data visits the ranks: excluded ranks ascending, then the members in
-// ring order starting after the highest excluded rank (all ranks ascending if none is excluded).
-void chain_order(uint32_t R, uint64_t members, uint32_t *excl, uint32_t &m, uint32_t *order, uint32_t &p)
+// A level's ring: its members in rank order, starting after the highest-numbered rank that is left
+// out (level 0: from rank 0), then re-ranked.  Returns an R2 code; order receives popcount(members) ranks.
+int level_ring_order(uint32_t R, uint32_t C, const uint64_t *fail_masks, uint64_t members, uint32_t *order, uint32_t &p)
 {
-    m = p = 0;
+    const uint64_t full = C == 64 ? ~0ull : ((1ull << C) - 1);
+    uint32_t base[R2_MAX_RANKS], start = 0;
     for (uint32_t r = 0; r < R; ++r)
-        if (!((members >> r) & 1u)) excl[m++] = r;
-    const uint32_t start = m ? excl[m - 1] + 1 : 0;
+        if (!((members >> r) & 1u)) start = r + 1;
+    p = 0;
     for (uint32_t i = 0; i < R; ++i) {
         const uint32_t r = (start + i) % R;
-        if ((members >> r) & 1u) order[p++] = r;
+        if ((members >> r) & 1u) base[p++] = r;
     }
+    // the re-ranking works on nodes 0..p-1: node i is base[i], its rails the channels it still has
+    uint32_t ident[R2_MAX_RANKS], moved[R2_MAX_RANKS];
+    uint64_t rails[R2_MAX_RANKS];
+    for (uint32_t i = 0; i < p; ++i) {
+        ident[i] = i;
+        rails[i] = ~fail_masks[base[i]] & full;
+    }
+    const int rc = r2_bridge_rerank(ident, rails, p, moved, nullptr);
+    if (rc) return rc;
+    for (uint32_t i = 0; i < p; ++i) order[i] = base[moved[i]];
+    return R2_OK;
+}
+
+// A ring moves data at the rate of its narrowest link; a link carries what both its ends still have.
+uint64_t ring_bandwidth(const uint32_t *weights, const uint64_t *fail_masks, const uint32_t *order, uint32_t p,
+                        uint32_t C, uint64_t full)
+{
+    uint64_t lo = ~0ull;
+    for (uint32_t i = 0; i < p; ++i) {
+        const uint64_t w = weight_of(weights, (fail_masks[order[i]] | fail_masks[order[(i + 1) % p]]) & full, C);
+        if (w < lo) lo = w;
+    }
+    return lo;
+}
+
+// Shares that minimise max_k f_k u_k + max_{k>=1} u_k (u_k = share_k / increment_k, f_k the ring
+// factor), the completion time with latency ignored: the time is piecewise linear in the shares, so
+// the minimum lies where the rings of the levels up to some j finish together (u_k = tau / f_k) and the
+// levels from j on have the same u (= tau / f_j): their shares are then exactly proportional to the
+// bandwidth they add.  Every j is tried; ties go to the smallest.  Two levels: the point T1 = T2.
+void optimal_shares(r2_level *levels, uint32_t L, uint32_t gpus_per_rank)
+{
+    if (L == 1) {
+        levels[0].share = 1.0;
+        return;
+    }
+    double f[R2_MAX_LEVELS], best_t = 0.0;
+    for (uint32_t k = 0; k < L; ++k) f[k] = ring_factor((double)popcount64(levels[k].members) * gpus_per_rank);
+    for (uint32_t j = 1; j < L; ++j) {
+        double work = 0.0;  // sum of increment_k * u_k / tau
+        for (uint32_t k = 0; k < L; ++k) work += (double)levels[k].increment / f[k <= j ? k : j];
+        const double t = (1.0 + 1.0 / f[j]) / work;
+        if (j == 1 || t < best_t) {
+            best_t = t;
+            for (uint32_t k = 0; k < L; ++k) levels[k].share = (double)levels[k].increment / f[k <= j ? k : j] / work;
+        }
+    }
+}
+
+// The ranks a level's broadcast visits, in order.  The ranks left out add their segments up in
+// ascending order (kGather); the sum goes round the ring's members in the ring's order, each adding it to
+// its ring result and passing it on unchanged (kMember; the last passes its finished result on); the
+// ranks left out take the result in ascending order (kTake).  A hop between two ranks that have no
+// channel in common goes through a third that is linked to both and forwards the data untouched
+// (kRelay): the first such rank among the ring's members in ring order, then among the ranks left out.
+enum Role : uint8_t { kGather, kMember, kTake, kRelay };
+struct Visit {
+    uint32_t rank;
+    Role role;
+};
+constexpr uint32_t kMaxVisits = 6 * R2_MAX_RANKS;  // 2m + p ranks, and at most one relay per hop
+
+int chain_visits(uint32_t R, uint32_t C, const uint64_t *fail_masks, uint64_t members, const uint32_t *order,
+                 uint32_t p, Visit *visits, uint32_t &n)
+{
+    const uint64_t full = C == 64 ? ~0ull : ((1ull << C) - 1);
+    uint32_t excl[R2_MAX_RANKS], m = 0;
+    for (uint32_t r = 0; r < R; ++r)
+        if (!((members >> r) & 1u)) excl[m++] = r;
+    n = 0;
+    if (!m) return R2_OK;
+    Visit walk[3 * R2_MAX_RANKS];
+    uint32_t nw = 0;
+    for (uint32_t i = 0; i < m; ++i) walk[nw++] = Visit{excl[i], kGather};
+    for (uint32_t i = 0; i < p; ++i) walk[nw++] = Visit{order[i], kMember};
+    for (uint32_t i = 0; i < m; ++i) walk[nw++] = Visit{excl[i], kTake};
+    auto linked = [&](uint32_t a, uint32_t b) { return ((fail_masks[a] | fail_masks[b]) & full) != full; };
+    visits[n++] = walk[0];
+    for (uint32_t i = 1; i < nw; ++i) {
+        const uint32_t u = visits[n - 1].rank, v = walk[i].rank;
+        if (!linked(u, v)) {
+            bool found = false;
+            for (uint32_t q = 0; q < p + m && !found; ++q) {
+                const uint32_t w = q < p ? order[q] : excl[q - p];
+                if (w != u && w != v && linked(u, w) && linked(w, v)) {
+                    visits[n++] = Visit{w, kRelay};
+                    found = true;
+                }
+            }
+            if (!found) return R2_ERR_NO_HEALTHY_CHANNEL;
+        }
+        visits[n++] = walk[i];
+    }
+    return R2_OK;
 }
 
 struct LevelShape {
     r2_sim_desc ring;
     uint64_t bytes, cap, ws_ring;
-    uint64_t ring_off, tables_off, stage_off;  // the level's own part of the workspace
+    uint64_t ring_off, tables_off, stage_off, relay_off;  // the level's own part of the workspace
     uint32_t m, p, hops;
 };
 
@@ -85,17 +185,19 @@ int rec_shape(const r2_recursive_desc *d, const r2_level *levels, const uint64_t
         l.bytes = n * s.elem;
         if (l.bytes % 16 != 0) return R2_ERR_INVALID;
         l.cap = round_up(l.bytes ? l.bytes : 1, kAlign256);
-        l.ring = r2_sim_desc{l.p, d->n_slabs, d->n_channels, d->align, n, d->dtype, R2_PHASE_RS | R2_PHASE_AG, 0,
-                             d->schedule, 0};
+        l.ring = r2_sim_desc{l.p, d->n_slabs, d->n_channels, d->align, n, d->dtype,
+                             R2_PHASE_RS | R2_PHASE_AG | R2_PHASE_LINKS, 0, d->schedule, 0};
         l.ws_ring = 0;
-        l.ring_off = l.tables_off = l.stage_off = s.total;
+        l.ring_off = l.tables_off = l.stage_off = l.relay_off = s.total;
         if (n) {
             if (r2_sim_num_steps(&l.ring) == 0) return R2_ERR_INVALID;
             l.ws_ring = round_up(r2_sim_workspace_bytes(&l.ring), kAlign256);
             if (l.ws_ring == 0) return R2_ERR_INVALID;
             l.tables_off = l.ring_off + l.ws_ring;
-            l.stage_off = l.tables_off + round_up(l.hops * (uint64_t)(d->n_channels + 1) * 8, kAlign256);
-            s.total = l.stage_off + (l.m ? 2 * (uint64_t)d->n_channels * l.cap : 0);
+            // every hop may need a relay: twice the rows; a relay's landing place: one segment
+            l.stage_off = l.tables_off + round_up(2 * l.hops * (uint64_t)(d->n_channels + 1) * 8, kAlign256);
+            l.relay_off = l.stage_off + (l.m ? 2 * (uint64_t)d->n_channels * l.cap : 0);
+            s.total = l.relay_off + (l.m ? l.cap : 0);
         }
     }
     if (sum != d->n_elems) return R2_ERR_INVALID;
@@ -118,12 +220,17 @@ extern "C" int r2_recursive_plan(uint32_t n_ranks, uint32_t gpus_per_rank, uint3
     uint64_t own[R2_MAX_RANKS];
     for (uint32_t r = 0; r < R; ++r) own[r] = weight_of(weights, fail_masks[r] & full, C);
 
+    uint64_t masks[R2_MAX_RANKS];
+    for (uint32_t r = 0; r < R; ++r) masks[r] = fail_masks[r] & full;
+    uint32_t order[R2_MAX_RANKS], p = 0;
+
     uint64_t members = R == 64 ? ~0ull : ((1ull << R) - 1);
-    uint64_t mask = union_mask(fail_masks, members, R, full);
-    uint64_t bw = weight_of(weights, mask, C);
-    if (bw == 0) return R2_ERR_NO_HEALTHY_CHANNEL;
+    int rc = level_ring_order(R, C, masks, members, order, p);
+    if (rc) return rc;
+    uint64_t bw = ring_bandwidth(weights, masks, order, p, C, full);
+    if (bw == 0) return R2_ERR_NO_HEALTHY_CHANNEL;  // a link of the global ring is left without a channel
     uint32_t L = 0;
-    levels[L++] = r2_level{members, mask, bw, bw, 0.0};
+    levels[L++] = r2_level{members, union_mask(masks, members, R, full), bw, bw, 0.0};
     while (L < max_levels) {
         uint64_t lo = ~0ull;
         for (uint32_t r = 0; r < R; ++r)
@@ -133,23 +240,27 @@ extern "C" int r2_recursive_plan(uint32_t n_ranks, uint32_t gpus_per_rank, uint3
             if (((members >> r) & 1u) && own[r] > lo) rest |= 1ull << r;
         if (popcount64(rest) < 2) break;
         members = rest;
-        mask = union_mask(fail_masks, members, R, full);
-        bw = weight_of(weights, mask, C);
+        if ((rc = level_ring_order(R, C, masks, members, order, p))) return rc;
+        bw = ring_bandwidth(weights, masks, order, p, C, full);
         if (bw > levels[L - 1].bandwidth) {
-            levels[L] = r2_level{members, mask, bw, bw - levels[L - 1].bandwidth, 0.0};
+            levels[L] = r2_level{members, union_mask(masks, members, R, full), bw, bw - levels[L - 1].bandwidth, 0.0};
             ++L;
         }
     }
-    // shares: all rings finish together when latency is ignored
-    double raw[R2_MAX_LEVELS], sum = 0.0;
-    for (uint32_t k = 0; k < L; ++k) {
-        const double p = (double)popcount64(levels[k].members) * gpus_per_rank;
-        raw[k] = (double)levels[k].increment / ring_factor(p);
-        sum += raw[k];
-    }
-    for (uint32_t k = 0; k < L; ++k) levels[k].share = raw[k] / sum;
+    optimal_shares(levels, L, gpus_per_rank);
     *n_levels = L;
     return R2_OK;
+}
+
+extern "C" int r2_recursive_ring_order(uint32_t n_ranks, uint32_t n_channels, const uint64_t *fail_masks,
+                                       uint64_t members, uint32_t *order)
+{
+    if (n_ranks < 2 || n_ranks > R2_MAX_RANKS || n_channels == 0 || n_channels > R2_MAX_CHANNELS) return R2_ERR_INVALID;
+    if (!fail_masks || !order) return R2_ERR_INVALID;
+    const uint64_t all = n_ranks == 64 ? ~0ull : ((1ull << n_ranks) - 1);
+    if ((members & ~all) != 0 || popcount64(members) < 2) return R2_ERR_INVALID;
+    uint32_t p = 0;
+    return level_ring_order(n_ranks, n_channels, fail_masks, members, order, p);
 }
 
 extern "C" double r2_recursive_time(uint32_t n_ranks, uint32_t gpus_per_rank, const r2_level *levels,
@@ -256,27 +367,36 @@ extern "C" int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *c
         if (desc->n_elems && (!p || (p & 15u))) return R2_ERR_INVALID;
     }
 
-    // Every table this run needs must leave a channel: the levels' rings and every link of the chains.
-    uint32_t excl[R2_MAX_RANKS], order[R2_MAX_RANKS], chain[3 * R2_MAX_RANKS];
+    uint64_t masks[R2_MAX_RANKS];
+    for (uint32_t r = 0; r < R; ++r) masks[r] = fail_masks[r] & full;
+
+    // Everything is laid out and checked before the first launch: every level's ring order, that each of
+    // its links has a channel, and the walk of its broadcast with the relays it needs.
+    struct LevelWalk {
+        uint32_t order[R2_MAX_RANKS], p, n;
+        Visit visits[kMaxVisits];
+    };
+    std::vector<LevelWalk> walks;
+    try {
+        walks.resize(desc->n_levels);
+    } catch (const std::bad_alloc &) {
+        return R2_ERR_CAPACITY;
+    }
     for (uint32_t k = 0; k < desc->n_levels; ++k) {
+        LevelWalk &w = walks[k];
+        w.p = w.n = 0;
         if (level_elems[k] == 0) continue;
-        if (!r2::any_healthy(weights, levels[k].fail_mask & full, C)) return R2_ERR_NO_HEALTHY_CHANNEL;
-        uint32_t m, p;
-        chain_order(R, levels[k].members, excl, m, order, p);
-        if (!m) continue;
-        uint32_t n = 0;
-        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
-        for (uint32_t i = 0; i < p; ++i) chain[n++] = order[i];
-        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
-        for (uint32_t i = 0; i + 1 < n; ++i)
-            if (!r2::any_healthy(weights, (fail_masks[chain[i]] | fail_masks[chain[i + 1]]) & full, C))
-                return R2_ERR_NO_HEALTHY_CHANNEL;
+        if ((rc = level_ring_order(R, C, masks, levels[k].members, w.order, w.p))) return rc;
+        if (ring_bandwidth(weights, masks, w.order, w.p, C, full) == 0) return R2_ERR_NO_HEALTHY_CHANNEL;
+        if ((rc = chain_visits(R, C, masks, levels[k].members, w.order, w.p, w.visits, w.n))) return rc;
     }
 
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const r2_dtype dt = (r2_dtype)desc->dtype;
     uint64_t lo = 0;  // first element of the level's segment
-    r2_epoch links[3 * R2_MAX_RANKS];
+    r2_epoch links[kMaxVisits], member_state[R2_MAX_RANKS];
+    const r2_epoch *member_list[R2_MAX_RANKS];
+    uint32_t ones[R2_MAX_RANKS];
     // The levels work on disjoint segments with workspaces of their own: each runs, ring and
     // broadcast chain, on a lane of its own, side by side with the others.
     r2::ForkJoin lanes((hipStream_t)stream);
@@ -284,43 +404,50 @@ extern "C" int r2_recursive_allreduce_sim(const r2_recursive_desc *desc, void *c
     uint32_t n_busy = 0;
     for (uint32_t k = 0; k < desc->n_levels; ++k) {
         const LevelShape &l = s.lv[k];
+        const LevelWalk &w = walks[k];
         const uint64_t seg_off = lo * s.elem;
         lo += level_elems[k];
         if (level_elems[k] == 0) continue;
         void *const lane = lanes.lane(n_busy++ % (r2::kSideStreams + 1));
         uint64_t *tables = reinterpret_cast<uint64_t *>(ws + l.tables_off);
-        uint32_t m, p;
-        chain_order(R, levels[k].members, excl, m, order, p);
 
-        // 1. the level's ring over its members, under the channels that are up at all of them
+        // 1. the level's ring over its members in the level's order, link by link: a link carries what
+        //    both its ends still have
         void *seg[R2_MAX_RANKS];
-        for (uint32_t i = 0; i < p; ++i) seg[i] = static_cast<uint8_t *>(rank_bufs[order[i]]) + seg_off;
-        const r2_epoch state = {0, levels[k].fail_mask & full, weights};
-        rc = r2_ring_allreduce_sim(&l.ring, seg, &state, 1, ws + l.ring_off, l.ws_ring, nullptr, lane);
+        for (uint32_t i = 0; i < w.p; ++i) {
+            seg[i] = static_cast<uint8_t *>(rank_bufs[w.order[i]]) + seg_off;
+            member_state[i] = r2_epoch{0, masks[w.order[i]], weights};
+            member_list[i] = &member_state[i];
+            ones[i] = 1;
+        }
+        rc = r2_ring_rails_sim(&l.ring, seg, member_list, ones, ws + l.ring_off, l.ws_ring, nullptr, lane);
         if (rc) return rc;
-        if (!m) continue;
+        if (!w.n) continue;
 
-        // 2. the broadcast chain; link i joins chain[i] and chain[i+1] and has table i
-        uint32_t n = 0;
-        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
-        for (uint32_t i = 0; i < p; ++i) chain[n++] = order[i];
-        for (uint32_t i = 0; i < m; ++i) chain[n++] = excl[i];
-        for (uint32_t i = 0; i + 1 < n; ++i)
-            links[i] = r2_epoch{i, (fail_masks[chain[i]] | fail_masks[chain[i + 1]]) & full, weights};
-        rc = r2::launch_partition_epochs(links, n - 1, C, desc->align, l.bytes, n - 1, tables, nullptr,
+        // 2. the broadcast chain; hop i joins visits[i] and visits[i+1] and has table i
+        for (uint32_t i = 0; i + 1 < w.n; ++i)
+            links[i] = r2_epoch{i, masks[w.visits[i].rank] | masks[w.visits[i + 1].rank], weights};
+        rc = r2::launch_partition_epochs(links, w.n - 1, C, desc->align, l.bytes, w.n - 1, tables, nullptr,
                                          (hipStream_t)lane);
         if (rc) return rc;
         void *stage[2][R2_MAX_CHANNELS];
         for (uint32_t par = 0; par < 2; ++par)
             for (uint32_t c = 0; c < C; ++c) stage[par][c] = ws + l.stage_off + ((uint64_t)par * C + c) * l.cap;
-        for (uint32_t i = 0; i < n; ++i) {
-            const bool first = i == 0, last = i + 1 == n;
+        uint32_t last_member = 0;
+        for (uint32_t i = 0; i < w.n; ++i)
+            if (w.visits[i].role == kMember) last_member = i;
+        for (uint32_t i = 0; i < w.n; ++i) {
+            const bool first = i == 0, last = i + 1 == w.n;
+            void *local = static_cast<uint8_t *>(rank_bufs[w.visits[i].rank]) + seg_off;
             int op;
-            if (i < m) op = R2_OP_SUM;                    // excluded ranks add themselves up
-            else if (i < m + p - 1) op = R2_OP_SUM_FORWARD;  // members take the sum, relay it unchanged
-            else if (i == m + p - 1) op = R2_OP_SUM;      // the last member sends its finished result on
-            else op = R2_OP_COPY;                         // excluded ranks take the result, pass it on
-            void *local = static_cast<uint8_t *>(rank_bufs[chain[i]]) + seg_off;
+            switch (w.visits[i].role) {
+            case kGather: op = R2_OP_SUM; break;  // the ranks left out add themselves up
+            case kMember: op = i == last_member ? R2_OP_SUM : R2_OP_SUM_FORWARD; break;
+            case kTake: op = R2_OP_COPY; break;   // the ranks left out take the result, pass it on
+            default:                              // a relay forwards what it gets; its own data is not involved
+                op = R2_OP_COPY;
+                local = ws + l.relay_off;
+            }
             rc = r2_reduce_copy(local, l.bytes, dt, op, first ? nullptr : stage[(i + 1) & 1],
                                 first ? nullptr : tables + (uint64_t)(i - 1) * (C + 1), last ? nullptr : stage[i & 1],
                                 last ? nullptr : tables + (uint64_t)i * (C + 1), C, l.cap, nullptr, lane);

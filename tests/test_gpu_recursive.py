@@ -59,7 +59,9 @@ def _run(r2, oracle, xs, dtype, plan, elems, S, C, align, weights, masks, schedu
         trace = rec.recursive_sim(o_bufs, odt, plan, elems, S, C, align, weights, masks)
         for r in range(R):
             assert outs[r].tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
-        # Every level has its own part of the workspace: ring workspace, link tables, chain stage.
+        # Every level has its own part of the workspace: the ring's workspace (its per-link tables come
+        # first), the chain's hop tables (room for a relay on every hop), the chain's stage, and the
+        # place relayed data lands in.
         es = xs[0].itemsize
         up = lambda x: (x + 255) // 256 * 256
         at = 0
@@ -67,21 +69,26 @@ def _run(r2, oracle, xs, dtype, plan, elems, S, C, align, weights, masks, schedu
             if n == 0:
                 continue
             p = len(lv.members)
-            ring = r2.SimDesc(p, S, C, align, n, gdt, r2.PHASE_AR, 0, schedule)
+            assert r2.r2_recursive_ring_order(C, masks, sum(1 << r for r in lv.members)) == lv.order
+            ring = r2.SimDesc(p, S, C, align, n, gdt, r2.PHASE_AR | r2.PHASE_LINKS, 0, schedule)
+            ring_tables, visits, tables, stage = tr
+            got_ring = ws[at: at + ring_tables.size * 8].cpu().numpy().view(np.uint64).reshape(ring_tables.shape)
+            assert got_ring.tolist() == ring_tables.tolist(), f"per-link tables of the ring {lv.order}"
             at += up(r2.r2_sim_workspace_bytes(ring))
-            if tr is None:
+            if visits is None:
                 continue
-            chain, tables, stage = tr
             cap = up(n * es)
             got_tab = ws[at: at + tables.size * 8].cpu().numpy().view(np.uint64).reshape(tables.shape)
-            assert got_tab.tolist() == tables.tolist(), f"link tables of the ring over {lv.members}"
-            at += up((len(chain) - 1) * (C + 1) * 8)
+            assert got_tab.tolist() == tables.tolist(), f"hop tables of the chain of the ring {lv.order}"
+            hops = p + 2 * (R - p) - 1
+            assert len(visits) - 1 <= 2 * hops
+            at += up(2 * hops * (C + 1) * 8)
             got_stage = ws[at: at + 2 * C * cap].cpu().numpy().reshape(2, C, cap)
             for par in range(2):
                 for c in range(C):
                     assert got_stage[par, c].tobytes() == stage[par][c].tobytes(), \
-                        f"chain stage of the ring over {lv.members}: parity {par} channel {c}"
-            at += 2 * C * cap
+                        f"chain stage of the ring {lv.order}: parity {par} channel {c}"
+            at += 2 * C * cap + cap
         assert at == need
     return outs
 
@@ -94,6 +101,10 @@ CASES = [
     ([5] * 6, [0b000110, 0b000010, 0b000100, 0, 0, 0]),            # two equally slow ranks leave together
     ([50000] * 8, [0] * 6),                                           # no failure: one ring
     ([9, 9, 9], [0b001, 0b011, 0, 0b001, 0, 0, 0b011, 0, 0]),
+    ([1] * 8, [0b00001111, 0b11110000, 0, 0, 0, 0]),                  # two servers lost complementary halves: no rail is
+                                                                      # up everywhere; re-ranked ring, relayed broadcast hops
+    ([1, 1, 1, 1], [0b0011, 0b0100, 0, 0]),                           # the global ring is re-ranked (0 2 1 3)
+    ([2, 3, 5, 7, 11, 13], [0b000111, 0b111000, 0b010101, 0, 0b000001, 0, 0]),  # three levels, relays, unequal rails
 ]
 
 
@@ -112,34 +123,61 @@ def test_recursive_small(r2, oracle, dtype, schedule):
             _run(r2, oracle, xs, dtype, plan, elems, S, C, 16, weights, masks, schedule)
 
 
-@pytest.mark.parametrize("seed", [1, 2])
+@pytest.mark.parametrize("seed", [1, 2, 3])
 def test_recursive_random_failure_patterns(r2, oracle, seed):
-    """Random failure patterns: ranks lose random channels (one channel is kept up everywhere so that the
-    global ring exists), random weights, types, schedules and segment sizes."""
+    """Random failure patterns: ranks lose random channels -- no channel is kept up everywhere, so that
+    rings get re-ranked and broadcast hops relayed; where the oracle finds no way the product must refuse
+    too --, random weights, types, schedules and segment sizes."""
     rng = np.random.default_rng(600 + seed)
-    n_multi = 0
-    for case in range(15):
+    n_multi = n_relay = n_refused = n_reranked = 0
+    for case in range(25):
         R, C = int(rng.integers(2, 10)), int(rng.integers(2, 9))
         weights = [int(x) for x in rng.integers(1, 1000, C)]
-        keep = int(rng.integers(0, C))
         masks = []
         for _ in range(R):
             m = 0
             if rng.random() < 0.6:
-                m = int(rng.integers(0, 1 << C)) & ~(1 << keep)
+                m = int(rng.integers(0, 1 << C))
+                if m == (1 << C) - 1:
+                    m &= ~(1 << int(rng.integers(0, C)))
             masks.append(m)
-        plan = rec.plan(weights, masks)
-        n_multi += len(plan) > 2
         dtype = "f32" if rng.random() < 0.5 else "bf16"
         per16 = 4 if dtype == "f32" else 8
         S = int(rng.integers(1, 3))
-        schedule = int(rng.integers(0, 3))
+        schedule = int(rng.integers(0, 2))
+        try:
+            plan = rec.plan(weights, masks)
+        except oracle.NoHealthyChannel:  # a link of the global ring has no channel, re-ranked or not
+            n_refused += 1
+            with pytest.raises(r2.R2Error) as e:
+                r2.r2_recursive_plan(weights, masks)
+            assert e.value.code == -2
+            continue
+        try:
+            for lv in plan:
+                rec.chain_visits(R, C, masks, lv)
+        except oracle.NoHealthyChannel:  # a broadcast hop with no way round: the run itself refuses
+            n_refused += 1
+            lv = _levels(r2, plan)
+            elems = [S * len(l.members) * per16 for l in plan]
+            desc = r2.RecursiveDesc(R, C, 16, sum(elems), r2.F32 if dtype == "f32" else r2.BF16, len(lv), S, schedule)
+            ws = torch.empty(r2.r2_recursive_workspace_bytes(desc, lv, elems), dtype=torch.uint8, device="cuda")
+            bufs = [torch.zeros(sum(elems), dtype=torch.float32 if dtype == "f32" else torch.int16, device="cuda")
+                    for _ in range(R)]
+            with pytest.raises(r2.R2Error) as e:
+                r2.r2_recursive_allreduce_sim(desc, bufs, weights, masks, lv, elems, ws)
+            assert e.value.code == -2
+            continue
+        n_multi += len(plan) > 2
+        n_relay += any(role == "relay" for lv in plan for _, role in rec.chain_visits(R, C, masks, lv))
+        n_reranked += any(lv.order != sorted(lv.order) and lv.order != rec.ring_order(R, C, [0] * R, lv.members) for lv in plan)
         elems = [S * len(l.members) * per16 * int(rng.integers(0, 40)) for l in plan]
         if sum(elems) == 0:
             elems[0] = S * R * per16
         say(f"recursive random {seed}.{case} {dtype} sched={schedule} R={R} C={C} masks={masks} levels={len(plan)} elems={elems}")
         xs = _inputs(rng, R, sum(elems), dtype)
         _run(r2, oracle, xs, dtype, plan, elems, S, C, (16, 256)[int(rng.integers(0, 2))], weights, masks, schedule)
+    say(f"recursive random {seed}: multi-level {n_multi}, with relays {n_relay}, re-ranked {n_reranked}, refused {n_refused}")
     assert n_multi >= 3
 
 
@@ -222,8 +260,9 @@ def test_recursive_argument_errors(r2):
     fails(-1, lv=[levels[0], r2.Level(0b1111, 0)])                      # not shrinking
     fails(-1, lv=[levels[0], r2.Level(0b1000, 0)])                      # a ring of one
     fails(-1, lv=[r2.Level(0b0111, 0), levels[1]])                      # level 0 must hold everybody
-    fails(-2, lv=[r2.Level(0b1111, 0b1111), levels[1]])                 # the level's ring has no channel
-    fails(-2, m=[0b0011, 0b1100, 0, 0])                                 # the link 0 -> 1 has no channel
+    fails(-2, m=[0b0011, 0b1100, 0b1111, 0])                            # rank 2 has no channel left: no ring through it
+    fails(-2, m=[0b0011, 0b1100, 0b0110, 0b1001], d=r2.RecursiveDesc(4, 4, 16, N, r2.F32, 1), lv=[levels[0]],
+          el=[N])                                                       # four ranks, every second pair shares nothing
     assert r2.r2_recursive_workspace_bytes(r2.RecursiveDesc(4, 4, 16, N, r2.F32, 0), levels, elems) == 0
     torch.cuda.synchronize()
     assert all(float(b.abs().sum()) == 0.0 for b in bufs)               # nothing ran

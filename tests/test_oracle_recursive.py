@@ -411,7 +411,6 @@ def test_chain_visits():
 
 # ------------------------------------------------------------------ product's host planner vs oracle
 
-@pytest.mark.skip(reason="the product's planner follows the oracle's new rules in the next commit")
 def test_host_planner_matches_oracle(r2):
     rng = np.random.default_rng(78)
     n_multi = 0
@@ -429,6 +428,7 @@ def test_host_planner_matches_oracle(r2):
         assert len(got) == len(want)
         for a, b in zip(got, want):
             assert a.ranks() == b.members and a.fail_mask == b.fail_mask
+            assert r2.r2_recursive_ring_order(C, masks, a.members) == b.order
             assert (a.bandwidth, a.increment) == (b.bandwidth, b.increment)
             assert a.share == pytest.approx(float(b.share), rel=1e-13)
         n_multi += len(want) > 1
@@ -446,7 +446,6 @@ def test_host_planner_matches_oracle(r2):
     assert n_multi > 100
 
 
-@pytest.mark.skip(reason="the product's planner follows the oracle's new rules in the next commit")
 def test_segments_follow_the_shares_and_fit_the_rings(r2):
     """Every segment divides into its ring in whole 16-byte vectors, level 0's into the global ring; the
     upper levels get their share rounded down by less than one granule, level 0 the rest; the host
