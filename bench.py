@@ -274,6 +274,17 @@ def config_entry(r2, torch, np, wl, name, check, reps, cold_window=0):
         e["kernel"] = dom
         e["avg_launch_ms"] = round(avg_ms, 5)
         e["frac"] = round(launch_bytes / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+        # the same run with pairs of half-window passes issued side by side on two streams (opt-in):
+        # whole-run figures only, since launches that share the GPU have no duration of their own
+        del run
+        run = Runner(r2, torch, np, w, xs, schedule=r2.SCHED_STEPS_OVERLAP)
+        run.step()
+        torch.cuda.synchronize()
+        same = all(np.array_equal(b.cpu().numpy().view(x.dtype), f) for b, x, f in zip(run.bufs, xs, first))
+        so = run.time_steps(ops, 3) / ops
+        e["overlap_schedule"] = {"ms_per_step": round(so * 1e3, 4), "GBps": round(w.algorithmic_bytes / so / 1e9, 1),
+                                 "pct_of_hbm_peak": round(100 * w.algorithmic_bytes / so / 1e9 / HBM_PEAK_GBPS, 2),
+                                 "passes": run.P, "same_result": bool(same)}
     if check:
         e["matches_oracle"] = bool(_matches_definition(w, xs, first, np))
     del run, first
@@ -553,7 +564,7 @@ def main() -> int:
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg4 or cfg5_tok{1,16,64,256}")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=5)
-    ap.add_argument("--schedule", choices=["auto", "steps", "fused"], default="auto")
+    ap.add_argument("--schedule", choices=["auto", "steps", "fused", "overlap"], default="auto")
     ap.add_argument("--stage-window-mib", type=float, default=0.0,
                     help="stage bytes one launch may write (0 = library default)")
     ap.add_argument("--headline-only", action="store_true",
@@ -583,7 +594,7 @@ def main() -> int:
     w = _workload(args.config)
     xs = wl.make_inputs(w)
     run = Runner(r2, torch, np, w, xs, int(args.stage_window_mib * (1 << 20)),
-                 {"auto": 0, "steps": 1, "fused": 2}[args.schedule])
+                 {"auto": 0, "steps": 1, "fused": 2, "overlap": 3}[args.schedule])
 
     # one pass from pristine inputs, kept for the correctness check
     run.step()

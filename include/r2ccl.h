@@ -63,7 +63,7 @@ enum { R2_PHASE_RS = 1, R2_PHASE_AG = 2, /* both = all-reduce */
        /* a flag for the ring phases (RS, AG or both): every ring link has tables of its own instead of
           one table per transmission for all ranks; see r2_ring_rails_sim */
        R2_PHASE_LINKS = 64 };
-enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2 };
+enum { R2_SCHED_AUTO = 0, R2_SCHED_STEPS = 1, R2_SCHED_FUSED = 2, R2_SCHED_STEPS_OVERLAP = 3 };
 
 /* Static, human-readable text for a return code. */
 const char *r2_strerror(int code);
@@ -238,7 +238,16 @@ typedef struct {
                             R2_SCHED_FUSED: one launch takes every column (1 or 2 KiB of each ring chunk)
                             through all steps between two channel-state changes; needs chunks that
                             are a multiple of 16 bytes.
-                            R2_SCHED_AUTO (0): FUSED for launch-bound sizes, else STEPS.           */
+                            R2_SCHED_AUTO (0): FUSED for launch-bound sizes, else STEPS.
+                            R2_SCHED_STEPS_OVERLAP: as STEPS, but the run is cut into at least two
+                            passes of half the stage window each, and passes are issued in pairs,
+                            step by step alternately on the caller's stream and on a library-owned
+                            stream (default priority, created once per device, forked off `stream`
+                            after the partition launch and joined to it again with events before
+                            the call returns to the caller's order): while one pass's launch ramps
+                            up or drains, the other's fills the GPU.  Passes are independent, so
+                            the result is the same.  Never chosen by AUTO; not with
+                            R2_PHASE_LINKS.                                                      */
     int32_t root;        /* R2_PHASE_BROADCAST: the rank whose buffer everybody gets;
                             R2_PHASE_REDUCE: the rank that gets the sum; otherwise 0              */
 } r2_sim_desc;

@@ -21,7 +21,7 @@ OP_SUM, OP_COPY, OP_SUM_FORWARD, OP_SUM_SEND = 0, 1, 2, 3
 PHASE_RS, PHASE_AG = 1, 2
 PHASE_AR = PHASE_RS | PHASE_AG
 PHASE_SENDRECV, PHASE_BROADCAST, PHASE_REDUCE, PHASE_ALLTOALL, PHASE_LINKS = 4, 8, 16, 32, 64
-SCHED_AUTO, SCHED_STEPS, SCHED_FUSED = 0, 1, 2
+SCHED_AUTO, SCHED_STEPS, SCHED_FUSED, SCHED_STEPS_OVERLAP = 0, 1, 2, 3
 
 R2_OK = 0
 R2_ERR_INVALID = -1

@@ -544,6 +544,21 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         hipLaunchKernelGGL(own_block_copy_kernel, grid, dim3(kThreads), 0, (hipStream_t)stream, own);
         if ((rc = hip_rc(hipGetLastError()))) return rc;
     }
+    if (desc->schedule == R2_SCHED_STEPS_OVERLAP && s.n_passes >= 2) {
+        // Pairs of passes side by side, issued step by step alternately so that their launches
+        // interleave in time.  The fork point lies behind the partition launch, which both lanes need.
+        ForkJoin lanes((hipStream_t)stream);
+        if (lanes.rc()) return lanes.rc();
+        void *const side = lanes.lane(1);
+        for (uint64_t p = 0; p < s.n_passes; p += 2)
+            for (uint32_t j = 0; j < s.J; ++j) {
+                if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
+                if (p + 1 < s.n_passes &&
+                    (rc = r2_sim_step(desc, rank_bufs, p + 1, j, workspace, workspace_bytes, side)))
+                    return rc;
+            }
+        return lanes.join();
+    }
     for (uint64_t p = 0; p < s.n_passes; ++p)
         for (uint32_t j = 0; j < s.J; ++j)
             if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;

@@ -62,8 +62,10 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     case R2_PHASE_ALLTOALL: s.kind = SimShape::kAllToAll; break;
     default: return R2_ERR_INVALID;
     }
-    if (d->schedule != R2_SCHED_AUTO && d->schedule != R2_SCHED_STEPS && d->schedule != R2_SCHED_FUSED)
+    if (d->schedule != R2_SCHED_AUTO && d->schedule != R2_SCHED_STEPS && d->schedule != R2_SCHED_FUSED &&
+        d->schedule != R2_SCHED_STEPS_OVERLAP)
         return R2_ERR_INVALID;
+    if (s.links && d->schedule == R2_SCHED_STEPS_OVERLAP) return R2_ERR_INVALID;
     if (s.links && s.kind != SimShape::kRing) return R2_ERR_INVALID;
     if (s.kind != SimShape::kRing && d->schedule == R2_SCHED_FUSED) return R2_ERR_INVALID;
     const int ring_phases = d->phases & ~R2_PHASE_LINKS;
@@ -93,10 +95,17 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     s.total_bytes = s.stage_off + (uint64_t)stage;
 
     // The two-step exchanges use one stage parity only, so twice as much fits the same cache footprint.
-    const uint64_t window = d->stage_window_bytes ? d->stage_window_bytes
-                            : s.two_lists()       ? 2 * kDefaultStageWindow
-                                                  : kDefaultStageWindow;
+    uint64_t window = d->stage_window_bytes ? d->stage_window_bytes
+                      : s.two_lists()       ? 2 * kDefaultStageWindow
+                                            : kDefaultStageWindow;
     const uint64_t per_slab = (uint64_t)s.active() * s.chunk_bytes;  // stage bytes a step writes per slab
+    if (d->schedule == R2_SCHED_STEPS_OVERLAP) {
+        // Two passes are in flight side by side: each gets half the window, and the run is cut into
+        // at least two passes so that there is a pair to overlap.
+        const uint64_t half_run = (per_slab * s.S + 1) / 2;
+        window = window / 2 < half_run ? window / 2 : half_run;
+        if (window == 0) window = 1;
+    }
     if (per_slab > window) {
         const uint64_t tile_bytes = (uint64_t)kThreads * kUnroll * 16;
         const uint64_t parts = (per_slab + window - 1) / window;

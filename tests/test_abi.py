@@ -111,7 +111,7 @@ def test_pass_planning(r2):
     dict(n_ranks=1), dict(n_ranks=65), dict(n_channels=0), dict(n_channels=65), dict(n_slabs=0),
     dict(align=0), dict(align=8), dict(align=24), dict(n_elems=(1 << 20) + 1), dict(dtype=7),
     dict(phases=0), dict(phases=5), dict(phases=7), dict(phases=9), dict(phases=24), dict(phases=48), dict(phases=64),
-    dict(n_slabs=8192, n_elems=8192 * 8 * 4), dict(schedule=3), dict(root=1),
+    dict(n_slabs=8192, n_elems=8192 * 8 * 4), dict(schedule=4), dict(phases=3 | 64, schedule=3), dict(root=1),
     dict(phases=8, root=8), dict(phases=8, root=-1), dict(phases=16, root=8), dict(phases=32, root=1),
     dict(phases=8, schedule=2), dict(phases=16, schedule=2), dict(phases=32, schedule=2),
     dict(phases=32, n_slabs=1171, n_elems=1171 * 8 * 16),  # all-to-all: R*(R-1)*S > 65535
@@ -159,6 +159,20 @@ def test_chain_and_alltoall_descriptor_arithmetic(r2):
     assert r2.r2_sim_stage_capacity(d) == 512  # 400 bytes per chunk
     assert r2.r2_sim_workspace_bytes(d) == r2.r2_sim_stage_offset(d) + 2 * 4 * 15 * 8 * 512
     assert r2.r2_sim_num_steps(r2.SimDesc(4, 5, 8, 256, 4 * 5 * 100 + 4, r2.F32, r2.PHASE_ALLTOALL)) == 0
+
+
+def test_overlapped_schedule_cuts_at_least_two_passes(r2):
+    """R2_SCHED_STEPS_OVERLAP halves the stage window and always leaves a pair of passes to overlap."""
+    mk = lambda N, S, sched, window=0: r2.SimDesc(8, S, 8, 256, N, r2.BF16, r2.PHASE_AR, window, sched)
+    assert r2.r2_sim_num_passes(mk(1 << 26, 1, r2.SCHED_STEPS)) == 1          # cfg2: 128 MiB staged per step
+    assert r2.r2_sim_num_passes(mk(1 << 26, 1, r2.SCHED_STEPS_OVERLAP)) == 2  # two byte ranges of 64 MiB
+    assert r2.r2_sim_num_passes(mk(1 << 25, 32, r2.SCHED_STEPS)) == 1         # cfg4: 64 MiB staged per step
+    assert r2.r2_sim_num_passes(mk(1 << 25, 32, r2.SCHED_STEPS_OVERLAP)) == 2  # two groups of 16 slabs
+    assert r2.r2_sim_num_passes(mk(1 << 28, 1, r2.SCHED_STEPS)) == 4
+    assert r2.r2_sim_num_passes(mk(1 << 28, 1, r2.SCHED_STEPS_OVERLAP)) == 8
+    assert r2.r2_sim_num_passes(mk(8 * 3 * 64, 3, r2.SCHED_STEPS_OVERLAP)) == 3  # three small slabs: one by one
+    assert r2.r2_sim_resolve_schedule(mk(1 << 26, 1, r2.SCHED_STEPS_OVERLAP), [(0, 0, [1] * 8)]) == r2.SCHED_STEPS_OVERLAP
+    assert r2.r2_sim_resolve_schedule(mk(1 << 26, 1, r2.SCHED_AUTO), [(0, 0, [1] * 8)]) == r2.SCHED_STEPS  # never by itself
 
 
 def test_rails_schedule_is_host_arithmetic(r2):

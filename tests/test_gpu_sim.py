@@ -455,6 +455,26 @@ def test_full_cfg2_ragged_one_pass_stage_beyond_cache(r2, oracle):
     _full_size(r2, oracle, wl.scaled(wl.cfg2(), 8 * ((1 << 23) + 24)), schedule=1, window=1 << 30)
 
 
+@pytest.mark.parametrize("make", [wl.cfg2, wl.cfg3, wl.cfg4], ids=["cfg2", "cfg3", "cfg4"])
+def test_full_overlapped_passes(r2, oracle, make):
+    """The opt-in schedule that issues pairs of half-window passes side by side on two streams: same
+    result, same tables, at full size."""
+    _full_size(r2, oracle, make(), schedule=3)
+
+
+def test_sim_overlapped_passes_small(r2, oracle):
+    """Small shapes under the overlapped schedule: odd numbers of passes, byte-range passes of one slab,
+    slab groups, a window that leaves a single pass."""
+    from dataclasses import replace
+
+    for w, window in ((wl.scaled(wl.cfg2(), 8 * 8192 * 2 + 8 * 24), 0),          # one slab: two byte ranges
+                      (wl.scaled(wl.cfg2(), 8 * 8192 * 6 + 8 * 24), 3 * 8 * 8192),   # five byte ranges (odd)
+                      (wl.scaled(wl.cfg4(S=32), 8 * 32 * 1100), 0),              # 32 slabs: two groups of 16
+                      (wl.scaled(wl.cfg3(S=4), 16 * 4 * 5000), 16 * 5000 * 4 * 2),   # reduce-scatter, four slabs one by one
+                      (replace(wl.scaled(wl.cfg1(), 4 * 3 * 1000), S=3), 0)):     # three slabs: a pair and a single pass
+        _full_compare_small(r2, oracle, w, window=window, check_stage=False, schedule=3)
+
+
 def test_full_cfg4(r2, oracle):
     _full_size(r2, oracle, wl.cfg4(), check_bound=True)
 
