@@ -30,11 +30,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure (8 TB/s)
 # (the JSON line says so in roofline.traffic_source).  The counters sit between L2 and the fabric and
 # cannot tell HBM from the Infinity Cache.
 MEASURED_TRAFFIC = {
-    ("cfg2", "sum"): (int((131112.8 * (131072.0 / 65550.7) + 262158.2 * (131072.0 / 131072.0)) * 1024),
+    ("cfg2", "sum"): (int((131113.1 * (131072.0 / 65551.1) + 262155.8 * (131072.0 / 131072.0)) * 1024),
                       "profiles/ring_step_sum_bf16_cfg2_pmc.md"),
-    ("cfg3", "sum"): (int((131114.8 * (262144.0 / 131087.4) + 262156.1 * (262144.0 / 262144.0)) * 1024),
+    ("cfg3", "sum"): (int((131114.5 * (262144.0 / 131087.7) + 262161.1 * (262144.0 / 262144.0)) * 1024),
                       "profiles/ring_step_sum_f32_cfg3_pmc.md"),
-    ("cfg4", "sum"): (int((65611.1 * (65536.0 / 32781.6) + 131074.6 * (65536.0 / 65536.0)) * 1024),
+    ("cfg4", "sum"): (int((65611.5 * (65536.0 / 32782.1) + 131074.5 * (65536.0 / 65536.0)) * 1024),
                       "profiles/ring_step_sum_bf16_cfg4_pmc.md"),
 }
 
@@ -324,6 +324,29 @@ def cold_reduce_copy(r2, torch, dtype="bf16", chunk_mib=256, sets=4, reps=40):
     del calls
     torch.cuda.empty_cache()
     return ms, 4 * nbytes
+
+
+def plain_copy_rate(torch, mib=1024, sets=3, reps=24):
+    """Context for the cold figures: what a plain device-to-device copy (torch's, one read and one write
+    stream, buffers rotated so that nothing is cache-resident) reaches on this GPU.  Returns the
+    fraction of the HBM peak (bytes read + bytes written over time)."""
+    n = mib << 20
+    src = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(sets)]
+    dst = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(sets)]
+    for i in range(sets):
+        src[i].zero_()
+        dst[i].copy_(src[i])
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        dst[i % sets].copy_(src[i % sets])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2 * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
 
 
 def cold_one_pass(r2, torch, np, w, xs, window, reps):
@@ -704,6 +727,7 @@ def main() -> int:
         rc_frac = rc_bytes / (rc_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
         c3_frac = c3_bytes / (c3_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
         out["roofline"]["frac_cold"] = round(min(rc_frac, c3_frac), 4)
+        out["roofline"]["plain_copy_frac"] = round(plain_copy_rate(torch), 4)  # context: a 1 GiB device copy, same units
         out["roofline"]["cold"] = {
             "reduce_copy_bf16_sum_256MiB_chunks_rotated_over_4_buffer_sets": {"avg_launch_ms": round(rc_ms, 5), "frac": round(rc_frac, 4)},
             "cfg3_forced_to_one_pass_f32_sum_1GiB_per_launch": {"avg_launch_ms": round(c3_ms, 5), "frac": round(c3_frac, 4)},
