@@ -134,9 +134,10 @@ class Runner:
         return time.perf_counter() - t0
 
     def kernel_times(self, reps: int):
-        """Average launch duration in ms per kind of fused step, over `reps` runs driven launch by
-        launch in the order r2_ring_allreduce_sim uses.  Steps of one kind are consecutive within a
-        pass (send | sum ... | copy ... | last); each such group is bracketed by one pair of HIP
+        """Average launch duration in ms per kind of fused step (the median over `reps` runs of each
+        run's average), the runs driven launch by launch in the order r2_ring_allreduce_sim uses.
+        Steps of one kind are consecutive within a pass (send | sum ... | copy ... | last); each such
+        group is bracketed by one pair of HIP
         events, recorded on the stream the kernels run on, so the figure holds the kernels and the
         dispatch gaps between them, as in the real run.  Returns {kind: (avg_ms, launches)}."""
         torch, r2 = self.torch, self.r2
@@ -149,7 +150,8 @@ class Runner:
                 groups[-1][2] = j
             else:
                 groups.append([k, j, j])
-        total, count = {}, {}
+        per_rep = {}  # kind -> [average ms per launch in each repetition]
+        count = {}
         for _ in range(reps):
             self.restore()
             r2.r2_sim_prepare(self.desc, self.w.epochs, self.ws)
@@ -163,10 +165,16 @@ class Runner:
                     e1.record()
                     pairs.append((k, j1 - j0 + 1, e0, e1))
             torch.cuda.synchronize()
+            total, n_launch = {}, {}
             for k, n, e0, e1 in pairs:
                 total[k] = total.get(k, 0.0) + e0.elapsed_time(e1)
-                count[k] = count.get(k, 0) + n
-        return {k: (total[k] / count[k], count[k]) for k in total}
+                n_launch[k] = n_launch.get(k, 0) + n
+            for k in total:
+                per_rep.setdefault(k, []).append(total[k] / n_launch[k])
+                count[k] = count.get(k, 0) + n_launch[k]
+        # the median repetition: one stall of the host or the box inside a repetition (seen: a single
+        # event pair of tens of milliseconds) must not become the figure
+        return {k: (sorted(v)[len(v) // 2], count[k]) for k, v in per_rep.items()}
 
 
 def _fused_segments(w):
@@ -306,10 +314,15 @@ def cold_reduce_copy(r2, torch, dtype="bf16", chunk_mib=256, sets=4, reps=40):
     cap = (max(off[c + 1] - off[c] for c in range(C)) + 255) // 256 * 256
     d_off = torch.tensor(off, dtype=torch.int64, device="cuda")
     calls = []
+    def filled(n):  # values of the workloads' distribution: all-zero buffers move faster through this GPU's
+        t = torch.empty(n, dtype=torch.uint8, device="cuda")  # caches than any other data and would flatter the figure
+        (t.view(torch.bfloat16) if dtype == "bf16" else t.view(torch.float32)).normal_(0.0, 0.02)
+        return t
+
     for _ in range(sets):
-        local = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
-        ins = [torch.zeros(cap, dtype=torch.uint8, device="cuda") for _ in range(C)]
-        outs = [torch.zeros(cap, dtype=torch.uint8, device="cuda") for _ in range(C)]
+        local = filled(nbytes)
+        ins = [filled(cap) for _ in range(C)]
+        outs = [filled(cap) for _ in range(C)]
         calls.append(r2.ReduceCopyCall(local, dt, r2.OP_SUM, ins, d_off, outs, d_off, C, cap, nbytes=nbytes))
     for i in range(2 * sets):
         calls[i % sets].run()
