@@ -150,12 +150,13 @@ bool fused_eligible(const SimShape &s) { return !s.links && columns_fit(s); }
 // A stage this large is gone from the caches before anybody reads it: written around them.
 constexpr uint64_t kNtStageBytes = 128ull << 20;
 
-// One fused step: `rows` (rank, slab) pairs, each moving bytes [lo, hi) of its ring chunk.
+// One fused step: `rows` (rank, slab) pairs, each moving bytes [lo, hi) of its ring chunk.  A stage of
+// more than `cached_up_to` bytes per launch is written around the caches.
 template <Mode M, bool HAS_OUT, bool KEEP = false>
-void launch_step(const StepArgs &a, unsigned rows, hipStream_t st)
+void launch_step(const StepArgs &a, unsigned rows, uint64_t cached_up_to, hipStream_t st)
 {
     const dim3 grid(blocks_for(a.hi - a.lo), rows);
-    if (HAS_OUT && (uint64_t)rows * (a.hi - a.lo) > kNtStageBytes)
+    if (HAS_OUT && (uint64_t)rows * (a.hi - a.lo) > cached_up_to)
         hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT, KEEP, HAS_OUT>), grid, dim3(kThreads), 0, st, a);
     else
         hipLaunchKernelGGL((ring_step_kernel<M, HAS_OUT, KEEP, false>), grid, dim3(kThreads), 0, st, a);
@@ -366,21 +367,23 @@ extern "C" int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint
     const bool keep = s.kind == SimShape::kReduce && has_in && has_out;  // the sum is passed on, not kept
 
     const unsigned grid = s.active() * a.slab_count;  // rows of workgroups: one per (rank, slab)
+    // the two-step exchanges use one stage parity only: twice as much stays within reach of the next step
+    const uint64_t keep_cached = s.two_lists() ? 2 * kNtStageBytes : kNtStageBytes;
     hipStream_t st = (hipStream_t)stream;
     switch (m) {
-    case kSend: launch_step<kSend, true>(a, grid, st); break;
+    case kSend: launch_step<kSend, true>(a, grid, keep_cached, st); break;
     case kSumF32:
-        if (keep) launch_step<kSumF32, true, true>(a, grid, st);
-        else if (has_out) launch_step<kSumF32, true>(a, grid, st);
-        else launch_step<kSumF32, false>(a, grid, st);
+        if (keep) launch_step<kSumF32, true, true>(a, grid, keep_cached, st);
+        else if (has_out) launch_step<kSumF32, true>(a, grid, keep_cached, st);
+        else launch_step<kSumF32, false>(a, grid, keep_cached, st);
         break;
     case kSumBF16:
-        if (keep) launch_step<kSumBF16, true, true>(a, grid, st);
-        else if (has_out) launch_step<kSumBF16, true>(a, grid, st);
-        else launch_step<kSumBF16, false>(a, grid, st);
+        if (keep) launch_step<kSumBF16, true, true>(a, grid, keep_cached, st);
+        else if (has_out) launch_step<kSumBF16, true>(a, grid, keep_cached, st);
+        else launch_step<kSumBF16, false>(a, grid, keep_cached, st);
         break;
     case kCopy:
-        if (has_out) launch_step<kCopy, true>(a, grid, st); else launch_step<kCopy, false>(a, grid, st);
+        if (has_out) launch_step<kCopy, true>(a, grid, keep_cached, st); else launch_step<kCopy, false>(a, grid, keep_cached, st);
         break;
     }
     return hip_rc(hipGetLastError());
