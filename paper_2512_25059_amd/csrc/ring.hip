@@ -594,7 +594,7 @@ extern "C" int r2_ring_allreduce_sim_inflight(const r2_sim_desc *desc, void *con
     }
     if (any && !plans) return R2_ERR_INVALID;
     if (!any) {
-        if (plans && s.chunk_bytes) {  // every row is written: zero
+        if (plans) {  // every row is written: zero
             rc = launch_inflight_plans(epochs, nullptr, n_epochs, s.C, desc->align, s.chunk_bytes, s.n_tx, plans,
                                        (hipStream_t)stream);
             if (rc) return rc;
@@ -612,11 +612,9 @@ extern "C" int r2_ring_allreduce_sim_inflight(const r2_sim_desc *desc, void *con
         }
         if (!rank_bufs) return R2_ERR_INVALID;
         if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
-        if (s.chunk_bytes) {
-            rc = launch_inflight_plans(epochs, in_flight, n_epochs, s.C, desc->align, s.chunk_bytes, s.n_tx, plans,
-                                       (hipStream_t)stream);
-            if (rc) return rc;
-        }
+        rc = launch_inflight_plans(epochs, in_flight, n_epochs, s.C, desc->align, s.chunk_bytes, s.n_tx, plans,
+                                   (hipStream_t)stream);
+        if (rc) return rc;
         return r2_ring_allreduce_sim(desc, rank_bufs, seen.data(), (uint32_t)seen.size(), workspace, workspace_bytes,
                                      offsets_log, stream);
     } catch (const std::bad_alloc &) {

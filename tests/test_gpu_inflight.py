@@ -137,6 +137,20 @@ def test_inflight_without_flags_is_the_plain_run(r2, oracle):
     assert all(to_host(b, x).tobytes() == e.tobytes() for b, x, e in zip(bufs, xs, want))
 
 
+def test_inflight_empty_buffers_still_get_their_plans_written(r2):
+    """Nothing to move: the run is a no-op, and every row of the plans is written all the same (zero: an
+    empty chunk has empty slices)."""
+    eq = tuple([1] * 4)
+    desc = r2.SimDesc(4, 2, 4, 16, 0, r2.F32, r2.PHASE_AR)
+    bufs = [torch.zeros(4, dtype=torch.float32, device="cuda") for _ in range(4)]
+    ws = torch.empty(max(r2.r2_sim_workspace_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    plans = torch.full((2, 4, 5), -1, dtype=torch.int64, device="cuda")
+    say("in flight: empty buffers")
+    r2.r2_ring_allreduce_sim_inflight(desc, bufs, [(0, 0, eq), (3, 0b10, eq)], [False, True], ws, None, plans)
+    torch.cuda.synchronize()
+    assert int(plans.abs().max()) == 0
+
+
 def test_inflight_argument_errors(r2):
     w = wl.scaled(wl.cfg2(), 8 * 4096)
     desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, r2.BF16, r2.PHASE_AR)
