@@ -471,7 +471,8 @@ typedef struct {
     uint64_t n_elems;         /* elements per rank                           */
     uint64_t n_partial;       /* elements of the tail (partial all-reduce)   */
     int32_t dtype;            /* r2_dtype                                    */
-    int32_t schedule;         /* R2_SCHED_* for the two ring runs            */
+    int32_t schedule;         /* R2_SCHED_AUTO, _STEPS or _FUSED for the two ring runs (they already run
+                                 side by side: no R2_SCHED_STEPS_OVERLAP)    */
     uint32_t n_slabs_global;  /* slabs of the global ring run, >= 1          */
     uint32_t n_slabs_partial; /* slabs of the partial ring run, >= 1         */
 } r2_split_desc;
@@ -578,7 +579,7 @@ typedef struct {
     uint32_t n_channels; /* C                                       */
     uint32_t align;      /* partition alignment, a multiple of 16   */
     int32_t dtype;       /* r2_dtype                                */
-    int32_t schedule;    /* R2_SCHED_* for the ring runs            */
+    int32_t schedule;    /* R2_SCHED_AUTO, _STEPS or _FUSED for the ring runs (no R2_SCHED_STEPS_OVERLAP) */
     uint32_t n_slabs;    /* slabs of every ring run, >= 1           */
     uint32_t n_levels;   /* 1..R2_MAX_LEVELS                        */
     uint32_t reserved;   /* 0                                       */

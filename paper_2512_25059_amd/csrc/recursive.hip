@@ -165,6 +165,7 @@ int rec_shape(const r2_recursive_desc *d, const r2_level *levels, const uint64_t
     if (d->align == 0 || d->align % 16 != 0) return R2_ERR_INVALID;
     if (d->dtype != R2_F32 && d->dtype != R2_BF16) return R2_ERR_INVALID;
     if (d->n_levels == 0 || d->n_levels > R2_MAX_LEVELS || d->n_slabs == 0 || d->reserved != 0) return R2_ERR_INVALID;
+    if (d->schedule == R2_SCHED_STEPS_OVERLAP) return R2_ERR_INVALID;  // the levels already run side by side
     const uint32_t R = d->n_ranks;
     const uint64_t all = R == 64 ? ~0ull : ((1ull << R) - 1);
     s.elem = d->dtype == R2_F32 ? 4 : 2;

@@ -30,6 +30,8 @@ int split_shape(const r2_split_desc *d, SplitShape &s)
     if (d->dtype != R2_F32 && d->dtype != R2_BF16) return R2_ERR_INVALID;
     if (d->n_partial > d->n_elems) return R2_ERR_INVALID;
     if (d->n_slabs_global == 0 || d->n_slabs_partial == 0) return R2_ERR_INVALID;
+    // the two rings already run side by side on the library's streams: no overlapped passes inside them
+    if (d->schedule == R2_SCHED_STEPS_OVERLAP) return R2_ERR_INVALID;
     s.elem = d->dtype == R2_F32 ? 4 : 2;
     s.n_partial = d->n_partial;
     s.n_global = d->n_elems - d->n_partial;

@@ -175,6 +175,16 @@ def test_overlapped_schedule_cuts_at_least_two_passes(r2):
     assert r2.r2_sim_resolve_schedule(mk(1 << 26, 1, r2.SCHED_AUTO), [(0, 0, [1] * 8)]) == r2.SCHED_STEPS  # never by itself
 
 
+def test_forking_schedules_do_not_nest(r2):
+    """The split and the recursive all-reduce fork the caller's stream themselves; the overlapped step
+    schedule, which forks too, is refused inside them (host check, no GPU needed)."""
+    assert r2.r2_split_workspace_bytes(r2.SplitDesc(4, 1, 2, 16, 7 * 64, 3 * 64, r2.F32, r2.SCHED_STEPS)) > 0
+    assert r2.r2_split_workspace_bytes(r2.SplitDesc(4, 1, 2, 16, 7 * 64, 3 * 64, r2.F32, r2.SCHED_STEPS_OVERLAP)) == 0
+    lv = [r2.Level(0b1111, 0, 8, 8, 1.0)]
+    assert r2.r2_recursive_workspace_bytes(r2.RecursiveDesc(4, 4, 16, 64, r2.F32, 1, 1, r2.SCHED_STEPS), lv, [64]) > 0
+    assert r2.r2_recursive_workspace_bytes(r2.RecursiveDesc(4, 4, 16, 64, r2.F32, 1, 1, r2.SCHED_STEPS_OVERLAP), lv, [64]) == 0
+
+
 def test_rails_schedule_is_host_arithmetic(r2):
     """r2_rails_resolve_schedule: fused columns for launch-bound sizes whose ring chunks are whole
     16-byte vectors and whose links' rows fit LDS, else one launch per step; the errors r2_ring_rails_sim

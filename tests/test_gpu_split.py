@@ -111,7 +111,8 @@ def test_split_argument_checks(r2):
     ok = dict(n_ranks=4, degraded_rank=1, n_channels=2, align=16, n_elems=4 * 64 + 3 * 64, n_partial=3 * 64, dtype=0)
     assert r2.r2_split_workspace_bytes(r2.SplitDesc(**ok)) > 0
     for bad in (dict(n_ranks=2), dict(degraded_rank=4), dict(n_partial=10 ** 9), dict(n_partial=3 * 64 + 3),
-                dict(align=8), dict(n_channels=0), dict(dtype=5), dict(n_slabs_global=0)):
+                dict(align=8), dict(n_channels=0), dict(dtype=5), dict(n_slabs_global=0),
+                dict(schedule=3)):  # the two rings already run side by side: no overlapped passes inside them
         assert r2.r2_split_workspace_bytes(r2.SplitDesc(**{**ok, **bad})) == 0, bad
     desc = r2.SplitDesc(**ok)
     ws = torch.empty(r2.r2_split_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
