@@ -315,13 +315,13 @@ def test_sim_random_configurations(r2, oracle, seed):
         _full_compare_small(r2, oracle, w, window=window, check_stage=one_pass or len(eps) == 1, schedule=schedule)
 
 
-def test_sim_random_mid_sizes(r2, oracle):
-    """Random configurations of 0.25 to 17 MiB per rank -- the sizes where the library's own choice flips
-    between fused columns and one launch per step -- with random channel schedules, pass windows and
-    schedules: the buffers against the definition, the offsets log against the oracle's partition."""
-    rng = np.random.default_rng(9100)
+def _random_mid_sizes(r2, oracle, seed, n_cases, schedules):
+    """Random configurations of 0.25 to 17 MiB per rank with random channel schedules, pass windows and
+    schedules: the buffers against the definition, the offsets log against the oracle's partition.
+    Returns how many of them ran on fused columns."""
+    rng = np.random.default_rng(seed)
     n_fused = 0
-    for case in range(14):
+    for case in range(n_cases):
         R, S, C = int(rng.integers(2, 17)), int(rng.integers(1, 9)), int(rng.integers(1, 17))
         dtype = "f32" if rng.random() < 0.5 else "bf16"
         es = 4 if dtype == "f32" else 2
@@ -335,12 +335,12 @@ def test_sim_random_mid_sizes(r2, oracle):
         for t in sorted(set(int(x) for x in rng.integers(1, n_tx + 1, int(rng.integers(0, 5))))):
             epochs.append((t, int(rng.integers(0, (1 << C) - 1)), tuple(int(x) for x in rng.integers(1, 100000, C))))
         window = int(rng.choice([0, 0, 0, 1 << 20, 7 << 20]))
-        schedule = int(rng.choice([0, 0, 1, 2]))
+        schedule = int(rng.choice(schedules))
         if schedule == 2 and (E * es) % 16:
             schedule = 0
         w = wl.Workload(f"mid{case}", R, dtype, E * S * R, S, C, (16, 256)[int(rng.integers(0, 2))], phases, 1.0,
                         2000 + case, tuple(epochs))
-        say(f"mid-size {case}: R={R} S={S} C={C} {dtype} {phases} {w.N * es / 2 ** 20:.2f} MiB/rank window={window} "
+        say(f"mid-size {seed}.{case}: R={R} S={S} C={C} {dtype} {phases} {w.N * es / 2 ** 20:.2f} MiB/rank window={window} "
             f"schedule={schedule} epochs={[(e[0], e[1]) for e in epochs]}")
         xs = wl.make_inputs(w)
         outs, log, ws, desc = run_gpu_sim(r2, w, xs, window=window, schedule=schedule)
@@ -352,7 +352,19 @@ def test_sim_random_mid_sizes(r2, oracle):
         assert log.tolist() == expected_log(oracle, w).tolist(), f"case {case}: offsets log"
         del ws, outs, xs, want
         torch.cuda.empty_cache()
+    return n_fused
+
+
+def test_sim_random_mid_sizes(r2, oracle):
+    """The sizes where the library's own choice flips between fused columns and one launch per step."""
+    n_fused = _random_mid_sizes(r2, oracle, 9100, 14, [0, 0, 1, 2])
     assert 2 <= n_fused <= 12  # both schedules were exercised
+
+
+def test_sim_random_mid_sizes_overlapped_passes(r2, oracle):
+    """The same kind of cases under the schedule that issues pairs of passes side by side on two streams:
+    odd pass counts, byte-range passes and slab groups, state changes anywhere."""
+    _random_mid_sizes(r2, oracle, 9300, 12, [3])
 
 
 def test_sim_result_independent_of_schedule(r2, oracle):
