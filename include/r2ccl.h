@@ -245,9 +245,14 @@ typedef struct {
                             stream (default priority, created once per device, forked off `stream`
                             after the partition launch and joined to it again with events before
                             the call returns to the caller's order): while one pass's launch ramps
-                            up or drains, the other's fills the GPU.  Passes are independent, so
-                            the result is the same.  Never chosen by AUTO; not with
-                            R2_PHASE_LINKS.                                                      */
+                            up or drains, the other's fills the GPU.  Two passes only run side by
+                            side if they cover different slabs, or if one channel state holds for
+                            the whole run: byte ranges of one slab share its stage buffers, and a
+                            pass that is a step ahead under a newer table would overwrite what the
+                            other has not read yet.  So with a state that changes on the way the
+                            two streams take the even and the odd slabs, and a run of a single slab
+                            takes the plain step schedule.  The result is the same as that of
+                            R2_SCHED_STEPS.  Never chosen by AUTO; not with R2_PHASE_LINKS.      */
     int32_t root;        /* R2_PHASE_BROADCAST: the rank whose buffer everybody gets;
                             R2_PHASE_REDUCE: the rank that gets the sum; otherwise 0              */
 } r2_sim_desc;

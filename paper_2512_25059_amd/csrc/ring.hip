@@ -144,6 +144,12 @@ int check_epochs(const r2_epoch *epochs, uint32_t n, const SimShape &s)
     return R2_OK;
 }
 
+// One channel state for every transmission of the run?
+bool single_state(const r2_epoch *epochs, uint32_t n, const SimShape &s)
+{
+    return n < 2 || epochs[1].t_start >= s.n_tx;
+}
+
 // The plain ring's fused columns: not for per-link tables (rails.hip has those).
 bool fused_eligible(const SimShape &s) { return !s.links && columns_fit(s); }
 
@@ -505,6 +511,14 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
     if ((rc = check_epochs(epochs, n_epochs, s))) return rc;
     if ((rc = check_workspace(workspace, workspace_bytes, s))) return rc;
 
+    if (desc->schedule == R2_SCHED_STEPS_OVERLAP && s.S == 1 && !single_state(epochs, n_epochs, s)) {
+        // One slab whose channel state changes on the way: its byte ranges cannot run side by side
+        // (see below), so the run takes the plain step schedule, with that schedule's window.
+        r2_sim_desc plain = *desc;
+        plain.schedule = R2_SCHED_STEPS;
+        return r2_ring_allreduce_sim(&plain, rank_bufs, epochs, n_epochs, workspace, workspace_bytes, offsets_log, stream);
+    }
+
     bool cut[2 * R2_MAX_RANKS];
     const bool fused = s.chunk_bytes && plan_schedule(desc, s, epochs, n_epochs, cut) == R2_SCHED_FUSED;
     if (fused) {
@@ -548,18 +562,32 @@ extern "C" int r2_ring_allreduce_sim(const r2_sim_desc *desc, void *const *rank_
         if ((rc = hip_rc(hipGetLastError()))) return rc;
     }
     if (desc->schedule == R2_SCHED_STEPS_OVERLAP && s.n_passes >= 2) {
-        // Pairs of passes side by side, issued step by step alternately so that their launches
-        // interleave in time.  The fork point lies behind the partition launch, which both lanes need.
+        // Two passes side by side, issued step by step alternately so that their launches interleave in
+        // time.  Passes that cover different slabs share nothing.  Byte ranges of ONE slab share its
+        // stage buffers: under one table their slices are disjoint, but a pass that is a step ahead and
+        // already writes with a newer table would overwrite stage bytes the other has not read yet (the
+        // hazard of the fused columns).  So such passes only run side by side while one channel state
+        // holds for the whole run; otherwise the lanes are split by slab (even / odd), and a run of a
+        // single slab was sent to the plain schedule above.  The fork point lies behind the partition
+        // launch, which both lanes need.
+        const bool by_slab = s.n_sub > 1 && !single_state(epochs, n_epochs, s);
         ForkJoin lanes((hipStream_t)stream);
         if (lanes.rc()) return lanes.rc();
-        void *const side = lanes.lane(1);
-        for (uint64_t p = 0; p < s.n_passes; p += 2)
-            for (uint32_t j = 0; j < s.J; ++j) {
-                if ((rc = r2_sim_step(desc, rank_bufs, p, j, workspace, workspace_bytes, stream))) return rc;
-                if (p + 1 < s.n_passes &&
-                    (rc = r2_sim_step(desc, rank_bufs, p + 1, j, workspace, workspace_bytes, side)))
-                    return rc;
-            }
+        void *const lane[2] = {stream, lanes.lane(1)};
+        uint64_t next[2] = {0, 0};  // per lane: the pass it takes next
+        auto mine = [&](uint64_t p, unsigned l) { return ((by_slab ? p / s.n_sub : p) & 1u) == l; };
+        for (;;) {
+            for (unsigned l = 0; l < 2; ++l)
+                while (next[l] < s.n_passes && !mine(next[l], l)) ++next[l];
+            if (next[0] >= s.n_passes && next[1] >= s.n_passes) break;
+            for (uint32_t j = 0; j < s.J; ++j)
+                for (unsigned l = 0; l < 2; ++l)
+                    if (next[l] < s.n_passes &&
+                        (rc = r2_sim_step(desc, rank_bufs, next[l], j, workspace, workspace_bytes, lane[l])))
+                        return rc;
+            ++next[0];
+            ++next[1];
+        }
         return lanes.join();
     }
     for (uint64_t p = 0; p < s.n_passes; ++p)

@@ -361,6 +361,39 @@ def test_sim_random_mid_sizes(r2, oracle):
     assert 2 <= n_fused <= 12  # both schedules were exercised
 
 
+def test_sim_overlapped_passes_never_share_a_slab_across_tables(r2, oracle):
+    """Byte ranges of one slab share its stage buffers; under different tables their slices overlap, so a
+    pass that runs a step ahead of its neighbour on the other stream would overwrite stage bytes that
+    are still to be read.  Shapes that provoke it: many byte ranges per slab (a window far below a
+    chunk), a new channel state at every transmission, enough bytes for the two streams to drift apart.
+    One slab (the run must take the plain schedule), two and five slabs (the streams take the even and
+    the odd slabs), both types; several runs each, every one bit-exact."""
+    from dataclasses import replace
+
+    for R, S, dtype, phases in ((10, 1, "bf16", "ar"), (12, 5, "bf16", "ag"), (16, 2, "f32", "rs"), (8, 2, "bf16", "ar")):
+        es = 4 if dtype == "f32" else 2
+        C = 11
+        E = (1 << 20) // es // 8 * 8 + 8  # chunks of just over 1 MiB
+        n_tx = S * ((2 * R - 2) if phases == "ar" else (R - 1))
+        rng = np.random.default_rng(R * 100 + S)
+        epochs = tuple((t, int(rng.integers(0, (1 << C) - 1)), tuple(int(x) for x in rng.integers(1, 100000, C)))
+                       for t in range(n_tx))
+        w = replace(wl.cfg1(), name=f"overlap_hazard_R{R}_S{S}", R=R, dtype=dtype, N=E * S * R, S=S, C=C, align=16,
+                    phases=phases, sigma=1.0, seed=R + S, epochs=epochs)
+        xs = wl.make_inputs(w)
+        _, _, odt, oph = codes(r2, oracle, w)
+        want = oracle.expected(xs, odt, S, oph)
+        for attempt in range(3):
+            say(f"overlapped passes across tables: R={R} S={S} {dtype} {phases} chunk {E * es} B, window 1 MiB, "
+                f"{len(epochs)} states, run {attempt}")
+            outs, log, ws, desc = run_gpu_sim(r2, w, xs, window=1 << 20, schedule=3)
+            assert r2.r2_sim_num_passes(desc) > 2 * S
+            for r in range(R):
+                assert outs[r].tobytes() == want[r].tobytes(), f"rank {r}"
+            assert log.tolist() == expected_log(oracle, w).tolist()
+            del ws, outs
+
+
 def test_sim_random_mid_sizes_overlapped_passes(r2, oracle):
     """The same kind of cases under the schedule that issues pairs of passes side by side on two streams:
     odd pass counts, byte-range passes and slab groups, state changes anywhere."""
