@@ -304,8 +304,10 @@ int r2_sim_step(const r2_sim_desc *desc, void *const *rank_bufs, uint64_t pass, 
 int r2_sim_fused_steps(const r2_sim_desc *desc, void *const *rank_bufs, uint32_t step_begin,
                        uint32_t step_end, void *workspace, uint64_t workspace_bytes, void *stream);
 
-/* Which schedule r2_ring_allreduce_sim will use for this descriptor and epoch list: R2_SCHED_STEPS
- * or R2_SCHED_FUSED (desc->schedule itself unless that is R2_SCHED_AUTO), or a negative R2_ERR code
+/* Which schedule r2_ring_allreduce_sim will use for this descriptor and epoch list: R2_SCHED_STEPS,
+ * R2_SCHED_FUSED or R2_SCHED_STEPS_OVERLAP (desc->schedule itself unless that is R2_SCHED_AUTO, or
+ * R2_SCHED_STEPS_OVERLAP for a single slab whose channel state changes on the way, which runs as
+ * R2_SCHED_STEPS), or a negative R2_ERR code
  * (R2_ERR_INVALID for R2_PHASE_LINKS: ask r2_rails_resolve_schedule).  Host arithmetic only. */
 int r2_sim_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *epochs, uint32_t n_epochs);
 

@@ -403,6 +403,8 @@ extern "C" int r2_sim_resolve_schedule(const r2_sim_desc *desc, const r2_epoch *
     if (s.links) return R2_ERR_INVALID;  // one epoch list cannot say what a ring with per-link tables will do
     if ((rc = check_epochs(epochs, n_epochs, s))) return rc;
     if (desc->schedule == R2_SCHED_FUSED && s.chunk_bytes && !fused_eligible(s)) return R2_ERR_INVALID;
+    // one slab whose state changes on the way has no two passes that may run side by side
+    if (desc->schedule == R2_SCHED_STEPS_OVERLAP && s.S == 1 && !single_state(epochs, n_epochs, s)) return R2_SCHED_STEPS;
     bool cut[2 * R2_MAX_RANKS];
     return plan_schedule(desc, s, epochs, n_epochs, cut);
 }

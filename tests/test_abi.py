@@ -173,6 +173,12 @@ def test_overlapped_schedule_cuts_at_least_two_passes(r2):
     assert r2.r2_sim_num_passes(mk(8 * 3 * 64, 3, r2.SCHED_STEPS_OVERLAP)) == 3  # three small slabs: one by one
     assert r2.r2_sim_resolve_schedule(mk(1 << 26, 1, r2.SCHED_STEPS_OVERLAP), [(0, 0, [1] * 8)]) == r2.SCHED_STEPS_OVERLAP
     assert r2.r2_sim_resolve_schedule(mk(1 << 26, 1, r2.SCHED_AUTO), [(0, 0, [1] * 8)]) == r2.SCHED_STEPS  # never by itself
+    # one slab whose channel state changes on the way: its byte ranges share stage buffers under different
+    # tables and may not run side by side -> the plain step schedule; with several slabs the streams split by slab
+    changing = [(0, 0, [1] * 8), (3, 0b100100, [1] * 8)]
+    assert r2.r2_sim_resolve_schedule(mk(1 << 26, 1, r2.SCHED_STEPS_OVERLAP), changing) == r2.SCHED_STEPS
+    assert r2.r2_sim_resolve_schedule(mk(1 << 26, 2, r2.SCHED_STEPS_OVERLAP), changing) == r2.SCHED_STEPS_OVERLAP
+    assert r2.r2_sim_resolve_schedule(mk(1 << 26, 1, r2.SCHED_STEPS_OVERLAP), [(0, 0, [1] * 8), (14, 1, [1] * 8)]) == r2.SCHED_STEPS_OVERLAP  # beyond the run
 
 
 def test_forking_schedules_do_not_nest(r2):
