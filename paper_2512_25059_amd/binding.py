@@ -1,4 +1,4 @@
-"""ctypes binding of ``libr2ccl.so`` (see ``include/r2ccl.h`` for the contract).
+"""ctypes binding of ``libr2ccl.so`` (see ``include/r2ccl.h`` and ``include/r2ccl_ext.h`` for the contract).
 
 Argument marshalling only.  torch is used for device memory and streams; a
 torch tensor stands for "device pointer + size".  Each wrapper has the name of

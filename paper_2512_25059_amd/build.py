@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("partition.hip", "ring.hip", "rails.hip", "split.hip", "recursive.hip", "streams.hip", "rerank.cpp")]
-HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + [os.path.join(ROOT, "include", "r2ccl.h")]
+HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
 LIB = os.path.join(HERE, "libr2ccl.so")
 EXAMPLE_SRC = os.path.join(HERE, "examples", "ring_allreduce.c")
 EXAMPLE = os.path.join(HERE, "examples", "ring_allreduce")

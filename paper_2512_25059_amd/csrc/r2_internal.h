@@ -4,7 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "r2ccl.h"
+#include "r2ccl_ext.h"
 
 namespace r2 {
 

@@ -14,7 +14,7 @@
 #include <new>
 #include <vector>
 
-#include "r2ccl.h"
+#include "r2ccl_ext.h"
 
 namespace {
 

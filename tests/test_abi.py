@@ -7,7 +7,12 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "r2ccl.h")
+INCLUDE = os.path.join(ROOT, "include")
+HEADERS = [os.path.join(INCLUDE, "r2ccl.h"), os.path.join(INCLUDE, "r2ccl_ext.h")]
+
+
+def _header_text():
+    return "\n".join(open(h).read() for h in HEADERS)
 
 
 @pytest.fixture(scope="module")
@@ -22,7 +27,7 @@ def r2():
 
 
 def _declared_functions():
-    text = open(HEADER).read()
+    text = _header_text()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(r2_[a-z0-9_]+)\s*\(", text)))
 
@@ -33,13 +38,13 @@ def test_header_symbols_are_exported(r2):
             "r2_sim_prepare", "r2_sim_step", "r2_sim_workspace_bytes", "r2_strerror"} <= set(names)
     lib = C.CDLL(r2.library_path())
     for n in names:
-        assert hasattr(lib, n), f"{n} is declared in r2ccl.h but not exported"
+        assert hasattr(lib, n), f"{n} is declared in include/*.h but not exported"
 
 
 def test_binding_constants_and_structs_follow_the_header(r2):
     """The Python names carry the header's values, every exported function has a binding of the same name,
     and the descriptor structs are laid out as the C compiler lays them out."""
-    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    text = re.sub(r"/\*.*?\*/", "", _header_text(), flags=re.S)
     enums = dict((k, int(v)) for k, v in re.findall(r"\b(R2_[A-Z0-9_]+)\s*=\s*(-?\d+)", text))
     defines = dict((k, int(v)) for k, v in re.findall(r"#define\s+(R2_[A-Z0-9_]+)\s+(\d+)", text))
     assert len(enums) >= 20
@@ -55,12 +60,12 @@ def test_binding_constants_and_structs_follow_the_header(r2):
     import subprocess
     import tempfile
     names = ["r2_sim_desc", "r2_split_desc", "r2_recursive_desc", "r2_level", "r2_epoch"]
-    src = '#include <stdio.h>\n#include "r2ccl.h"\nint main(void){' + "".join(
+    src = '#include <stdio.h>\n#include "r2ccl_ext.h"\nint main(void){' + "".join(
         f'printf("%zu\\n", sizeof({n}));' for n in names) + "return 0;}"
     with tempfile.TemporaryDirectory() as d:
         c, exe = os.path.join(d, "s.c"), os.path.join(d, "s")
         open(c, "w").write(src)
-        subprocess.run(["gcc", "-I", os.path.dirname(HEADER), c, "-o", exe], check=True)
+        subprocess.run(["gcc", "-I", INCLUDE, c, "-o", exe], check=True)
         sizes = [int(x) for x in subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()]
     b = r2.binding
     assert sizes == [C.sizeof(b._SimDesc), C.sizeof(b._SplitDesc), C.sizeof(b._RecursiveDesc), C.sizeof(b._Level),
