@@ -58,6 +58,67 @@ def test_ring_run_in_a_graph(r2, oracle, schedule):
         assert log.cpu().numpy().any()
 
 
+def _replayed_run(r2, oracle, w, run, what):
+    """Captures `run(bufs)` in a graph after one eager call, replays it four times from pristine inputs
+    with eager work in between, and checks every replay against the oracle's result."""
+    dt, ph, odt, oph = codes(r2, oracle, w)
+    xs = wl.make_inputs(w)
+    want = oracle.expected(xs, odt, w.S, oph)
+    pristine = [to_device(x) for x in xs]
+    bufs = [p.clone() for p in pristine]
+    say(f"graph capture: {what}")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(bufs)  # once outside the capture: streams, events and symbol addresses are looked up here
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(bufs)
+    for replay in range(4):
+        say(f"graph replay {replay}: {what}")
+        for b, p in zip(bufs, pristine):
+            b.copy_(p)
+        junk = torch.randn(1 << 16, device="cuda").sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for r in range(w.R):
+            assert np.array_equal(bufs[r].cpu().numpy().view(xs[r].dtype), want[r]), f"{what}: replay {replay}, rank {r}"
+
+
+def test_overlapped_passes_in_a_graph(r2, oracle):
+    """The overlapped step schedule forks the caller's stream behind its partition launch and joins it
+    again: captured, a fork and a join inside the graph.  32 slabs in two groups, a flapping channel."""
+    w = wl.scaled(wl.cfg4(S=32), 8 * 32 * 4096)
+    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, r2.BF16, r2.PHASE_AR, 0, r2.SCHED_STEPS_OVERLAP)
+    assert r2.r2_sim_num_passes(desc) == 2
+    ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    _replayed_run(r2, oracle, w, lambda bufs: r2.r2_ring_allreduce_sim(desc, bufs, w.epochs, ws), "overlapped passes")
+
+
+@pytest.mark.parametrize("schedule", [1, 2])
+def test_inflight_run_in_a_graph(r2, oracle, schedule):
+    """The run with a failure in flight: its plan launch and the run in one graph; the plan of every
+    replay is the oracle's."""
+    w = wl.scaled(wl.cfg2(), 8 * 8192 * 4)
+    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, r2.BF16, r2.PHASE_AR, 0, schedule)
+    ws = torch.empty(r2.r2_sim_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    plans = torch.zeros((2, w.C, w.C + 1), dtype=torch.int64, device="cuda")
+
+    def run(bufs):
+        plans.fill_(-1)  # a fill kernel, captured with the rest: every replay must write the plans anew
+        r2.r2_ring_allreduce_sim_inflight(desc, bufs, w.epochs, [False, True], ws, None, plans)
+
+    _replayed_run(r2, oracle, w, run, f"failure in flight, schedule {schedule}")
+    old = oracle.partition(w.epochs[0][2], w.epochs[0][1], w.chunk_bytes, w.align)
+    want = oracle.rollback_plan(old, w.epochs[1][2], w.epochs[0][1], w.epochs[1][1], w.align)
+    got = plans.cpu().numpy().view(np.uint64)
+    assert got[0].tolist() == np.zeros_like(want).tolist() and got[1].tolist() == want.tolist()
+
+
 def test_split_run_in_a_graph(r2, oracle):
     """The split all-reduce forks the caller's stream into a library-owned one and joins it again with
     events; captured, that becomes a fork and a join inside the graph."""

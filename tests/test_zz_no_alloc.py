@@ -63,6 +63,38 @@ def test_static_workspace_matches_caller_workspace(r2, oracle, pair, schedule):
         assert got_log.tolist() == expected_log(oracle, w).tolist()
 
 
+@pytest.mark.parametrize("schedule", [1, 2], ids=["steps", "fused"])
+def test_static_workspace_run_in_a_graph(r2, oracle, schedule):
+    """What the entry point is for: a caller under graph capture, where nothing may be allocated.  One
+    eager call first (the array's address is looked up then), then the call is captured and replayed
+    four times from pristine inputs, every replay against the oracle."""
+    w = wl.cfg5(64)
+    _, _, odt, oph = codes(r2, oracle, w)
+    xs = wl.make_inputs(w)
+    want = oracle.expected(xs, odt, w.S, oph)
+    desc = r2.SimDesc(w.R, w.S, w.C, w.align, w.N, r2.BF16, r2.PHASE_AR, 0, schedule)
+    pristine = [to_device(x) for x in xs]
+    bufs = [p.clone() for p in pristine]
+    say(f"static workspace under graph capture, schedule={schedule}")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        r2.r2_ring_allreduce_sim_static(desc, bufs, w.epochs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        r2.r2_ring_allreduce_sim_static(desc, bufs, w.epochs)
+    for replay in range(4):
+        for b, p in zip(bufs, pristine):
+            b.copy_(p)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for r in range(w.R):
+            assert np.array_equal(to_host(bufs[r], xs[r]), want[r]), f"replay {replay}, rank {r}"
+
+
 def test_static_workspace_refuses_what_does_not_fit(r2):
     """A run that needs more than the array holds is refused before anything is launched; the same
     arguments that r2_ring_allreduce_sim refuses are refused here too."""
