@@ -596,6 +596,68 @@ def recursive_line(r2, torch, np, wl, out=sys.stderr):
           f"selector (alpha 5 us, 50 MB/s per unit of weight) picks depth {depth}", file=out, flush=True)
 
 
+def stream_mix_lines(torch, out=sys.stderr):
+    """What this GPU's memory system gives bare kernels with the step kernel's access shape and none of its
+    tables or slices (csrc/stream_probe.hip, a library of its own): cold mixes of one or two read and write
+    streams of 256 MiB each over 3 GiB of rotated buffers, and the ring step's own pattern, in which the
+    stage one launch writes is what the next reads, at 64 and 128 MiB per stream (cfg4's and cfg2's launch
+    sizes).  The product's launches are to be read against these, not against the nominal peak alone."""
+    import ctypes
+
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_25059_amd", "libr2probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError("libr2probe.so is not built: run `python -m paper_2512_25059_amd.build` first")
+    lib = ctypes.CDLL(path)
+    lib.r2probe_cold_mix.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int,
+                                     ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]
+    lib.r2probe_ring_pattern.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int, ctypes.c_uint64,
+                                         ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def filled(n):  # not zeros: all-zero lines move faster through this GPU's caches than any other data
+        t = torch.empty(n, dtype=torch.uint8, device="cuda")
+        t.view(torch.bfloat16).normal_(0.0, 0.02)
+        return t
+
+    def timed(launch, reps, warm):
+        assert launch(warm) == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        assert launch(reps) == 0
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3  # us per launch
+
+    nbytes = 256 << 20
+    bufs = [filled(nbytes) for _ in range(12)]
+    addrs = (ctypes.c_uint64 * 12)(*[b.data_ptr() for b in bufs])
+    print(f"cold stream mixes, {nbytes >> 20} MiB per stream, 12 buffers in rotation, non-temporal accesses "
+          "(bare kernel, no tables):", file=out)
+    for nr, nw in ((1, 0), (2, 0), (0, 1), (0, 2), (1, 1), (2, 1), (1, 2), (2, 2)):
+        us = timed(lambda n: lib.r2probe_cold_mix(nr, nw, addrs, 12, nbytes, n, stream), 40, 4)
+        rate = (nr + nw) * nbytes / us / 1e3
+        print(f"  {nr}R{nw}W  {us:8.1f} us per launch  {rate:8.1f} GB/s  {rate / HBM_PEAK_GBPS:.3f} of the HBM peak", file=out, flush=True)
+    del bufs
+    torch.cuda.empty_cache()
+
+    print("the ring step's pattern (locals cold and non-temporal, the stage written cacheable by one launch and read "
+          "by the next), bare kernel, us per launch:", file=out)
+    streams = {0: 4, 1: 3, 2: 2, 3: 2}
+    for mib in (64, 128):
+        nbytes = mib << 20
+        locs = [filled(nbytes) for _ in range(3072 // mib)]
+        laddrs = (ctypes.c_uint64 * len(locs))(*[b.data_ptr() for b in locs])
+        sa, sb = filled(nbytes), filled(nbytes)
+        cells = []
+        for kind, name in ((0, "sum"), (1, "copy, staged"), (2, "last copy"), (3, "send")):
+            us = timed(lambda n: lib.r2probe_ring_pattern(kind, laddrs, len(locs), sa.data_ptr(), sb.data_ptr(), nbytes, n, stream), 60, 6)
+            cells.append(f"{name} {us:6.1f} ({streams[kind] * nbytes / us / 1e3 / HBM_PEAK_GBPS:.3f})")
+        print(f"  {mib:4d} MiB per stream: " + " | ".join(cells), file=out, flush=True)
+        del locs, sa, sb
+        torch.cuda.empty_cache()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -615,6 +677,9 @@ def main() -> int:
                     help="also print the all-reduce with per-link tables (cfg2 shape and cfg5's sizes) to stderr")
     ap.add_argument("--sweep", action="store_true",
                     help="also print size sweeps to stderr: r2_reduce_copy, and the whole all-reduce without and with failures")
+    ap.add_argument("--stream-mix", action="store_true",
+                    help="also print to stderr what bare kernels with the step kernel's access shape reach on this GPU "
+                         "(cold mixes of read and write streams; the ring step's warm pattern)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -796,6 +861,8 @@ def main() -> int:
         other_collectives_lines(r2, torch, np, wl)
     if args.rails and not args.all:
         rails_lines(r2, torch, np, wl)
+    if args.stream_mix:
+        stream_mix_lines(torch)
     if args.sweep:
         reduce_copy_sweep(r2, torch)
         allreduce_size_sweep(r2, torch, np, wl)

@@ -11,6 +11,8 @@ ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("partition.hip", "ring.hip", "rails.hip", "split.hip", "recursive.hip", "streams.hip", "rerank.cpp")]
 HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
 LIB = os.path.join(HERE, "libr2ccl.so")
+PROBE_SRC = os.path.join(HERE, "csrc", "stream_probe.hip")
+PROBE_LIB = os.path.join(HERE, "libr2probe.so")
 EXAMPLE_SRC = os.path.join(HERE, "examples", "ring_allreduce.c")
 EXAMPLE = os.path.join(HERE, "examples", "ring_allreduce")
 
@@ -41,7 +43,21 @@ def build(verbose: bool = False) -> str:
     if verbose and out.strip():
         print(out)
     build_example(verbose)
+    build_probe(verbose)
     return LIB
+
+
+def build_probe(verbose: bool = False) -> str:
+    """The bare-kernel memory probe `bench.py --stream-mix` times beside the product: a library of its own,
+    so that nothing of it is in libr2ccl.so."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, "-o", PROBE_LIB, PROBE_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on the stream probe:\n" + res.stdout)
+    return PROBE_LIB
 
 
 def build_example(verbose: bool = False) -> str:
