@@ -35,3 +35,36 @@ def test_graft_entry_has_build_and_smoke():
     sys.path.insert(0, ROOT)
     entry = importlib.import_module("__graft_entry__")
     assert callable(entry.build) and callable(entry.smoke)
+
+
+def test_stream_probe_is_a_library_of_its_own():
+    """The bare kernels `bench.py --stream-mix` times are measurement aids: they sit in libr2probe.so, which
+    exports its two calls and refuses arguments that do not fit them before any launch; nothing of them is in
+    the product library, and the package never loads them."""
+    import ctypes
+
+    pkg = os.path.join(ROOT, "paper_2512_25059_amd")
+    probe = os.path.join(pkg, "libr2probe.so")
+    if not os.path.exists(probe):
+        from paper_2512_25059_amd import build
+
+        build.build_probe()
+    lib = ctypes.CDLL(probe)
+    lib.r2probe_cold_mix.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int,
+                                     ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]
+    lib.r2probe_ring_pattern.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int, ctypes.c_uint64,
+                                         ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]
+    four = (ctypes.c_uint64 * 4)(4096, 8192, 12288, 16384)
+    assert lib.r2probe_cold_mix(1, 1, four, 4, 8191, 1, None) == -1  # not a whole number of tiles
+    assert lib.r2probe_cold_mix(3, 0, four, 4, 8192, 1, None) == -1  # at most two streams each way
+    assert lib.r2probe_cold_mix(0, 0, four, 4, 8192, 1, None) == -1
+    assert lib.r2probe_cold_mix(1, 1, four, 3, 8192, 1, None) == -1  # four buffers at least
+    assert lib.r2probe_cold_mix(1, 1, None, 4, 8192, 1, None) == -1
+    assert lib.r2probe_ring_pattern(4, four, 4, 4096, 8192, 8192, 1, None) == -1
+    assert lib.r2probe_ring_pattern(0, four, 4, 0, 8192, 8192, 1, None) == -1
+    assert lib.r2probe_ring_pattern(0, four, 4, 4096, 8200, 8192, 1, None) == -1  # stage not 16-byte aligned
+    product = ctypes.CDLL(os.path.join(pkg, "libr2ccl.so"))
+    assert not hasattr(product, "r2probe_cold_mix") and not hasattr(product, "r2probe_ring_pattern")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            assert "r2probe" not in open(os.path.join(pkg, name)).read() or name == "build.py"
