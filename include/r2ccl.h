@@ -24,9 +24,9 @@
  *   - "device" pointers are HIP device memory of the current device, "host" pointers
  *     are ordinary process memory.  The caller owns every buffer.  The library allocates no
  *     device memory.  The only state it keeps for the life of the process, per device: the side
- *     streams and events of r2_split_allreduce_sim / r2_recursive_allreduce_sim, created at their
- *     first call, and two device arrays that are part of its code (see r2_ring_allreduce_sim_static
- *     and r2_partition).
+ *     streams and events of r2_split_allreduce_sim, r2_recursive_allreduce_sim and the
+ *     R2_SCHED_STEPS_OVERLAP schedule, created at the first such call, and two device arrays that
+ *     are part of its code (see r2_ring_allreduce_sim_static and r2_partition).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and return; r2_partition alone waits for its result.
  *   - Data buffers (rank buffers, stage buffers) must be 16-byte aligned.
@@ -338,7 +338,8 @@ int r2_ring_allreduce_sim_inflight(const r2_sim_desc *desc, void *const *rank_bu
  * the inference sizes).  Same kernels, same result, same other arguments and errors as
  * r2_ring_allreduce_sim; rank buffers and the optional log are still the caller's.  The call makes no
  * hipMalloc/hipFree and calls nothing that allocates; the first call on a device asks the runtime once
- * for the array's address there.  All calls on one GPU share the one array: it keeps what the last call
+ * for the array's address there.  R2_SCHED_STEPS_OVERLAP is R2_ERR_INVALID here: its side stream and
+ * events would have to be created at its first use.  All calls on one GPU share the one array: it keeps what the last call
  * left (no step ever reads bytes its own run has not written, so nothing is cleared), and calls that
  * overlap in time on one GPU -- different streams, different host threads -- race on it: keep them in
  * order on one stream. */

@@ -693,6 +693,8 @@ extern "C" int r2_ring_allreduce_sim_static(const r2_sim_desc *desc, void *const
     SimShape s;
     int rc = shape_of(desc, s);
     if (rc) return rc;
+    // the overlapped schedule creates its side stream and events at first use: not for a caller that may not allocate
+    if (desc->schedule == R2_SCHED_STEPS_OVERLAP) return R2_ERR_INVALID;
     if (s.total_bytes > R2_STATIC_WORKSPACE_BYTES) return R2_ERR_CAPACITY;
     void *ws = nullptr;
     if ((rc = scratch_of_current_device(&ws))) return rc;

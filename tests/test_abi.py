@@ -196,6 +196,19 @@ def test_forking_schedules_do_not_nest(r2):
     assert r2.r2_recursive_workspace_bytes(r2.RecursiveDesc(4, 4, 16, 64, r2.F32, 1, 1, r2.SCHED_STEPS_OVERLAP), lv, [64]) == 0
 
 
+def test_static_workspace_call_refuses_the_forking_schedule(r2):
+    """The call for callers that may not allocate cannot create the overlapped schedule's side stream and
+    events either: refused on the host, before any HIP call; an oversize descriptor likewise."""
+    import ctypes
+
+    lib = r2.load_library()
+    d = r2.SimDesc(8, 1, 8, 256, 8 * 64, r2.BF16, r2.PHASE_AR, 0, r2.SCHED_STEPS_OVERLAP)
+    assert lib.r2_ring_allreduce_sim_static(ctypes.byref(d.c()), None, None, 0, None, None) == -1
+    big = r2.SimDesc(8, 1, 8, 256, 1 << 26, r2.BF16, r2.PHASE_AR)
+    assert r2.r2_sim_workspace_bytes(big) > r2.STATIC_WORKSPACE_BYTES
+    assert lib.r2_ring_allreduce_sim_static(ctypes.byref(big.c()), None, None, 0, None, None) == -4
+
+
 def test_rails_schedule_is_host_arithmetic(r2):
     """r2_rails_resolve_schedule: fused columns for launch-bound sizes whose ring chunks are whole
     16-byte vectors and whose links' rows fit LDS, else one launch per step; the errors r2_ring_rails_sim

@@ -112,3 +112,7 @@ def test_static_workspace_refuses_what_does_not_fit(r2):
     with pytest.raises(r2.R2Error) as e:
         r2.r2_ring_allreduce_sim_static(small, [b[:512] for b in bufs], [(0, 0xFF, [1] * 8)])
     assert e.value.code == -2  # no healthy channel
+    overlapped = r2.SimDesc(8, 1, 8, 256, 8 * 64, r2.BF16, r2.PHASE_AR, 0, r2.SCHED_STEPS_OVERLAP)
+    with pytest.raises(r2.R2Error) as e:  # would create a side stream and events at first use
+        r2.r2_ring_allreduce_sim_static(overlapped, [b[:512] for b in bufs], [(0, 0, [1] * 8)])
+    assert e.value.code == -1
