@@ -83,6 +83,24 @@ def test_hand_case_B_second_configuration(oracle):
         assert got.tobytes() == exp.tobytes()
 
 
+def test_plan_shares_by_the_weights_the_failure_leaves_by_hand(oracle):
+    """Two ranks, fp32, one 4 KiB chunk per rank half, four channels, 256-byte units.  Equal weights cut
+    the chunk at 1024, 2048, 3072.  Channel 0 fails during transmission 1 and the state it leaves rates
+    channels 1, 2, 3 at 3 : 1 : 0.  The struck transmission keeps the even table; channel 0's four units
+    are re-carried three by channel 1 and one by channel 2, none by channel 3 (healthy, weight 0) --
+    with the old, equal weights it would have been 1 : 1 : 2 units."""
+    rng = np.random.default_rng(8)
+    xs = [rng.standard_normal(2048).astype(np.float32) for _ in range(2)]
+    epochs = [(0, 0, (1, 1, 1, 1)), (1, 0b0001, (5, 3, 1, 0))]
+    bufs = [x.copy() for x in xs]
+    log, _, plans = inflight.ring_sim_inflight(bufs, oracle.F32, 1, 4, 256, epochs, [False, True], oracle.PHASE_AR)
+    assert log.tolist() == [[0, 1024, 2048, 3072, 4096]] * 2
+    assert sorted(plans) == [1]
+    assert plans[1].tolist() == [[0, 0, 768, 1024, 1024]] + [[0] * 5] * 3
+    for got, exp in zip(bufs, oracle.expected(xs, oracle.F32, 1, oracle.PHASE_AR)):
+        assert got.tobytes() == exp.tobytes()
+
+
 def test_invariants_random(oracle):
     """What must hold whatever the rounding: the result is the plain definition's (lossless whatever
     the failure timing); the transmission a failure strikes in keeps the table of the state before it

@@ -68,6 +68,35 @@ def test_worked_example_by_hand():
     assert rec.completion_time(lv, 4, 1, 1, 0, F(1, 100000)) == F(24, 37) > F(21, 34)
 
 
+def test_top_ring_adds_most_by_hand():
+    """Eight servers with eight equal NICs: one kept a single NIC, five kept two (that one among them),
+    two kept all eight.  Rings: all eight at 1 NIC, seven at 2 (adds 1), two at 8 (adds 6); ring factors
+    7/4, 12/7, 1.  Here it pays to let all three rings finish together (u_k = tau/f_k): shares
+    1*(4/7) : 1*(7/12) : 6*1 = 48 : 49 : 504, time 2 / (601/84) = 168/601 of D/(50000 beta).  Giving the two
+    upper levels data in proportion to what they add (u_1 = u_2 = tau*7/12) costs (1 + 7/12) / (391/84) =
+    133/391, a fifth more: which levels share one u is found by trying, not fixed."""
+    masks = [0b01111111] + [0b00111111] * 5 + [0, 0]
+    lv = rec.plan(EQ8, masks)
+    assert [l.members for l in lv] == [list(range(8)), list(range(1, 8)), [6, 7]]
+    assert [l.increment for l in lv] == [50000, 50000, 300000]
+    assert [l.share for l in lv] == [F(48, 601), F(49, 601), F(504, 601)]
+    assert rec.completion_time(lv, 8, 1, 1, 0, F(1, 50000)) == F(168, 601)
+    for l, x in zip(lv, (F(48, 391), F(49, 391), F(294, 391))):
+        l.share = x
+    assert rec.completion_time(lv, 8, 1, 1, 0, F(1, 50000)) == F(133, 391) > F(168, 601)
+
+
+def test_share_tie_goes_to_exact_proportion_by_hand():
+    """Increments 3 : 4 : 4 on rings of 10, 7 and 6 participants (ring factors 9/5, 12/7, 5/3).  Two share
+    vectors reach the minimal time 1/4: 5 : 7 : 7 of 19 (the two lower rings finish together, both upper
+    levels take data in exact proportion to what they add) and 25 : 35 : 36 of 96 (all three rings
+    finish together).  The rule takes the first: as many levels as possible in the paper's proportion."""
+    inc, parts = (3, 4, 4), (10, 7, 6)
+    assert _time_of(inc, parts, [F(5, 19), F(7, 19), F(7, 19)]) == F(1, 4)
+    assert _time_of(inc, parts, [F(25, 96), F(35, 96), F(36, 96)]) == F(1, 4)
+    assert rec.optimal_shares(inc, parts) == [F(5, 19), F(7, 19), F(7, 19)]
+
+
 def _time_of(increments, participants, shares):
     """The completion time by its definition (latency ignored, D = beta = 1), written out again here:
     the slowest ring, then the slowest broadcast."""
@@ -82,6 +111,10 @@ def _time_of(increments, participants, shares):
     ((1, 3, 2), (6, 4, 2)),            # a slow global ring under fast upper ones
     ((5, 1, 1), (16, 12, 8)),          # little to gain: X = 2/7 is below the two-ring threshold
     ((3, 3), (5, 4)),                  # two levels: the balance point of Sec. 5.2
+    ((1, 1, 6), (8, 7, 2)),            # the top ring adds most: all three rings finish together (j = 2)
+    ((1, 1, 4, 1), (8, 7, 3, 2)),      # four levels, the lower three finish together (j = 2)
+    ((1, 1, 1, 4), (9, 8, 7, 2)),      # four levels, all four finish together (j = 3)
+    ((3, 4, 4), (10, 7, 6)),           # a tie: two share vectors reach the minimum
 ])
 def test_shares_minimise_the_modelled_time_brute_force(increments, participants):
     """Every share vector on a grid of the simplex (steps of 1/120; levels above 0 may also get nothing)
