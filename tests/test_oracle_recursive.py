@@ -272,6 +272,22 @@ def test_selector_follows_the_papers_threshold_for_one_failure():
         assert depth == want, (lost, times)
 
 
+def test_latency_terms_by_hand():
+    """One ring of p participants is the textbook ring all-reduce: 2(p-1) steps of latency alpha each and
+    2(p-1)/p of the data over the ring's bandwidth.  The worked example of four servers (rings of 4, 3, 2)
+    with no data at all is latency only: the longest reduction, 2*3 steps, then the longest broadcast --
+    the top level's, which walks two servers left out, two members and the two left out again: 5 hops."""
+    for n, g in ((4, 1), (8, 8), (5, 3)):
+        lv = rec.plan(EQ8, [0] * n, g)
+        assert len(lv) == 1
+        p = n * g
+        assert rec.completion_time(lv, n, g, F(10**9), F(3, 10**6), F(7)) == \
+            2 * (p - 1) * F(3, 10**6) + F(2 * (p - 1), p) * F(10**9) / (400000 * 7)
+    lv = rec.plan(EQ8, [0b1111, 0b0011, 0, 0])
+    assert rec.completion_time(lv, 4, 1, 0, 1, 1) == 6 + 5
+    assert rec.completion_time(lv, 4, 2, 0, 1, 1) == 14 + 5      # two GPUs per server: rings of 8, 6, 4
+
+
 def test_selector_prefers_balance_for_small_messages():
     """Sec. 8 (AllReduce performance): for small messages R2CCL-Balance is faster, because the split
     schedule's extra steps cost latency; for large ones the split schedule is."""
@@ -428,6 +444,47 @@ def test_relays_between_ranks_that_share_no_rail(dtype):
     nbytes = elems[1] * xs[0].itemsize
     assert tables[0].tolist() == o.partition(w, 0b00001111, nbytes, 16).tolist()   # 0 -> relay 2: rank 0's rails
     assert tables[1].tolist() == o.partition(w, 0b11110000, nbytes, 16).tolist()   # relay 2 -> 1: rank 1's rails
+
+
+@pytest.mark.parametrize("dtype", [o.F32, o.BF16])
+def test_relay_on_the_way_in_only_by_hand(dtype):
+    """Four servers, eight equal NICs: server 0 kept NICs 0-1, server 1 lost exactly those.  The global
+    ring is re-ranked to 0 2 1 3; the upper ring 1 2 3 adds 4 to its 2.  Its broadcast starts at server 0,
+    whose first stop, server 1, shares nothing with it: the hop goes through server 2 -- before server 2's
+    own turn as a member.  The way back, 3 -> 0, needs no relay, so nothing ever repairs what the relay
+    would have damaged: server 2's own result must come out of forwarding untouched."""
+    per16 = 4 if dtype == o.F32 else 8
+    w, masks = [1] * 8, [0b11111100, 0b00000011, 0, 0]
+    lv = rec.plan(w, masks, max_levels=2)
+    assert [l.members for l in lv] == [[0, 1, 2, 3], [1, 2, 3]]
+    assert [l.order for l in lv] == [[0, 2, 1, 3], [1, 2, 3]]
+    assert [l.bandwidth for l in lv] == [2, 6]
+    assert rec.chain_visits(4, 8, masks, lv[1]) == [
+        (0, "gather"), (2, "relay"), (1, "member"), (2, "member"), (3, "member"), (0, "take")]
+    elems = [4 * per16 * 3, 3 * per16 * 4]
+    xs = _inputs(np.random.default_rng(33), 4, sum(elems), dtype)
+    bufs = [x.copy() for x in xs]
+    rec.recursive_sim(bufs, dtype, lv, elems, 1, 8, 16, w, masks)
+    want = rec.recursive_expected(xs, dtype, lv, elems, 1)
+    for r in range(4):
+        assert bufs[r].tobytes() == want[r].tobytes()
+
+
+def test_relay_is_the_first_member_linked_to_both_ends_by_hand():
+    """Five servers, eight equal NICs.  Servers 0, 1, 2 kept NICs {0,1}, {2,3}, {1,2}; server 3 lost NICs 2-3;
+    server 4 lost nothing.  The three slow servers leave together; the upper ring is 3 4.  Servers 0 and 1
+    share nothing.  Of the ring's members, server 3 is linked to 0 but not to 1, server 4 to both; server 2,
+    which is left out too, is linked to both as well.  The rule asks the members first, in ring order, and
+    wants a link to both ends: server 4 relays, on the way in and on the way out."""
+    keep = lambda *nics: 0xFF & ~sum(1 << c for c in nics)
+    masks = [keep(0, 1), keep(2, 3), keep(1, 2), 0b00001100, 0]
+    lv = rec.plan([1] * 8, masks)
+    assert [l.members for l in lv] == [[0, 1, 2, 3, 4], [3, 4]]
+    assert lv[0].order == [0, 4, 1, 2, 3] and lv[1].order == [3, 4]
+    assert [l.bandwidth for l in lv] == [1, 6]
+    assert rec.chain_visits(5, 8, masks, lv[1]) == [
+        (0, "gather"), (4, "relay"), (1, "gather"), (2, "gather"), (3, "member"), (4, "member"),
+        (0, "take"), (4, "relay"), (1, "take"), (2, "take")]
 
 
 def test_chain_visits():
