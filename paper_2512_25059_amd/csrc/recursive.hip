@@ -91,7 +91,9 @@ void optimal_shares(r2_level *levels, uint32_t L, uint32_t gpus_per_rank)
         double work = 0.0;  // sum of increment_k * u_k / tau
         for (uint32_t k = 0; k < L; ++k) work += (double)levels[k].increment / f[k <= j ? k : j];
         const double t = (1.0 + 1.0 / f[j]) / work;
-        if (j == 1 || t < best_t) {
+        // Two balance levels can reach the same time exactly (as rationals); in doubles such a tie would go
+        // to whichever rounds lower.  A later level must win by more than rounding to replace an earlier one.
+        if (j == 1 || t < best_t * (1.0 - 1e-13)) {
             best_t = t;
             for (uint32_t k = 0; k < L; ++k) levels[k].share = (double)levels[k].increment / f[k <= j ? k : j] / work;
         }

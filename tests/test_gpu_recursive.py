@@ -105,6 +105,11 @@ CASES = [
                                                                       # up everywhere; re-ranked ring, relayed broadcast hops
     ([1, 1, 1, 1], [0b0011, 0b0100, 0, 0]),                           # the global ring is re-ranked (0 2 1 3)
     ([2, 3, 5, 7, 11, 13], [0b000111, 0b111000, 0b010101, 0, 0b000001, 0, 0]),  # three levels, relays, unequal rails
+    ([1] * 8, [0b11111100, 0b00000011, 0, 0]),                        # a relay on the way in only, ahead of the relay's
+                                                                      # own turn as a member: its result must survive
+    ([1] * 8, [0b11111100, 0b11110011, 0b11111001, 0b00001100, 0]),   # the first member is linked to one end only, a rank
+                                                                      # left out to both: the second member relays
+    ([50000] * 8, [0b01111111] + [0b00111111] * 5 + [0, 0]),          # shares 48 : 49 : 504, all rings finish together
 ]
 
 

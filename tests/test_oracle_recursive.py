@@ -536,6 +536,82 @@ def test_host_planner_matches_oracle(r2):
     assert n_multi > 100
 
 
+def _masks_for(increments, participants):
+    """A failure pattern (equal NICs, one GPU per server) whose plan has these increments and ring sizes:
+    the servers that leave before level k keep the first sum(increments[:k]) NICs."""
+    C = sum(increments)
+    masks = []
+    for k in range(1, len(increments)):
+        kept = sum(increments[:k])
+        masks += [((1 << C) - 1) & ~((1 << kept) - 1)] * (participants[k - 1] - participants[k])
+    return C, masks + [0] * participants[-1]
+
+
+def test_host_planner_on_the_share_rules_corner_cases(r2):
+    """The plans in which a later balance level wins, and every exact tie between two balance levels that
+    small increments and ring sizes produce (the product compares in doubles, where an exact tie is a
+    matter of rounding unless it is handled): shares as the oracle's."""
+    import itertools
+
+    cases = [((2, 1, 1), (4, 3, 2)), ((1, 1, 6), (8, 7, 2)), ((1, 1, 4, 1), (8, 7, 3, 2)), ((1, 1, 1, 4), (9, 8, 7, 2))]
+    n_ties = 0
+    for parts in itertools.combinations(range(12, 1, -1), 3):
+        for inc in itertools.product(range(1, 9), repeat=3):
+            f = [F(2 * (p - 1), p) for p in parts]
+            t1 = (1 + 1 / f[1]) / (inc[0] / f[0] + (inc[1] + inc[2]) / f[1])
+            t2 = (1 + 1 / f[2]) / sum(i / x for i, x in zip(inc, f))
+            if t1 == t2:
+                cases.append((inc, parts))
+                n_ties += 1
+    assert n_ties > 50
+    for inc, parts in cases:
+        C, masks = _masks_for(inc, parts)
+        want = rec.plan([1000] * C, masks)
+        assert [l.increment for l in want] == [1000 * i for i in inc] and [len(l.members) for l in want] == list(parts)
+        got = r2.r2_recursive_plan([1000] * C, masks, 1)
+        assert [l.ranks() for l in got] == [l.members for l in want]
+        for a, b in zip(got, want):
+            assert a.share == pytest.approx(float(b.share), rel=1e-13), (inc, parts)
+
+
+def _masks_for(increments, participants):
+    """A failure pattern (equal NICs, one GPU per server) whose plan has these increments and ring sizes:
+    the servers that leave before level k keep the first sum(increments[:k]) NICs."""
+    C = sum(increments)
+    masks = []
+    for k in range(1, len(increments)):
+        kept = sum(increments[:k])
+        masks += [((1 << C) - 1) & ~((1 << kept) - 1)] * (participants[k - 1] - participants[k])
+    return C, masks + [0] * participants[-1]
+
+
+def test_host_planner_on_the_share_rules_corner_cases(r2):
+    """The plans in which a later balance level wins, and every exact tie between two balance levels that
+    small increments and ring sizes produce (the product compares in doubles, where an exact tie is a
+    matter of rounding unless it is handled): shares as the oracle's."""
+    import itertools
+
+    cases = [((2, 1, 1), (4, 3, 2)), ((1, 1, 6), (8, 7, 2)), ((1, 1, 4, 1), (8, 7, 3, 2)), ((1, 1, 1, 4), (9, 8, 7, 2))]
+    n_ties = 0
+    for parts in itertools.combinations(range(12, 1, -1), 3):
+        for inc in itertools.product(range(1, 9), repeat=3):
+            f = [F(2 * (p - 1), p) for p in parts]
+            t1 = (1 + 1 / f[1]) / (inc[0] / f[0] + (inc[1] + inc[2]) / f[1])
+            t2 = (1 + 1 / f[2]) / sum(i / x for i, x in zip(inc, f))
+            if t1 == t2:
+                cases.append((inc, parts))
+                n_ties += 1
+    assert n_ties > 50
+    for inc, parts in cases:
+        C, masks = _masks_for(inc, parts)
+        want = rec.plan([1000] * C, masks)
+        assert [l.increment for l in want] == [1000 * i for i in inc] and [len(l.members) for l in want] == list(parts)
+        got = r2.r2_recursive_plan([1000] * C, masks, 1)
+        assert [l.ranks() for l in got] == [l.members for l in want]
+        for a, b in zip(got, want):
+            assert a.share == pytest.approx(float(b.share), rel=1e-13), (inc, parts)
+
+
 def test_segments_follow_the_shares_and_fit_the_rings(r2):
     """Every segment divides into its ring in whole 16-byte vectors, level 0's into the global ring; the
     upper levels get their share rounded down by less than one granule, level 0 the rest; the host
