@@ -8,7 +8,7 @@ shared with the product.
 from __future__ import annotations
 
 from fractions import Fraction
-from typing import List, Sequence, Tuple
+from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -92,23 +92,28 @@ def _add(a: np.ndarray, b: np.ndarray, dtype: int) -> np.ndarray:
 
 def split_sim(bufs: Sequence[np.ndarray], dtype: int, d: int, n_partial: int, slabs_global: int,
               slabs_partial: int, n_channels: int, align: int, weights: Sequence[int],
-              degraded_mask: int) -> Tuple[np.ndarray, List[np.ndarray]]:
+              degraded_mask: int, ring_logs: Optional[dict] = None) -> Tuple[np.ndarray, List[np.ndarray]]:
     """The schedule step by step, in place on ``bufs``.  Returns the two broadcast tables and the
-    final contents of the two broadcast stage parities (C buffers each)."""
+    final contents of the two broadcast stage parities (C buffers each).  ``ring_logs``, if given,
+    receives the table of every transmission of the two rings under "global" and "partial"."""
     R = len(bufs)
     N = bufs[0].size
     ng = N - n_partial
     es = bufs[0].itemsize
     if ng:
         heads = [np.ascontiguousarray(b[:ng]) for b in bufs]
-        o.ring_sim(heads, dtype, slabs_global, n_channels, align, [(0, degraded_mask, weights)], o.PHASE_AR)
+        log, _ = o.ring_sim(heads, dtype, slabs_global, n_channels, align, [(0, degraded_mask, weights)], o.PHASE_AR)
+        if ring_logs is not None:
+            ring_logs["global"] = log
         for b, h in zip(bufs, heads):
             b[:ng] = h
     if not n_partial:
         return np.zeros((2, n_channels + 1), np.uint64), []
     order = [(d + 1 + i) % R for i in range(R - 1)]
     tails = [np.ascontiguousarray(bufs[r][ng:]) for r in order]
-    o.ring_sim(tails, dtype, slabs_partial, n_channels, align, [(0, 0, weights)], o.PHASE_AR)
+    log, _ = o.ring_sim(tails, dtype, slabs_partial, n_channels, align, [(0, 0, weights)], o.PHASE_AR)
+    if ring_logs is not None:
+        ring_logs["partial"] = log
 
     nbytes = n_partial * es
     t_deg = o.partition(weights, degraded_mask, nbytes, align)

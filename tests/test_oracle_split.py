@@ -140,6 +140,27 @@ def test_split_schedule_equals_its_definition_and_sums_everything(oracle, dtype)
         assert np.array_equal(_f64(dtype, b), total)
 
 
+def test_each_ring_is_cut_by_its_own_channel_state_by_hand(oracle):
+    """Sec. 5.2: the global ring runs through the degraded server and is throttled to what that server has
+    left; the partial ring runs among the healthy servers at full width.  Four ranks, fp32, four equal
+    channels, rank 1 lost channels 0 and 1.  Head: 4 ring chunks of 64 bytes, every one of the 6
+    transmissions cut over channels 2 and 3 alone (32 bytes each).  Tail: 3 ring chunks of 128 bytes,
+    every one of the 4 transmissions cut into quarters.  Broadcast hops that touch rank 1 carry the
+    384-byte tail on channels 2 and 3, the others on all four."""
+    rng = np.random.default_rng(12)
+    ng, npart = 4 * 16, 3 * 32
+    xs = _inputs(rng, 4, ng + npart, F32)
+    bufs = [x.copy() for x in xs]
+    logs = {}
+    tables, _ = split.split_sim(bufs, F32, 1, npart, 1, 1, 4, 16, (7, 7, 7, 7), 0b0011, ring_logs=logs)
+    assert logs["global"].tolist() == [[0, 0, 0, 32, 64]] * 6
+    assert logs["partial"].tolist() == [[0, 32, 64, 96, 128]] * 4
+    assert tables.tolist() == [[0, 0, 0, 192, 384], [0, 96, 192, 288, 384]]
+    want = split.split_expected(xs, F32, 1, npart, 1, 1)
+    for r in range(4):
+        assert bufs[r].tobytes() == want[r].tobytes()
+
+
 def test_split_with_nothing_partial_is_the_plain_ring(oracle):
     rng = np.random.default_rng(5)
     xs = _inputs(rng, 4, 4 * 32, F32)
