@@ -50,11 +50,23 @@ def _run_split(r2, oracle, xs, dtype, d, n_partial, Sg, Sp, C, align, weights, m
     torch.cuda.synchronize()
     outs = [b.cpu().numpy().view(x.dtype) for b, x in zip(bufs, xs)]
     o_bufs = [x.copy() for x in xs]
-    tables, stage = split.split_sim(o_bufs, odt, d, n_partial, Sg, Sp, C, align, weights, mask)
+    logs = {}
+    tables, stage = split.split_sim(o_bufs, odt, d, n_partial, Sg, Sp, C, align, weights, mask, ring_logs=logs)
     want = split.split_expected(xs, odt, d, n_partial, Sg, Sp)
     for r in range(R):
         assert outs[r].tobytes() == o_bufs[r].tobytes(), f"rank {r} vs step-by-step oracle"
         assert outs[r].tobytes() == want[r].tobytes(), f"rank {r} vs definition"
+    # each ring's workspace begins with the table of every transmission: the global ring's is cut by the
+    # degraded server's channel state, the partial ring's by the full one
+    up = lambda x: (x + 255) // 256 * 256
+    g_desc = r2.SimDesc(R, Sg, C, align, N - n_partial, gdt, r2.PHASE_AR, 0, schedule)
+    if N - n_partial:
+        got = ws[: logs["global"].size * 8].cpu().numpy().view(np.uint64).reshape(logs["global"].shape)
+        assert got.tolist() == logs["global"].tolist(), "tables of the global ring"
+    if n_partial:
+        at = up(r2.r2_sim_workspace_bytes(g_desc))
+        got = ws[at: at + logs["partial"].size * 8].cpu().numpy().view(np.uint64).reshape(logs["partial"].shape)
+        assert got.tolist() == logs["partial"].tolist(), "tables of the partial ring"
     if n_partial:
         # the broadcast's tables and stage buffers sit at the end of the workspace
         es = xs[0].itemsize
