@@ -596,6 +596,66 @@ def recursive_line(r2, torch, np, wl, out=sys.stderr):
           f"selector (alpha 5 us, 50 MB/s per unit of weight) picks depth {depth}", file=out, flush=True)
 
 
+def warm_reduce_copy_lines(r2, torch, out=sys.stderr):
+    """The product's stand-alone r2_reduce_copy (tables, checks and all; one chunk, eight long slices) run
+    in the ring step's pattern: call i reads the stage call i-1 wrote and a cold local chunk.  To be read
+    beside the bare ring-pattern kernel of stream_mix_lines and the ring step's own launches."""
+    C, align = 8, 256
+    print("stand-alone r2_reduce_copy (bf16) in the ring step's pattern, us per call:", file=out)
+    for mib in (64, 128):
+        nbytes = mib << 20
+        off = r2.r2_partition([50000] * C, 0b100100, nbytes, align)
+        cap = (max(off[c + 1] - off[c] for c in range(C)) + 255) // 256 * 256
+        d_off = torch.tensor(off, dtype=torch.int64, device="cuda")
+
+        def filled(n):
+            t = torch.empty(n, dtype=torch.uint8, device="cuda")
+            t.view(torch.bfloat16).normal_(0.0, 0.02)
+            return t
+
+        n_loc = 3072 // mib
+        locs = [filled(nbytes) for _ in range(n_loc)]
+        st = [[filled(cap) for _ in range(C)] for _ in range(2)]
+        cells = []
+        for name, op, has_in, has_out in (("sum", r2.OP_SUM, True, True), ("copy, staged", r2.OP_COPY, True, True),
+                                          ("last copy", r2.OP_COPY, True, False), ("send", r2.OP_SUM, False, True)):
+            calls = [r2.ReduceCopyCall(locs[i % n_loc], r2.BF16, op, st[(i + 1) & 1] if has_in else None,
+                                       d_off if has_in else None, st[i & 1] if has_out else None,
+                                       d_off if has_out else None, C, cap, nbytes=nbytes) for i in range(2 * n_loc)]
+            for i in range(6):
+                calls[i % len(calls)].run()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(60):
+                calls[i % len(calls)].run()
+            e1.record()
+            torch.cuda.synchronize()
+            cells.append(f"{name} {e0.elapsed_time(e1) / 60 * 1e3:6.1f}")
+            del calls
+        print(f"  {mib:4d} MiB per stream, channels 2 and 5 down: " + " | ".join(cells), file=out, flush=True)
+        del locs, st
+        torch.cuda.empty_cache()
+
+
+def data_values_lines(r2, torch, np, wl, out=sys.stderr):
+    """The same cfg2 run on buffers of other contents: this GPU's cache hierarchy moves all-zero lines
+    faster than any other data, so a figure measured on zero-filled buffers is not a figure."""
+    w = _workload("cfg2")
+    print("cfg2 whole run by what the rank buffers hold (same kernels, same bytes), ms per all-reduce:", file=out)
+    for name in ("N(0, 0.02) (the workload)", "all zero", "all 1.0"):
+        if name.startswith("N("):
+            xs = wl.make_inputs(w)
+        else:
+            one = np.uint16(0x3F80) if name == "all 1.0" else np.uint16(0)
+            xs = [np.full(w.N, one, dtype=np.uint16) for _ in range(w.R)]
+        run = Runner(r2, torch, np, w, xs)
+        ms = run.time_steps(20, 3) / 20 * 1e3
+        print(f"  {name:26s} {ms:7.4f} ms  {w.algorithmic_bytes / ms / 1e6 / HBM_PEAK_GBPS:.3f} of the HBM peak", file=out, flush=True)
+        del run, xs
+        torch.cuda.empty_cache()
+
+
 def stream_mix_lines(torch, out=sys.stderr):
     """What this GPU's memory system gives bare kernels with the step kernel's access shape and none of its
     tables or slices (csrc/stream_probe.hip, a library of its own): cold mixes of one or two read and write
@@ -679,7 +739,8 @@ def main() -> int:
                     help="also print size sweeps to stderr: r2_reduce_copy, and the whole all-reduce without and with failures")
     ap.add_argument("--stream-mix", action="store_true",
                     help="also print to stderr what bare kernels with the step kernel's access shape reach on this GPU "
-                         "(cold mixes of read and write streams; the ring step's warm pattern)")
+                         "(cold mixes of read and write streams; the ring step's warm pattern), the stand-alone "
+                         "r2_reduce_copy in that pattern, and cfg2 on buffers of other contents (zeros move faster)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -863,6 +924,8 @@ def main() -> int:
         rails_lines(r2, torch, np, wl)
     if args.stream_mix:
         stream_mix_lines(torch)
+        warm_reduce_copy_lines(r2, torch)
+        data_values_lines(r2, torch, np, wl)
     if args.sweep:
         reduce_copy_sweep(r2, torch)
         allreduce_size_sweep(r2, torch, np, wl)
