@@ -108,8 +108,21 @@ def test_pass_planning(r2):
     assert r2.r2_sim_num_passes(r2.SimDesc(8, 32, 8, 256, 1 << 25, r2.BF16, r2.PHASE_AR)) == 1
     assert r2.r2_sim_num_passes(r2.SimDesc(8, 32, 8, 256, 1 << 25, r2.BF16, r2.PHASE_AR, 2 * mib)) == 32
     assert r2.r2_sim_num_passes(r2.SimDesc(8, 32, 8, 256, 1 << 25, r2.BF16, r2.PHASE_AR, 5 * mib)) == 16
+    # five slabs of 2 MiB under a 4 MiB window: two per pass, the last pass holds one
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 5, 8, 256, 5 * (1 << 20), r2.BF16, r2.PHASE_AR, 4 * mib)) == 3
+    # 128 MiB per step under a 48 MiB window: three byte ranges (two would stage 64 MiB each)
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 1, 8, 256, 1 << 26, r2.BF16, r2.PHASE_AR, 48 * mib)) == 3
+    # two slabs of 128 MiB per step under a 64 MiB window: two byte ranges of each slab
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 2, 8, 256, 1 << 27, r2.BF16, r2.PHASE_AR, 64 * mib)) == 4
+    # the two-step exchanges use one stage parity, so their default window is twice as wide: 8 ranks x 32 MiB
+    # messages are one pass, 8 x 64 MiB two
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 1, 8, 256, 1 << 24, r2.BF16, r2.PHASE_SENDRECV)) == 1
+    assert r2.r2_sim_num_passes(r2.SimDesc(8, 1, 8, 256, 1 << 25, r2.BF16, r2.PHASE_SENDRECV)) == 2
     # empty input: one empty pass
     assert r2.r2_sim_num_passes(r2.SimDesc(4, 1, 4, 256, 0, r2.F32, r2.PHASE_AR)) == 1
+    # per-link tables: a block of rows per ring link, 4 links x 6 transmissions x 5 entries of 8 bytes
+    assert r2.r2_sim_stage_offset(r2.SimDesc(4, 1, 4, 256, 4 * 64, r2.F32, r2.PHASE_AR)) == 256
+    assert r2.r2_sim_stage_offset(r2.SimDesc(4, 1, 4, 256, 4 * 64, r2.F32, r2.PHASE_AR | r2.PHASE_LINKS)) == 1024
 
 
 @pytest.mark.parametrize("bad", [
