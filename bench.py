@@ -30,11 +30,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure (8 TB/s)
 # (the JSON line says so in roofline.traffic_source).  The counters sit between L2 and the fabric and
 # cannot tell HBM from the Infinity Cache.
 MEASURED_TRAFFIC = {
-    ("cfg2", "sum"): (int((131113.1 * (131072.0 / 65551.1) + 262155.8 * (131072.0 / 131072.0)) * 1024),
+    ("cfg2", "sum"): (int((131113.5 * (131072.0 / 65551.0) + 262152.2 * (131072.0 / 131072.0)) * 1024),
                       "profiles/ring_step_sum_bf16_cfg2_pmc.md"),
-    ("cfg3", "sum"): (int((131114.5 * (262144.0 / 131087.7) + 262161.1 * (262144.0 / 262144.0)) * 1024),
+    ("cfg3", "sum"): (int((131114.5 * (262144.0 / 131087.6) + 262160.0 * (262144.0 / 262144.0)) * 1024),
                       "profiles/ring_step_sum_f32_cfg3_pmc.md"),
-    ("cfg4", "sum"): (int((65611.5 * (65536.0 / 32782.1) + 131074.5 * (65536.0 / 65536.0)) * 1024),
+    ("cfg4", "sum"): (int((65611.5 * (65536.0 / 32781.3) + 131074.2 * (65536.0 / 65536.0)) * 1024),
                       "profiles/ring_step_sum_bf16_cfg4_pmc.md"),
 }
 

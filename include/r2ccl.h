@@ -245,7 +245,11 @@ uint64_t r2_sim_num_transmissions(const r2_sim_desc *desc); /* rows of the table
                                                                R2_PHASE_LINKS (one block per link)    */
 uint64_t r2_sim_workspace_bytes(const r2_sim_desc *desc);
 uint64_t r2_sim_stage_offset(const r2_sim_desc *desc);      /* byte offset of the stage area      */
-uint64_t r2_sim_stage_capacity(const r2_sim_desc *desc);    /* bytes per channel buffer           */
+uint64_t r2_sim_stage_capacity(const r2_sim_desc *desc);    /* bytes per channel buffer: the ring
+                                                               chunk rounded up to 256, plus, for
+                                                               chunks of 1 MiB and more, 128 KiB + 256
+                                                               that keep the buffers off power-of-two
+                                                               distances (never written)             */
 
 /* Workspace (device, 256-byte aligned, >= r2_sim_workspace_bytes) layout:
  *   [0, ...)                 offsets tables  uint64 [r2_sim_num_transmissions][C+1], row t = transmission t

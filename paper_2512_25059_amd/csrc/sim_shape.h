@@ -17,6 +17,16 @@ uint64_t elem_bytes(int d) { return d == R2_F32 ? 4 : 2; }
 // inside the 256 MiB Infinity Cache lets the read be served from it.
 constexpr uint64_t kDefaultStageWindow = 128ull << 20;
 
+// Channel buffers of ring chunks of 1 MiB and more are this much longer than the chunk.  Without it the
+// buffers of all ranks and channels sit at power-of-two distances from each other and from the rank
+// buffers, and with equal channels so do the slices inside them: every stream of a workgroup then maps
+// to the same places in the caches and the memory channels.  Measured (128 KiB + 256 B against none):
+// the all-reduce with no channel down 1010 -> 992 us at 128 MiB per rank, 4 ranks x 4 MiB fused
+// 12.2 -> 10.7 us, 8 ranks x 8 MiB fused with three channels down 54 -> 45 us; pads of 1.25 KiB to 1 MiB
+// were tried, several of which help one channel state and cost another a per cent.
+constexpr uint64_t kStagePadBytes = (128ull << 10) + 256;
+constexpr uint64_t kStagePadFromChunkBytes = 1ull << 20;
+
 // R2_SCHED_AUTO picks the fused-column schedule when one ring step moves at most this many bytes
 // per stream (summed over ranks and slabs): below it a launch per step is launch-bound.
 constexpr uint64_t kFusedAutoBytes = 8ull << 20;
@@ -85,7 +95,7 @@ int shape_of(const r2_sim_desc *d, SimShape &s)
     s.J = s.two_lists() ? 2 : ring_phases == (R2_PHASE_RS | R2_PHASE_AG) ? 2 * s.R - 1 : s.R;
     s.T_slab = s.J - 1;
     s.chunk_bytes = d->n_elems / per * elem_bytes(d->dtype);
-    s.cap = round_up(s.chunk_bytes ? s.chunk_bytes : 1, 256);
+    s.cap = round_up(s.chunk_bytes ? s.chunk_bytes : 1, 256) + (s.chunk_bytes >= kStagePadFromChunkBytes ? kStagePadBytes : 0);
     s.tx_per_link = (uint64_t)s.S * s.T_slab;
     s.n_tx = s.links ? s.R * s.tx_per_link : s.tx_per_link;  // rows of the tables
     s.tables_bytes = round_up(s.n_tx * (s.C + 1) * 8, 256);

@@ -88,3 +88,15 @@ def windows_around(points, total: int, radius: int, unit: int = 1):
         else:
             merged.append((a, b))
     return merged
+
+
+def assert_same_stage(got: np.ndarray, want: np.ndarray, what: str = "stage area") -> None:
+    """Stage areas [..., capacity] of the product and of an oracle that sizes its channel buffers to the
+    rounded chunk: the product's buffers may be longer (r2_sim_stage_capacity: chunks of 1 MiB and more
+    get a pad); what both have must be the same bytes, and the rest must never have been written."""
+    got = got.reshape(want.shape[:-1] + (-1,))
+    cap = want.shape[-1]
+    assert got.shape[-1] >= cap
+    assert got[..., :cap].tobytes() == want.tobytes(), what
+    assert np.all(got[..., cap:] == FILL), what + ": bytes behind the chunk's capacity were written"
+

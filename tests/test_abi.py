@@ -85,13 +85,16 @@ def test_sim_shape_arithmetic(r2):
     assert r2.r2_sim_num_steps(d) == 15
     assert r2.r2_sim_num_transmissions(d) == 14
     cap = r2.r2_sim_stage_capacity(d)
-    assert cap == 16 << 20
+    pad = (128 << 10) + 256  # channel buffers of chunks of 1 MiB and more are kept off power-of-two distances
+    assert cap == (16 << 20) + pad
     off = r2.r2_sim_stage_offset(d)
     assert off % 256 == 0 and off >= 14 * 9 * 8
     assert r2.r2_sim_workspace_bytes(d) == off + 2 * 8 * 1 * 8 * cap
     rs = r2.SimDesc(16, 4, 8, 256, 1 << 26, r2.F32, r2.PHASE_RS)
     assert r2.r2_sim_num_steps(rs) == 16 and r2.r2_sim_num_transmissions(rs) == 60
-    assert r2.r2_sim_stage_capacity(rs) == 4 << 20
+    assert r2.r2_sim_stage_capacity(rs) == (4 << 20) + pad
+    assert r2.r2_sim_stage_capacity(r2.SimDesc(4, 1, 4, 256, 1 << 20, r2.F32, r2.PHASE_AR)) == (1 << 20) + pad
+    assert r2.r2_sim_stage_capacity(r2.SimDesc(8, 1, 8, 256, 1 << 21, r2.BF16, r2.PHASE_AR)) == 512 << 10  # below 1 MiB: none
 
 
 def test_pass_planning(r2):

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import FILL, say
+from gpu_util import FILL, assert_same_stage, say
 from oracle import rails
 
 pytestmark = pytest.mark.gpu
@@ -76,7 +76,7 @@ def _run(r2, oracle, xs, dtype, phases, S, C, align, weights, masks, window=0, c
             cap = r2.r2_sim_stage_capacity(desc)
             off = r2.r2_sim_stage_offset(desc)
             st = ws[off:off + 2 * R * S * C * cap].cpu().numpy()
-            assert st.tobytes() == stage.tobytes(), "stage area"
+            assert_same_stage(st, stage)
         ran.append(resolved)
     return ran
 
